@@ -1,0 +1,174 @@
+"""numpy front end of the CPU oracle in ``fq_oracle.c``.
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, by the smoke check and by the benchmark's
+``cpu_baseline`` leg.  Nothing in the product package imports this module, and this module
+imports nothing from the product package.  All arithmetic lives in the C file; this file only
+marshals numpy arrays into it.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "fq_oracle.c")
+_LIB = os.path.join(_HERE, "libfq_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile ``fq_oracle.c`` with gcc (no fast-math) and return the library path."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        subprocess.check_call(
+            ["gcc", "-O2", "-fopenmp", "-Wall", "-Wextra", "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"]
+        )
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    u8p = ctypes.POINTER(ctypes.c_uint8)
+    i8p = ctypes.POINTER(ctypes.c_int8)
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    f32p = ctypes.POINTER(ctypes.c_float)
+    f64p = ctypes.POINTER(ctypes.c_double)
+    lib.fqo_e4m3_decode.restype = ctypes.c_double
+    lib.fqo_e4m3_decode.argtypes = [ctypes.c_uint8]
+    lib.fqo_e4m3_encode_rne.restype = ctypes.c_uint8
+    lib.fqo_e4m3_encode_rne.argtypes = [ctypes.c_double]
+    lib.fqo_int4_decode.restype = ctypes.c_int
+    lib.fqo_int4_decode.argtypes = [ctypes.c_uint8]
+    lib.fqo_bf16_decode.restype = ctypes.c_double
+    lib.fqo_bf16_decode.argtypes = [ctypes.c_uint16]
+    lib.fqo_bf16_encode_rne.restype = ctypes.c_uint16
+    lib.fqo_bf16_encode_rne.argtypes = [ctypes.c_double]
+    lib.fqo_bf16_ulp.restype = ctypes.c_double
+    lib.fqo_bf16_ulp.argtypes = [ctypes.c_double]
+    lib.fqo_bf16_encode_rne_array.restype = None
+    lib.fqo_bf16_encode_rne_array.argtypes = [f64p, u16p, ctypes.c_size_t]
+    lib.fqo_bf16_ulp_array.restype = None
+    lib.fqo_bf16_ulp_array.argtypes = [f64p, f64p, ctypes.c_size_t]
+    lib.fqo_w4a8_gemm.restype = ctypes.c_int
+    lib.fqo_w4a8_gemm.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
+                                  ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.fqo_quantize_act.restype = ctypes.c_int
+    lib.fqo_quantize_act.argtypes = [u16p, u8p, f32p, ctypes.c_int, ctypes.c_int]
+    lib.fqo_num_threads.restype = ctypes.c_int
+    lib.fqo_num_threads.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _ptr(a: np.ndarray, ctype):
+    return a.ctypes.data_as(ctypes.POINTER(ctype))
+
+
+def _c(a, dtype) -> np.ndarray:
+    a = np.ascontiguousarray(a)
+    if a.dtype != np.dtype(dtype):
+        raise TypeError("expected %s, got %s" % (np.dtype(dtype), a.dtype))
+    return a
+
+
+# ---- scalar format helpers -----------------------------------------------------------------
+
+def e4m3_decode(code: int) -> float:
+    return float(_load().fqo_e4m3_decode(int(code) & 0xFF))
+
+
+def e4m3_encode_rne(x: float) -> int:
+    return int(_load().fqo_e4m3_encode_rne(float(x)))
+
+
+def int4_decode(nibble: int) -> int:
+    return int(_load().fqo_int4_decode(int(nibble) & 0xFF))
+
+
+def bf16_decode(bits: int) -> float:
+    return float(_load().fqo_bf16_decode(int(bits) & 0xFFFF))
+
+
+def bf16_encode_rne(x: float) -> int:
+    return int(_load().fqo_bf16_encode_rne(float(x)))
+
+
+def bf16_ulp(x: float) -> float:
+    return float(_load().fqo_bf16_ulp(float(x)))
+
+
+def num_threads() -> int:
+    return int(_load().fqo_num_threads())
+
+
+# ---- array entry points --------------------------------------------------------------------
+
+def w4a8_gemm(A, a_scale, q, gscale, w_tscale, want_bound: bool = False):
+    """FP64 ``Y[M,N]`` (and optionally the absolute-value bound) of the W4A8-FP GEMM.
+
+    A: uint8 [M,K] E4M3 codes; a_scale: float32 [M]; q: int8 [N,K] in -8..7;
+    gscale: uint8 [N,K/128] E4M3 codes; w_tscale: float.
+    """
+    A = _c(A, np.uint8)
+    a_scale = _c(a_scale, np.float32)
+    q = _c(q, np.int8)
+    gscale = _c(gscale, np.uint8)
+    M, K = A.shape
+    N = q.shape[0]
+    if q.shape != (N, K) or a_scale.shape != (M,) or gscale.shape != (N, K // 128):
+        raise ValueError("operand shapes do not match")
+    Y = np.zeros((M, N), dtype=np.float64)
+    B = np.zeros((M, N), dtype=np.float64) if want_bound else None
+    rc = _load().fqo_w4a8_gemm(
+        _ptr(A, ctypes.c_uint8), _ptr(a_scale, ctypes.c_float), _ptr(q, ctypes.c_int8),
+        _ptr(gscale, ctypes.c_uint8), ctypes.c_float(float(np.float32(w_tscale))),
+        _ptr(Y, ctypes.c_double),
+        _ptr(B, ctypes.c_double) if want_bound else ctypes.POINTER(ctypes.c_double)(),
+        M, N, K)
+    if rc != 0:
+        raise ValueError("fqo_w4a8_gemm failed with %d" % rc)
+    return (Y, B) if want_bound else Y
+
+
+def quantize_act(X_bf16_bits):
+    """uint16 [M,K] bf16 bit patterns -> (uint8 [M,K] E4M3 codes, float32 [M] scales)."""
+    X = _c(X_bf16_bits, np.uint16)
+    M, K = X.shape
+    A = np.zeros((M, K), dtype=np.uint8)
+    s = np.zeros((M,), dtype=np.float32)
+    rc = _load().fqo_quantize_act(_ptr(X, ctypes.c_uint16), _ptr(A, ctypes.c_uint8),
+                                  _ptr(s, ctypes.c_float), M, K)
+    if rc != 0:
+        raise ValueError("fqo_quantize_act failed with %d" % rc)
+    return A, s
+
+
+def bf16_round_array(Y: np.ndarray) -> np.ndarray:
+    """Elementwise nearest-even bf16 bit patterns (uint16) of an FP64 array."""
+    flat = np.ascontiguousarray(Y, dtype=np.float64).ravel()
+    out = np.empty(flat.shape, dtype=np.uint16)
+    _load().fqo_bf16_encode_rne_array(_ptr(flat, ctypes.c_double), _ptr(out, ctypes.c_uint16), flat.size)
+    return out.reshape(np.shape(Y))
+
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact FP64 value of bf16 bit patterns (a pure re-labelling of bits)."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << 16
+    return b.view(np.float32).astype(np.float64)
+
+
+def bf16_ulp_array(Y: np.ndarray) -> np.ndarray:
+    """Elementwise size of one bf16 unit in the last place at each value's magnitude."""
+    flat = np.ascontiguousarray(Y, dtype=np.float64).ravel()
+    out = np.empty(flat.shape, dtype=np.float64)
+    _load().fqo_bf16_ulp_array(_ptr(flat, ctypes.c_double), _ptr(out, ctypes.c_double), flat.size)
+    return out.reshape(np.shape(Y))

@@ -1,0 +1,277 @@
+/*
+ * CPU oracle for the W4A8-FP linear layer of FireQ (arXiv 2505.20839).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file defines what the GPU library must compute and is
+ * used by the tests, the smoke check and the benchmark's cpu_baseline leg.  It shares no
+ * code, header, table or constant generator with the HIP path and must never be called
+ * from the product path.
+ *
+ * Everything is written out the slow, direct way, in FP64, with no blocking, fusion or
+ * reordering beyond what the definitions below state:
+ *
+ *   operand formats          Sec. 2.1 (eq. 1, eq. 2) and Sec. 3.1:
+ *                            INT4 weights, groups of 128 along K, one E4M3 scale per group;
+ *                            E4M3 activations with one scale per token (row).
+ *   linear layer             Sec. 2.2 eq. 3:  Y = X W^T.
+ *   per-tensor scale         Sec. 3.1.2, Def. 3.2: weights were scaled by delta = 2^n before
+ *                            quantisation, the GEMM output is multiplied by delta^-1
+ *                            (here: w_tscale).
+ *   FP8 constants            App. B (Lemma B.1: smallest subnormal 2^-9) and App. C.1
+ *                            (overflow threshold 1.75 * 2^8 = 448): OCP E4M3, bias 7.
+ *   INT4 range               Sec. 3.1.1 step 1: the table of dequantised values runs from
+ *                            -8*sigma to 7*sigma, so codes are the 16 two's-complement
+ *                            values -8..7.
+ *
+ *   Y[m,n] = a_scale[m] * w_tscale * sum_g dec8(gscale[n,g]) * sum_{k in g} dec8(A[m,k]) * q[n,k]
+ *
+ * Readings of points the paper leaves open (scale applied exactly in FP64 instead of a
+ * rounded FP8 look-up table; one round-to-nearest-even to bf16 at the very end; the
+ * activation scale is absmax/448 in FP32; an all-zero row gets scale 1) are stated at the
+ * functions that take them.
+ *
+ * Build:  gcc -O2 -fopenmp -shared -fPIC -o libfq_oracle.so fq_oracle.c -lm
+ */
+#include <math.h>
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define FQO_GROUP 128
+
+/* ---------------------------------------------------------------------------------------
+ * E4M3 (OCP "e4m3fn": 1 sign, 4 exponent, 3 mantissa bits, bias 7, no infinities).
+ * App. B, Lemma B.1 fixes the smallest subnormal at 2^-9; App. C.1 fixes the largest
+ * finite value at 1.75 * 2^8 = 448.  Codes 0x7F and 0xFF are NaN.
+ * ------------------------------------------------------------------------------------- */
+double fqo_e4m3_decode(uint8_t code)
+{
+    int sign = (code >> 7) & 1;
+    int expo = (code >> 3) & 0xF;
+    int mant = code & 0x7;
+    double v;
+    if (expo == 0xF && mant == 0x7)
+        return NAN;
+    if (expo == 0)
+        v = ldexp((double)mant, -9);              /* subnormal: mant/8 * 2^(1-7) */
+    else
+        v = ldexp(1.0 + (double)mant / 8.0, expo - 7);
+    return sign ? -v : v;
+}
+
+/* Round a real number to the nearest E4M3 value, ties to the code with an even mantissa,
+ * saturating at +-448 (never NaN for a finite input; NaN input gives the NaN code).
+ * Done by definition: scan the 127 finite non-negative codes, keep the closest.          */
+uint8_t fqo_e4m3_encode_rne(double x)
+{
+    if (isnan(x))
+        return 0x7F;
+    uint8_t sign = (uint8_t)(signbit(x) ? 0x80 : 0x00);
+    double a = fabs(x);
+    if (a >= 448.0)
+        return (uint8_t)(sign | 0x7E);
+    int best = 0;
+    double best_d = a;                            /* distance to code 0 (value 0) */
+    for (int c = 1; c <= 0x7E; ++c) {
+        double d = fabs(a - fqo_e4m3_decode((uint8_t)c));
+        if (d < best_d || (d == best_d && (c & 1) == 0 && (best & 1) == 1)) {
+            best = c;
+            best_d = d;
+        }
+    }
+    return (uint8_t)(sign | best);
+}
+
+/* INT4: the low four bits of `nibble` read as a two's-complement number, -8..7
+ * (Sec. 2.1 eq. 1 with b = 4; Sec. 3.1.1 step 1 lists -8*sigma .. 7*sigma).              */
+int fqo_int4_decode(uint8_t nibble)
+{
+    int v = nibble & 0xF;
+    return v >= 8 ? v - 16 : v;
+}
+
+/* bfloat16 <-> real.  A bf16 is the top 16 bits of an IEEE binary32.                      */
+double fqo_bf16_decode(uint16_t bits)
+{
+    uint32_t u = (uint32_t)bits << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* Nearest bf16 to a real number, ties to even, overflow to infinity (IEEE behaviour).
+ * Written from the definition: bf16 has 8 significand bits, so for a normal value the
+ * spacing is 2^(e-7) with e = floor(log2|x|); the exponent range is that of binary32.   */
+uint16_t fqo_bf16_encode_rne(double x)
+{
+    if (isnan(x))
+        return 0x7FC0;
+    uint16_t sign = (uint16_t)(signbit(x) ? 0x8000 : 0x0000);
+    double a = fabs(x);
+    if (a == 0.0)
+        return sign;
+    if (isinf(a))
+        return (uint16_t)(sign | 0x7F80);
+    int e;
+    (void)frexp(a, &e);                           /* a = f * 2^e, f in [0.5,1)  */
+    e -= 1;                                       /* a in [2^e, 2^(e+1))        */
+    if (e < -126)
+        e = -126;                                 /* subnormal spacing          */
+    double ulp = ldexp(1.0, e - 7);
+    double n = nearbyint(a / ulp);                /* default mode: ties to even; a/ulp is exact */
+    double r = n * ulp;
+    if (r >= ldexp(1.0, 128))
+        return (uint16_t)(sign | 0x7F80);
+    float f = (float)r;                           /* exact: r has <= 8 significant bits */
+    uint32_t u;
+    memcpy(&u, &f, sizeof u);
+    return (uint16_t)(sign | (uint16_t)(u >> 16));
+}
+
+/* Size of one bf16 unit in the last place at the magnitude of x (for tolerances).        */
+double fqo_bf16_ulp(double x)
+{
+    double a = fabs(x);
+    int e;
+    if (a == 0.0 || isnan(a) || isinf(a))
+        return ldexp(1.0, -126 - 7);
+    (void)frexp(a, &e);
+    e -= 1;
+    if (e < -126)
+        e = -126;
+    return ldexp(1.0, e - 7);
+}
+
+/* Array forms of the two bf16 helpers above (elementwise, nothing else).                  */
+void fqo_bf16_encode_rne_array(const double *x, uint16_t *out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        out[i] = fqo_bf16_encode_rne(x[i]);
+}
+
+void fqo_bf16_ulp_array(const double *x, double *out, size_t n)
+{
+    for (size_t i = 0; i < n; ++i)
+        out[i] = fqo_bf16_ulp(x[i]);
+}
+
+/* ---------------------------------------------------------------------------------------
+ * The W4A8-FP GEMM (Sec. 2.2 eq. 3 with the operands of Sec. 2.1 / 3.1 and the output
+ * scaling of Def. 3.2):
+ *
+ *   A       [M,K]      E4M3 codes, row-major
+ *   a_scale [M]        per-token scale (the paper's beta), FP32
+ *   q       [N,K]      INT4 codes, one int8 per code holding -8..7, row-major
+ *   gscale  [N,K/128]  E4M3 codes, one per (output channel, group of 128 along K)
+ *   w_tscale           per-tensor factor delta^-1
+ *   Y       [M,N]      FP64 result, not rounded
+ *   bound   [M,N]      optional (may be NULL): the same sum with every factor replaced by
+ *                      its absolute value -- the forward-error scale used by the
+ *                      per-element tolerance.
+ *
+ * Reading: the group scale multiplies the exact group sum (the paper's kernel instead
+ * rounds q*sigma to FP8 in a 16-entry table before the multiply; the benchmark spec asks
+ * for the exact formula).  Order: inner sum over the 128 k of a group, times the group
+ * scale, summed over groups, times the two outer scales.  Returns 0, -1 on a bad shape,
+ * -2 when the temporary FP64 copies of A and gscale cannot be allocated.
+ * ------------------------------------------------------------------------------------- */
+int fqo_w4a8_gemm(const uint8_t *A, const float *a_scale, const int8_t *q,
+                  const uint8_t *gscale, float w_tscale,
+                  double *Y, double *bound, int M, int N, int K)
+{
+    if (M < 0 || N < 0 || K < 0 || (K % FQO_GROUP) != 0)
+        return -1;
+    if (M == 0 || N == 0)
+        return 0;
+    const int G = K / FQO_GROUP;
+
+    /* Decode the operands once into FP64 (pure look-ups, no arithmetic on them yet). */
+    double *Ad = (double *)malloc((size_t)M * K * sizeof(double));
+    double *Sd = (double *)malloc((size_t)N * (G > 0 ? G : 1) * sizeof(double));
+    if (!Ad || !Sd) {
+        free(Ad);
+        free(Sd);
+        return -2;
+    }
+    for (size_t i = 0; i < (size_t)M * K; ++i)
+        Ad[i] = fqo_e4m3_decode(A[i]);
+    for (size_t i = 0; i < (size_t)N * G; ++i)
+        Sd[i] = fqo_e4m3_decode(gscale[i]);
+
+    long m;
+#pragma omp parallel for schedule(static)
+    for (m = 0; m < M; ++m) {
+        const double outer = (double)a_scale[m] * (double)w_tscale;
+        for (int n = 0; n < N; ++n) {
+            double y = 0.0, b = 0.0;
+            for (int g = 0; g < G; ++g) {
+                const double *a = Ad + (size_t)m * K + (size_t)g * FQO_GROUP;
+                const int8_t *w = q + (size_t)n * K + (size_t)g * FQO_GROUP;
+                double p = 0.0;
+                for (int k = 0; k < FQO_GROUP; ++k)
+                    p += a[k] * (double)w[k];
+                y += Sd[(size_t)n * G + g] * p;
+                if (bound) {
+                    double pa = 0.0;
+                    for (int k = 0; k < FQO_GROUP; ++k)
+                        pa += fabs(a[k]) * fabs((double)w[k]);
+                    b += fabs(Sd[(size_t)n * G + g]) * pa;
+                }
+            }
+            Y[(size_t)m * N + n] = outer * y;
+            if (bound)
+                bound[(size_t)m * N + n] = fabs(outer) * b;
+        }
+    }
+    free(Ad);
+    free(Sd);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------
+ * Activation quantisation (Sec. 2.1 eq. 2):  A = FP8(x / beta), one beta per token.
+ *
+ *   X [M,K] bf16 bit patterns -> A [M,K] E4M3 codes, a_scale [M] FP32.
+ *
+ * Readings (the paper gives no formula for beta and no rounding mode):
+ *   beta = absmax(row) / 448 rounded to FP32 (448 = the E4M3 maximum of App. C.1);
+ *   an all-zero row takes beta = 1;  the quotient x/beta is rounded to FP32 (IEEE
+ *   division) and then to E4M3, nearest-even, saturating.  Inputs are finite.
+ * ------------------------------------------------------------------------------------- */
+int fqo_quantize_act(const uint16_t *X, uint8_t *A, float *a_scale, int M, int K)
+{
+    if (M < 0 || K < 0)
+        return -1;
+    long m;
+#pragma omp parallel for schedule(static)
+    for (m = 0; m < M; ++m) {
+        double amax = 0.0;
+        for (int k = 0; k < K; ++k) {
+            double v = fabs(fqo_bf16_decode(X[(size_t)m * K + k]));
+            if (v > amax)
+                amax = v;
+        }
+        float s = (amax == 0.0) ? 1.0f : (float)(amax / 448.0);
+        a_scale[m] = s;
+        for (int k = 0; k < K; ++k) {
+            double x = fqo_bf16_decode(X[(size_t)m * K + k]);
+            float quot = (float)(x / (double)s);   /* = IEEE binary32 division of two floats */
+            A[(size_t)m * K + k] = fqo_e4m3_encode_rne((double)quot);
+        }
+    }
+    return 0;
+}
+
+/* Threads the parallel loops above will use (1 when built without OpenMP).               */
+int fqo_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
