@@ -1,0 +1,96 @@
+/*
+ * fireq.h -- C ABI of the W4A8-FP linear-layer library for AMD MI355X (gfx950).
+ *
+ * The library implements the INT4-weight x FP8-activation GEMM that runs every linear layer
+ * of FireQ (arXiv 2505.20839, Sec. 3.1.1), the activation quantiser that feeds it
+ * (Sec. 2.1 eq. 2) and the offline weight packing it reads.
+ *
+ * Conventions for every entry point
+ *   - All pointers are DEVICE pointers into memory owned by the caller.  The library
+ *     allocates nothing, keeps no state between calls and never synchronises: work is
+ *     enqueued on `stream` (a hipStream_t passed as void*; NULL is the default stream) and
+ *     the call returns at once.
+ *   - Inputs are never written.  After a non-zero status the outputs are undefined.
+ *   - No exception crosses this boundary; every function that can fail returns a status.
+ *   - M = 0 (or N = 0 where it is an output width) is a successful no-op.
+ *   - Base pointers must be 16-byte aligned (FQ_ERR_ALIGN otherwise), except a_scale and
+ *     the int8 code array, which need only their natural alignment.
+ *   - K must be a positive multiple of 128, the quantisation group (Sec. 3.1).
+ */
+#ifndef FIREQ_H
+#define FIREQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    FQ_OK         = 0,
+    FQ_ERR_NULL   = -1,  /* a required pointer is NULL                                        */
+    FQ_ERR_SHAPE  = -2,  /* negative size, K == 0, K % 128 != 0, N == 0 with M > 0            */
+    FQ_ERR_ALIGN  = -3,  /* a base pointer is not 16-byte aligned                             */
+    FQ_ERR_LAUNCH = -4   /* the HIP runtime reported an error when the kernel was launched    */
+};
+
+#define FQ_GROUP 128     /* weights along K share one E4M3 scale per 128 (Sec. 3.1)           */
+
+/*
+ * Y = X W^T (Sec. 2.2 eq. 3) on quantised operands (Sec. 2.1, Sec. 3.1), with the per-tensor
+ * factor of Def. 3.2 and the per-token factor of eq. 2 applied to the output:
+ *
+ *   Y[m,n] = bf16( a_scale[m] * w_tscale *
+ *                  sum_g e4m3(w_gscale[n,g]) * sum_{k in group g} e4m3(A_fp8[m,k]) * q[n,k] )
+ *
+ * The group sums are accumulated in FP32 from exact FP8 x FP8 products, each group sum is
+ * multiplied by its scale in FP32, and the result is rounded to bf16 once, to nearest even.
+ *
+ *   A_fp8      [M,K]  row-major OCP E4M3 codes (bias 7, max 448; NaN codes must not occur)
+ *   a_scale    [M]    FP32 per-token scale (the paper's beta)
+ *   Wq_packed         fq_packed_weight_bytes(N,K) bytes written by fq_pack_weights(N,K)
+ *   w_gscale   [N,K/128] row-major OCP E4M3 codes, any finite value (zero, subnormal, negative)
+ *   w_tscale          FP32 per-tensor factor (delta^-1 of Def. 3.2), by value
+ *   Y_bf16     [M,N]  row-major bfloat16 bit patterns (output)
+ */
+int fq_w4a8_gemm(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
+                 const uint8_t *w_gscale, float w_tscale, uint16_t *Y_bf16,
+                 int M, int N, int K, void *stream);
+
+/*
+ * Per-token FP8 quantisation of activations (Sec. 2.1 eq. 2: A = FP8(x / beta)).
+ *
+ *   beta[m] = max_k |X[m,k]| / 448 in FP32 (1 for an all-zero row);
+ *   A[m,k]  = E4M3 nearest-even of the FP32 quotient X[m,k] / beta[m], saturating at +-448.
+ *
+ *   X_bf16 [M,K] row-major bfloat16 bit patterns, finite;  A_fp8 [M,K];  a_scale [M].
+ *   K here only has to be a positive multiple of 8.
+ */
+int fq_quantize_act(const uint16_t *X_bf16, uint8_t *A_fp8, float *a_scale,
+                    int M, int K, void *stream);
+
+/*
+ * Offline weight packing (Sec. 3.1: INT4 weights in groups of 128).  The paper does not
+ * define a nibble order; the packed order is private to this library, laid out for the
+ * gfx950 FP8 MFMA operand, and versioned by fq_layout_version().
+ *
+ *   q [N,K] row-major, one int8 per INT4 code in -8..7 (only the low four bits are read).
+ *   fq_packed_weight_bytes(N,K) = ceil(N/32)*32 * K/2 (rows are padded to a multiple of 32
+ *   with code 0); returns 0 for an invalid shape.
+ *   fq_unpack_weights is the exact inverse: unpack(pack(q)) == q for every code.
+ */
+size_t fq_packed_weight_bytes(int N, int K);
+int fq_pack_weights(const int8_t *q, uint8_t *Wq_packed, int N, int K, void *stream);
+int fq_unpack_weights(const uint8_t *Wq_packed, int8_t *q, int N, int K, void *stream);
+
+/* Changes whenever the byte order written by fq_pack_weights changes. */
+int fq_layout_version(void);
+
+/* Static, NUL-terminated description of a status code. */
+const char *fq_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FIREQ_H */

@@ -1,0 +1,141 @@
+"""Thin Python binding of the C ABI in ``include/fireq.h``: argument marshalling only.
+
+Every step of the path runs in the HIP kernels of ``libfireq.so``; torch is used for device
+memory and the current stream.  There is no CPU fallback: if the library cannot be loaded or a
+tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+from . import build as _build
+
+GROUP = 128
+
+_lib = None
+
+
+class FireqError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (where, status_string(status), status))
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded shared library (built in-tree on first use if it was never built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build_library()
+    L = ctypes.CDLL(_build.LIB_PATH)
+    vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+    L.fq_w4a8_gemm.restype = ci
+    L.fq_w4a8_gemm.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
+    L.fq_quantize_act.restype = ci
+    L.fq_quantize_act.argtypes = [vp, vp, vp, ci, ci, vp]
+    L.fq_packed_weight_bytes.restype = ctypes.c_size_t
+    L.fq_packed_weight_bytes.argtypes = [ci, ci]
+    L.fq_pack_weights.restype = ci
+    L.fq_pack_weights.argtypes = [vp, vp, ci, ci, vp]
+    L.fq_unpack_weights.restype = ci
+    L.fq_unpack_weights.argtypes = [vp, vp, ci, ci, vp]
+    L.fq_layout_version.restype = ci
+    L.fq_layout_version.argtypes = []
+    L.fq_status_string.restype = ctypes.c_char_p
+    L.fq_status_string.argtypes = [ci]
+    _lib = L
+    return L
+
+
+def status_string(status: int) -> str:
+    return lib().fq_status_string(int(status)).decode()
+
+
+def fq_layout_version() -> int:
+    return int(lib().fq_layout_version())
+
+
+def fq_packed_weight_bytes(N: int, K: int) -> int:
+    return int(lib().fq_packed_weight_bytes(int(N), int(K)))
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError("%s must be a GPU tensor" % name)
+    if t.dtype != dtype:
+        raise TypeError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    return t
+
+
+def _stream() -> ctypes.c_void_p:
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def fq_pack_weights(q: torch.Tensor) -> torch.Tensor:
+    """int8 [N,K] codes in -8..7 -> packed uint8 buffer of fq_packed_weight_bytes(N,K) bytes."""
+    q = _dev(q, torch.int8, "q")
+    N, K = q.shape
+    nbytes = fq_packed_weight_bytes(N, K)
+    if nbytes == 0:
+        raise FireqError(-2, "fq_pack_weights")
+    out = torch.empty(nbytes, dtype=torch.uint8, device=q.device)
+    rc = lib().fq_pack_weights(q.data_ptr(), out.data_ptr(), N, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_pack_weights")
+    return out
+
+
+def fq_unpack_weights(packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
+    packed = _dev(packed, torch.uint8, "packed")
+    if packed.numel() < fq_packed_weight_bytes(N, K) or fq_packed_weight_bytes(N, K) == 0:
+        raise FireqError(-2, "fq_unpack_weights")
+    out = torch.empty((N, K), dtype=torch.int8, device=packed.device)
+    rc = lib().fq_unpack_weights(packed.data_ptr(), out.data_ptr(), N, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_unpack_weights")
+    return out
+
+
+def fq_quantize_act(X: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
+    """bf16 [M,K] -> (uint8 [M,K] E4M3 codes, float32 [M] per-row scales)."""
+    X = _dev(X, torch.bfloat16, "X")
+    M, K = X.shape
+    A = torch.empty((M, K), dtype=torch.uint8, device=X.device)
+    s = torch.empty((M,), dtype=torch.float32, device=X.device)
+    rc = lib().fq_quantize_act(X.data_ptr(), A.data_ptr(), s.data_ptr(), M, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_quantize_act")
+    return A, s
+
+
+def fq_w4a8_gemm(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor,
+                 w_gscale: torch.Tensor, w_tscale: float, N: int,
+                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[M,N] (bf16) = W4A8-FP GEMM of E4M3 activations and packed INT4 weights."""
+    A = _dev(A, torch.uint8, "A")
+    a_scale = _dev(a_scale, torch.float32, "a_scale")
+    Wq_packed = _dev(Wq_packed, torch.uint8, "Wq_packed")
+    w_gscale = _dev(w_gscale, torch.uint8, "w_gscale")
+    M, K = A.shape
+    if a_scale.numel() != M or K % GROUP or w_gscale.numel() != N * (K // GROUP) \
+            or Wq_packed.numel() < fq_packed_weight_bytes(N, K):
+        raise FireqError(-2, "fq_w4a8_gemm")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    else:
+        out = _dev(out, torch.bfloat16, "out")
+        if tuple(out.shape) != (M, N):
+            raise FireqError(-2, "fq_w4a8_gemm")
+    rc = lib().fq_w4a8_gemm(A.data_ptr(), a_scale.data_ptr(), Wq_packed.data_ptr(),
+                            w_gscale.data_ptr(), ctypes.c_float(float(w_tscale)), out.data_ptr(),
+                            M, N, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_w4a8_gemm")
+    return out

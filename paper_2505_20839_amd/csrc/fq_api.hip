@@ -1,0 +1,98 @@
+// C entry points of the W4A8-FP library: argument validation, kernel choice, launch.
+// Declarations and the contract of every call are in include/fireq.h.
+#include "../../include/fireq.h"
+#include "fq_common.h"
+#include "fq_kernels.h"
+
+#include <cstdlib>
+#include <cstring>
+
+namespace {
+
+inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+inline int after_launch() { return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_LAUNCH; }
+
+enum class GemmKernel { Auto, Simple, Large, Small };
+
+// FQ_FORCE_KERNEL=simple|large|small overrides the choice (tests use it to cross-check kernels).
+GemmKernel forced_kernel() {
+    const char* e = std::getenv("FQ_FORCE_KERNEL");
+    if (!e || !*e) return GemmKernel::Auto;
+    if (!std::strcmp(e, "simple")) return GemmKernel::Simple;
+    if (!std::strcmp(e, "large")) return GemmKernel::Large;
+    if (!std::strcmp(e, "small")) return GemmKernel::Small;
+    return GemmKernel::Auto;
+}
+
+}  // namespace
+
+extern "C" {
+
+int fq_layout_version(void) { return FQ_LAYOUT_VERSION; }
+
+const char* fq_status_string(int status) {
+    switch (status) {
+        case FQ_OK: return "ok";
+        case FQ_ERR_NULL: return "a required pointer is NULL";
+        case FQ_ERR_SHAPE: return "invalid shape (sizes must be non-negative, K a positive multiple of 128)";
+        case FQ_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
+        case FQ_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
+        default: return "unknown status";
+    }
+}
+
+size_t fq_packed_weight_bytes(int N, int K) {
+    if (N <= 0 || K <= 0 || (K % FQ_GROUP) != 0) return 0;
+    return (size_t)((N + 31) / 32) * 32u * (size_t)K / 2u;
+}
+
+int fq_pack_weights(const int8_t* q, uint8_t* Wq_packed, int N, int K, void* stream) {
+    if (N < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
+    if (N == 0) return FQ_OK;
+    if (!q || !Wq_packed) return FQ_ERR_NULL;
+    if (!aligned16(Wq_packed)) return FQ_ERR_ALIGN;
+    fq_launch_pack(q, Wq_packed, N, K, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_unpack_weights(const uint8_t* Wq_packed, int8_t* q, int N, int K, void* stream) {
+    if (N < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
+    if (N == 0) return FQ_OK;
+    if (!q || !Wq_packed) return FQ_ERR_NULL;
+    if (!aligned16(Wq_packed)) return FQ_ERR_ALIGN;
+    fq_launch_unpack(Wq_packed, q, N, K, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_quantize_act(const uint16_t* X_bf16, uint8_t* A_fp8, float* a_scale, int M, int K, void* stream) {
+    if (M < 0 || K <= 0 || (K % 8) != 0) return FQ_ERR_SHAPE;
+    if (M == 0) return FQ_OK;
+    if (!X_bf16 || !A_fp8 || !a_scale) return FQ_ERR_NULL;
+    if (!aligned16(X_bf16) || !aligned16(A_fp8)) return FQ_ERR_ALIGN;
+    if (((size_t)K * 2u) % 16u != 0 || ((size_t)K % 8u) != 0) return FQ_ERR_SHAPE;
+    fq_launch_quantize(X_bf16, A_fp8, a_scale, M, K, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                 const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
+                 int M, int N, int K, void* stream) {
+    if (M < 0 || N < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
+    if (M == 0) return FQ_OK;
+    if (N == 0) return FQ_ERR_SHAPE;
+    if (!A_fp8 || !a_scale || !Wq_packed || !w_gscale || !Y_bf16) return FQ_ERR_NULL;
+    if (!aligned16(A_fp8) || !aligned16(Wq_packed) || !aligned16(w_gscale) || !aligned16(Y_bf16))
+        return FQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    GemmKernel k = forced_kernel();
+    if (k == GemmKernel::Auto) k = (M <= 64) ? GemmKernel::Small : GemmKernel::Large;
+    switch (k) {
+        case GemmKernel::Simple: fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
+        case GemmKernel::Small:  fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
+        default:                 fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
+    }
+    return after_launch();
+}
+
+}  // extern "C"

@@ -1,0 +1,91 @@
+// Device-side helpers shared by the kernels of the W4A8-FP library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define FQ_GROUP 128
+#define FQ_LAYOUT_VERSION 1
+
+typedef int   fq_v4i  __attribute__((ext_vector_type(4)));
+typedef int   fq_v8i  __attribute__((ext_vector_type(8)));
+typedef int   fq_v2i  __attribute__((ext_vector_type(2)));
+typedef float fq_v16f __attribute__((ext_vector_type(16)));
+typedef float fq_v4f  __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------------------------------------
+// Packed weight layout (version 1), made for the B operand of v_mfma_f32_32x32x64_f8f6f4.
+//
+// Unit: one "block" per (tile of 32 output channels, group of 128 input channels) = 2048 bytes,
+// blocks ordered [n/32][k/128].  A block is [h = 0,1][lane = 0..63][16 bytes]: `h` is the 64-wide
+// half of the group that one MFMA consumes, `lane` = 32*kh + (n % 32) is the MFMA lane that needs
+// the bytes, so a wave fetches one half with a single coalesced 16-byte load per lane.
+// Inside the 16 bytes, byte 4*i + j holds two 4-bit codes:
+//     low  nibble -> operand register i,     byte j :  k = 128*g + 64*h + 32*kh +      4*i + j
+//     high nibble -> operand register 4 + i, byte j :  k = 128*g + 64*h + 32*kh + 16 + 4*i + j
+// A 4-bit code is sign-magnitude with the sign in bit 0:  code = 2*q      for q in  0..7
+//                                                          code = 2*(-q-1)+1 for q in -8..-1
+// so that  |q| = (code + (code & 1)) >> 1  is one v_lerp_u8 on four codes at a time, and the byte
+// (sign << 7) | |q| is the E4M3 number q * 2^-9 (E4M3 subnormals and the first binade share one
+// spacing, so the sixteen integers -8..7 times 2^-9 are all exact).  Channels past N hold code 0.
+// ---------------------------------------------------------------------------------------------
+__host__ __device__ inline size_t fq_block_offset(int nt, int g, int G) {
+    return ((size_t)nt * (size_t)G + (size_t)g) * 2048u;
+}
+
+__host__ __device__ inline unsigned fq_code_from_q(int q) {       // q in -8..7 (low 4 bits used)
+    q = (q << 28) >> 28;                                            // sign-extend the nibble
+    return q >= 0 ? (unsigned)(2 * q) : (unsigned)(2 * (-q - 1) + 1);
+}
+
+__host__ __device__ inline int fq_q_from_code(unsigned code) {
+    int s = (int)(code & 1u);
+    int mag = (int)((code + (unsigned)s) >> 1) & 0xF;
+    return s ? -mag : mag;
+}
+
+// Byte offset inside the packed buffer and nibble position (0 = low, 1 = high) of weight (n, k).
+__host__ __device__ inline size_t fq_weight_byte(int n, int k, int G, int* hi) {
+    int nt = n >> 5, n32 = n & 31;
+    int g = k >> 7, kk = k & 127;
+    int h = kk >> 6, kh = (kk >> 5) & 1, b = kk & 31;
+    *hi = b >> 4;
+    int ij = b & 15;
+    return fq_block_offset(nt, g, G) + (size_t)h * 1024u + (size_t)(kh * 32 + n32) * 16u + (size_t)ij;
+}
+
+#ifdef __HIPCC__
+// Four packed bytes of 4-bit codes (already masked to 0x0F per byte) -> four E4M3 bytes q*2^-9.
+__device__ __forceinline__ unsigned fq_codes_to_e4m3x4(unsigned x) {
+    unsigned mag = __builtin_amdgcn_lerp(x, 0u, x);                 // per byte (x + (x & 1)) >> 1
+    return ((x & 0x01010101u) << 7) | mag;
+}
+
+// One 16-byte packed chunk -> the 8 operand registers of one MFMA half.
+__device__ __forceinline__ fq_v8i fq_unpack_chunk(fq_v4i w) {
+    fq_v8i r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        unsigned u = (unsigned)w[i];
+        r[i]     = (int)fq_codes_to_e4m3x4(u & 0x0F0F0F0Fu);
+        r[4 + i] = (int)fq_codes_to_e4m3x4((u >> 4) & 0x0F0F0F0Fu);
+    }
+    return r;
+}
+
+// OCP E4M3 byte -> float (exact), done with integer operations (no table, handles subnormals).
+__device__ __forceinline__ float fq_e4m3_to_float(unsigned b) {
+    unsigned sign = (b & 0x80u) << 24;
+    unsigned em = b & 0x7Fu;
+    float mag;
+    if (em < 8u) mag = (float)em * 0.001953125f;                    // subnormal: m * 2^-9
+    else         mag = __uint_as_float((em << 20) + 0x3C000000u);   // (e + 120) << 23 | m << 20
+    return __uint_as_float(__float_as_uint(mag) | sign);
+}
+
+// float -> bf16 bits, round to nearest even (finite or infinite input; NaN not expected).
+__device__ __forceinline__ unsigned fq_float_to_bf16(float f) {
+    unsigned u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+#endif

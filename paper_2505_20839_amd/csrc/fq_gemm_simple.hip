@@ -1,0 +1,37 @@
+// Plain W4A8-FP GEMM: one thread per output element, no matrix cores.  It reads the same packed
+// weights as the tuned kernels and exists for shapes they do not cover and as an in-library
+// cross-check (selected with FQ_FORCE_KERNEL=simple).  Computes, in FP32,
+//   Y[m,n] = bf16( a_scale[m] * w_tscale * sum_g e4m3(gs[n,g]) * sum_{k in g} e4m3(A[m,k]) * q[n,k] )
+// (Sec. 2.2 eq. 3 with the operands of Sec. 3.1 and the output factor of Def. 3.2).
+#include "fq_common.h"
+#include "fq_kernels.h"
+
+__global__ __launch_bounds__(256) void fq_gemm_simple_kernel(const uint8_t* __restrict__ A,
+                                                             const float* __restrict__ a_scale,
+                                                             const uint8_t* __restrict__ wp,
+                                                             const uint8_t* __restrict__ gs, float tscale,
+                                                             uint16_t* __restrict__ Y, int M, int N, int K) {
+    int n = blockIdx.x * 64 + (threadIdx.x & 63);
+    int m = blockIdx.y * 4 + (threadIdx.x >> 6);
+    if (n >= N || m >= M) return;
+    const int G = K / FQ_GROUP;
+    float acc = 0.f;
+    for (int g = 0; g < G; ++g) {
+        float p = 0.f;
+        for (int kk = 0; kk < FQ_GROUP; ++kk) {
+            int k = g * FQ_GROUP + kk, hi;
+            size_t off = fq_weight_byte(n, k, G, &hi);
+            unsigned byte = wp[off];
+            int qv = fq_q_from_code(hi ? (byte >> 4) : (byte & 0xFu));
+            p = fmaf(fq_e4m3_to_float(A[(size_t)m * K + k]), (float)qv, p);
+        }
+        acc = fmaf(fq_e4m3_to_float(gs[(size_t)n * G + g]), p, acc);
+    }
+    Y[(size_t)m * N + n] = (uint16_t)fq_float_to_bf16(a_scale[m] * tscale * acc);
+}
+
+void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
+    dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 3) / 4));
+    hipLaunchKernelGGL(fq_gemm_simple_kernel, grid, dim3(256), 0, stream, A, a_scale, wp, gs, tscale, Y, M, N, K);
+}

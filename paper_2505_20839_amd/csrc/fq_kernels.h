@@ -1,0 +1,18 @@
+// Host-side launchers implemented by the kernel translation units (internal to the library).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+// Each launcher validates nothing: arguments were checked by the C entry point.  They enqueue on
+// `stream` and return; the caller reads hipGetLastError().
+void fq_launch_pack(const int8_t* q, uint8_t* wp, int N, int K, hipStream_t stream);
+void fq_launch_unpack(const uint8_t* wp, int8_t* q, int N, int K, hipStream_t stream);
+void fq_launch_quantize(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, hipStream_t stream);
+
+// GEMM kernels.  `which` selects the kernel: see fq_api.hip.
+void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);
+void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                          float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);
+void fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                          float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);

@@ -1,0 +1,69 @@
+"""CPU-only checks of the C ABI: the library loads, exports every symbol the header declares,
+and rejects bad arguments before touching the GPU (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_20839_amd import binding, build
+
+HEADER = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "fireq.h")
+
+
+def _declared_functions():
+    src = open(HEADER).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(fq_[a-z0-9_]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = _declared_functions()
+    assert names == sorted(["fq_w4a8_gemm", "fq_quantize_act", "fq_packed_weight_bytes", "fq_pack_weights",
+                            "fq_unpack_weights", "fq_layout_version", "fq_status_string"])
+    for name in names:
+        assert hasattr(L, name), name
+    assert os.path.samefile(L._name, build.LIB_PATH)
+
+
+def test_sizes_version_and_status_strings():
+    assert binding.fq_packed_weight_bytes(256, 512) == 256 * 512 // 2
+    assert binding.fq_packed_weight_bytes(33, 128) == 64 * 128 // 2      # rows padded to 32
+    assert binding.fq_packed_weight_bytes(14336, 4096) == 14336 * 4096 // 2
+    assert binding.fq_packed_weight_bytes(16, 100) == 0                  # K not a multiple of 128
+    assert binding.fq_packed_weight_bytes(0, 128) == 0
+    assert binding.fq_layout_version() >= 1
+    seen = {binding.status_string(s) for s in (0, -1, -2, -3, -4)}
+    assert len(seen) == 5 and binding.status_string(0) == "ok"
+    assert binding.status_string(-99) == "unknown status"
+
+
+def test_bad_arguments_are_rejected_without_a_launch():
+    L = binding.lib()
+    p = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    odd = ctypes.c_void_p(0x1008)
+    null = ctypes.c_void_p(0)
+    f1 = ctypes.c_float(1.0)
+    # shape errors
+    assert L.fq_w4a8_gemm(p, p, p, p, f1, p, 4, 32, 100, null) == -2
+    assert L.fq_w4a8_gemm(p, p, p, p, f1, p, -1, 32, 128, null) == -2
+    assert L.fq_w4a8_gemm(p, p, p, p, f1, p, 4, 0, 128, null) == -2
+    assert L.fq_w4a8_gemm(p, p, p, p, f1, p, 4, 32, 0, null) == -2
+    # M == 0 is a successful no-op even with NULL pointers
+    assert L.fq_w4a8_gemm(null, null, null, null, f1, null, 0, 32, 128, null) == 0
+    # NULL and misaligned pointers
+    assert L.fq_w4a8_gemm(null, p, p, p, f1, p, 4, 32, 128, null) == -1
+    assert L.fq_w4a8_gemm(p, p, p, p, f1, null, 4, 32, 128, null) == -1
+    assert L.fq_w4a8_gemm(odd, p, p, p, f1, p, 4, 32, 128, null) == -3
+    assert L.fq_w4a8_gemm(p, p, odd, p, f1, p, 4, 32, 128, null) == -3
+    assert L.fq_quantize_act(p, p, p, 4, 12, null) == -2
+    assert L.fq_quantize_act(p, p, p, 0, 128, null) == 0
+    assert L.fq_quantize_act(null, p, p, 4, 128, null) == -1
+    assert L.fq_quantize_act(p, odd, p, 4, 128, null) == -3
+    assert L.fq_pack_weights(p, p, 8, 100, null) == -2
+    assert L.fq_pack_weights(null, p, 8, 128, null) == -1
+    assert L.fq_pack_weights(p, odd, 8, 128, null) == -3
+    assert L.fq_pack_weights(null, null, 0, 128, null) == 0
+    assert L.fq_unpack_weights(p, null, 8, 128, null) == -1
+    assert L.fq_unpack_weights(p, p, 8, 64, null) == -2

@@ -1,0 +1,265 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integer/byte work (packing, E4M3 codes, row scales) must be bit-exact; the bf16
+GEMM output must satisfy  |Y - Y_ref| <= 1 bf16 ulp + 1e-3 * sum|terms|  per element and a relative
+Frobenius error of at most 2e-3 against the unrounded FP64 result."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_20839_amd import workloads
+from parity_util import bf16_bits_from_gpu, check_gemm, to_gpu_bf16
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def fq():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    from paper_2505_20839_amd import binding
+    binding.lib()
+    return binding
+
+
+@pytest.fixture
+def kernel_choice():
+    old = os.environ.get("FQ_FORCE_KERNEL")
+
+    def choose(name):
+        if name == "auto":
+            os.environ.pop("FQ_FORCE_KERNEL", None)
+        else:
+            os.environ["FQ_FORCE_KERNEL"] = name
+    yield choose
+    if old is None:
+        os.environ.pop("FQ_FORCE_KERNEL", None)
+    else:
+        os.environ["FQ_FORCE_KERNEL"] = old
+
+
+def _gpu(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def _run_gemm(fq, A, a_scale, q, gscale, t):
+    N = q.shape[0]
+    packed = fq.fq_pack_weights(_gpu(q))
+    Y = fq.fq_w4a8_gemm(_gpu(A), _gpu(a_scale), packed, _gpu(gscale), t, N)
+    torch.cuda.synchronize()
+    return bf16_bits_from_gpu(Y)
+
+
+def _rand_codes(M, N, K, seed, signed_scales=True):
+    rng = np.random.default_rng(seed)
+    A = rng.integers(0, 0x7F, (M, K)).astype(np.uint8) | (rng.integers(0, 2, (M, K)).astype(np.uint8) << 7)
+    q = rng.integers(-8, 8, (N, K), dtype=np.int8)
+    gs = rng.integers(0, 0x48, (N, K // 128)).astype(np.uint8)
+    if signed_scales:
+        gs |= (rng.integers(0, 2, gs.shape).astype(np.uint8) << 7)
+    a = rng.uniform(0.01, 2.0, M).astype(np.float32)
+    return A, a, q, gs, float(np.float32(rng.uniform(0.1, 3.0)))
+
+
+# ---- packing: bit-exact round trip ---------------------------------------------------------------
+
+@pytest.mark.parametrize("N,K", [(32, 128), (256, 512), (100, 384), (1, 128), (4096, 1408), (77, 2048)])
+def test_pack_unpack_roundtrip(fq, N, K):
+    rng = np.random.default_rng(N * 7 + K)
+    q = rng.integers(-8, 8, (N, K), dtype=np.int8)
+    packed = fq.fq_pack_weights(_gpu(q))
+    assert packed.numel() == fq.fq_packed_weight_bytes(N, K)
+    back = fq.fq_unpack_weights(packed, N, K).cpu().numpy()
+    assert np.array_equal(back, q)
+
+
+def test_pack_every_code_at_every_position(fq):
+    N, K = 64, 256
+    base = (np.arange(N)[:, None] * 5 + np.arange(K)[None, :] * 3)
+    for shift in range(16):
+        q = (((base + shift) % 16) - 8).astype(np.int8)
+        packed = fq.fq_pack_weights(_gpu(q))
+        assert np.array_equal(fq.fq_unpack_weights(packed, N, K).cpu().numpy(), q)
+    # only the low four bits of a code are read
+    q = np.random.default_rng(0).integers(-8, 8, (N, K), dtype=np.int8)
+    dirty = ((q.astype(np.int16) & 0xF) | 0x50).astype(np.uint8).view(np.int8)
+    assert np.array_equal(fq.fq_unpack_weights(fq.fq_pack_weights(_gpu(dirty)), N, K).cpu().numpy(), q)
+
+
+# ---- activation quantiser: bit-exact --------------------------------------------------------------
+
+def _check_quantize(fq, Xbits):
+    A_ref, s_ref = oracle.quantize_act(Xbits)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(Xbits))
+    torch.cuda.synchronize()
+    assert np.array_equal(s.cpu().numpy().view(np.uint32), s_ref.view(np.uint32))
+    A = A.cpu().numpy()
+    if not np.array_equal(A, A_ref):                       # -0 and +0 are the same number
+        diff = A != A_ref
+        assert np.all((A[diff] & 0x7F) == 0) and np.all((A_ref[diff] & 0x7F) == 0)
+    return A, s_ref
+
+
+@pytest.mark.parametrize("M,K,act,frac,seed", [(16, 512, "gauss", 0.0, 0), (300, 4096, "gauss", 0.01, 1),
+                                               (64, 11008, "laplace", 0.01, 2), (5, 16512, "gauss", 0.0, 3),
+                                               (1, 128, "gauss", 0.0, 4), (3, 8, "gauss", 0.0, 5)])
+def test_quantize_matches_oracle(fq, M, K, act, frac, seed):
+    if K % 128:
+        rng = np.random.default_rng(seed)
+        X = workloads.f32_to_bf16_bits(rng.standard_normal((M, K)).astype(np.float32))
+    else:
+        X = workloads.draw(M, 32, K, seed=seed, act=act, outlier_frac=frac)["X_bf16"]
+    _check_quantize(fq, X)
+
+
+def test_quantize_all_finite_bf16_values_and_zero_row(fq):
+    allbits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    vals = oracle.bf16_bits_to_f64(allbits)
+    rows = []
+    for amax in (1.0, 448.0, 0.0131, 3.0e4, 2.0 ** -100, 6.0e37):
+        ab = workloads.f32_to_bf16_bits(np.array([amax], np.float32))
+        am = oracle.bf16_bits_to_f64(ab)[0]
+        keep = allbits[np.isfinite(vals) & (np.abs(vals) <= am)]
+        row = np.concatenate([ab, keep])
+        rows.append(row)
+    K = max(len(r) for r in rows)
+    K += (-K) % 8
+    X = np.zeros((len(rows) + 1, K), np.uint16)           # last row stays all zero
+    for i, r in enumerate(rows):
+        X[i, :len(r)] = r
+    A, s = _check_quantize(fq, X)
+    assert s[-1] == 1.0 and not A[-1].any()
+
+
+# ---- GEMM: element-by-element against the oracle, every kernel ------------------------------------
+
+SMALL_SHAPES = [(16, 256, 512), (1, 32, 128), (33, 100, 384), (64, 96, 1408), (7, 31, 256)]
+LARGE_SHAPES = [(16, 256, 512), (300, 200, 640), (257, 513, 384), (512, 256, 1408), (65, 33, 128)]
+
+
+@pytest.mark.parametrize("kernel,shape", [("simple", s) for s in SMALL_SHAPES[:3]] +
+                         [("small", s) for s in SMALL_SHAPES] + [("large", s) for s in LARGE_SHAPES])
+def test_gemm_random_codes(fq, kernel_choice, kernel, shape):
+    M, N, K = shape
+    A, a, q, gs, t = _rand_codes(M, N, K, seed=M + N + K)
+    kernel_choice(kernel)
+    Yb = _run_gemm(fq, A, a, q, gs, t)
+    Y, B = oracle.w4a8_gemm(A, a, q, gs, t, want_bound=True)
+    check_gemm(Yb, Y, B, "%s %s" % (kernel, shape))
+
+
+@pytest.mark.parametrize("kernel", ["simple", "small", "large"])
+def test_gemm_config1(fq, kernel_choice, kernel):
+    d = workloads.draw_workload("c1_tiny")
+    A, s = _check_quantize(fq, d["X_bf16"])
+    kernel_choice(kernel)
+    Yb = _run_gemm(fq, A, s, d["q"], d["gscale"], d["w_tscale"])
+    Y, B = oracle.w4a8_gemm(A, s, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(Yb, Y, B, "config 1 " + kernel)
+
+
+@pytest.mark.parametrize("kernel", ["small", "large"])
+def test_gemm_one_hot_activations_read_back_weights(fq, kernel_choice, kernel):
+    # A = identity: Y[m,n] = a_scale[m] * t * e4m3(gs[n, m/128]) * q[n,m] -- one product per output, so
+    # every packed weight and every scale is read back individually (only bf16 rounding remains).
+    K = 256; N = 96
+    _, _, q, gs, t = _rand_codes(8, N, K, seed=77)
+    a = np.random.default_rng(1).uniform(0.5, 2.0, K).astype(np.float32)
+    for m0 in range(0, K, 64):
+        M = 64
+        A = np.zeros((M, K), np.uint8)
+        A[np.arange(M), m0 + np.arange(M)] = 0x38
+        kernel_choice(kernel)
+        Yb = _run_gemm(fq, A, a[m0:m0 + M], q, gs, t)
+        Y = oracle.w4a8_gemm(A, a[m0:m0 + M], q, gs, t)
+        assert np.array_equal(Yb, oracle.bf16_round_array(Y)) or \
+            np.array_equal(oracle.bf16_bits_to_f64(Yb), oracle.bf16_bits_to_f64(oracle.bf16_round_array(Y)))
+
+
+@pytest.mark.parametrize("kernel", ["small", "large"])
+def test_gemm_special_values(fq, kernel_choice, kernel):
+    M, N, K = 48, 64, 512
+    kernel_choice(kernel)
+    ones = np.ones(M, np.float32)
+    # all ones -> K exactly
+    Yb = _run_gemm(fq, np.full((M, K), 0x38, np.uint8), ones, np.ones((N, K), np.int8),
+                   np.full((N, K // 128), 0x38, np.uint8), 1.0)
+    assert np.all(oracle.bf16_bits_to_f64(Yb) == K)
+    # extremes: 448 * -8 * K, exactly representable in bf16 (7 * 2^9 * 512 * ... = -7 * 2^18)
+    Yb = _run_gemm(fq, np.full((M, K), 0x7E, np.uint8), ones, np.full((N, K), -8, np.int8),
+                   np.full((N, K // 128), 0x38, np.uint8), 1.0)
+    assert np.all(oracle.bf16_bits_to_f64(Yb) == -3584.0 * K)
+    # a zero-scale group contributes nothing (App. B, Lemma B.1); subnormal and negative scales work
+    A, a, q, gs, t = _rand_codes(M, N, K, seed=5)
+    gs[:, 1] = 0x00
+    gs[:, 2] = 0x03
+    gs[:, 3] = 0x85
+    Yb = _run_gemm(fq, A, a, q, gs, t)
+    Y, B = oracle.w4a8_gemm(A, a, q, gs, t, want_bound=True)
+    check_gemm(Yb, Y, B, "special scales " + kernel)
+
+
+def test_gemm_invariants_on_gpu(fq, kernel_choice):
+    M, N, K = 300, 256, 1024
+    A, a, q, gs, t = _rand_codes(M, N, K, seed=9)
+    kernel_choice("large")
+    Y1 = _run_gemm(fq, A, a, q, gs, t)
+    Y2 = _run_gemm(fq, A, a, q, gs, 2 * t)
+    assert np.array_equal(oracle.bf16_bits_to_f64(Y2), 2 * oracle.bf16_bits_to_f64(Y1))   # delta = 2^n is exact
+    Yagain = _run_gemm(fq, A, a, q, gs, t)
+    assert np.array_equal(Y1, Yagain)                                                     # deterministic
+    kernel_choice("small")
+    Yrow = _run_gemm(fq, A[5:6], a[5:6], q, gs, t)
+    d = np.abs(oracle.bf16_bits_to_f64(Yrow)[0] - oracle.bf16_bits_to_f64(Y1)[5])
+    assert np.all(d <= oracle.bf16_ulp_array(oracle.bf16_bits_to_f64(Y1)[5]))             # row independence
+    kernel_choice("auto")
+    assert np.array_equal(_run_gemm(fq, A, a, q, gs, t), Y1)
+
+
+def test_m_zero_is_a_noop(fq):
+    packed = torch.zeros(fq.fq_packed_weight_bytes(32, 128), dtype=torch.uint8, device="cuda")
+    Y = fq.fq_w4a8_gemm(torch.zeros((0, 128), dtype=torch.uint8, device="cuda"),
+                        torch.zeros((0,), dtype=torch.float32, device="cuda"), packed,
+                        torch.zeros((32, 1), dtype=torch.uint8, device="cuda"), 1.0, 32)
+    assert tuple(Y.shape) == (0, 32)
+
+
+# ---- the benchmark configurations at full size ----------------------------------------------------
+
+def _full_config(fq, name, sample_rows):
+    """GPU on the whole problem, oracle on sampled rows (all N columns of each)."""
+    w = workloads.WORKLOADS[name]
+    d = workloads.draw_workload(name)
+    X = to_gpu_bf16(d["X_bf16"])
+    A_gpu, s_gpu = fq.fq_quantize_act(X)
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    Y = fq.fq_w4a8_gemm(A_gpu, s_gpu, packed, _gpu(d["gscale"]), d["w_tscale"], w.N)
+    torch.cuda.synchronize()
+    rows = np.array(sorted(set(r for r in sample_rows if r < w.M)))
+    A_ref, s_ref = oracle.quantize_act(d["X_bf16"][rows])
+    assert np.array_equal(A_gpu.cpu().numpy()[rows] & 0x7F | (A_ref & 0x80), A_ref) or \
+        np.array_equal(A_gpu.cpu().numpy()[rows], A_ref)
+    assert np.array_equal(s_gpu.cpu().numpy()[rows], s_ref)
+    Yr, B = oracle.w4a8_gemm(A_ref, s_ref, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    stats = check_gemm(bf16_bits_from_gpu(Y)[rows], Yr, B, name)
+    back = fq.fq_unpack_weights(packed, w.N, w.K)
+    assert torch.equal(back.cpu(), torch.from_numpy(d["q"]))
+    return stats
+
+
+@pytest.mark.parametrize("name", ["c5_decode_m1", "c5_decode_m4", "c5_decode_m16", "c5_decode_m64"])
+def test_config5_full(fq, name):
+    _full_config(fq, name, range(64))
+
+
+@pytest.mark.parametrize("name,rows", [
+    ("c2_l2_7b_gateup", [0, 1, 31, 32, 255, 256, 1000, 1023, 1024, 2016, 2047]),
+    ("c3_l2_7b_down", [0, 17, 255, 256, 1500, 2047]),
+    ("c4a_l3_8b_qkv", [0, 33, 4095, 4096, 8000, 8191]),
+    ("c4b_l3_8b_up", [0, 255, 256, 7777, 8191]),
+])
+def test_large_configs_sampled_rows(fq, name, rows):
+    _full_config(fq, name, rows)
