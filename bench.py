@@ -1,0 +1,170 @@
+#!/usr/bin/env python3
+"""Benchmark of the W4A8-FP linear-layer path on one MI355X.
+
+A step is one pass of the hot path over one batch: fq_quantize_act (bf16 -> E4M3 + row scales)
+followed by fq_w4a8_gemm on weights packed once beforehand (packing is offline, once per weight).
+All inputs are synthetic (seeded) and resident in HBM before the timed region starts.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Prints one JSON line: whole-step throughput (`value`), the roofline figure of the GEMM kernel
+measured with HIP events around every GEMM launch of the timed region, and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import glob
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP8_TFLOPS = 5033.0      # 256 CU x 2.4 GHz x 8192 flop/clk/CU, dense FP8 MFMA
+PEAK_HBM_GBPS = 8000.0
+DEFAULT_WORKLOAD = "c2_l2_7b_gateup"
+DECODE_COPIES = 12            # rotating weight copies so that small-M launches read HBM, not cache
+
+
+def _traffic_from_profiles(workload: str):
+    """HBM bytes per GEMM launch measured with rocprofv3 --pmc, if a summary records them."""
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.txt")) +
+                       glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+        for line in open(path):
+            m = re.match(r"\s*TRAFFIC_BYTES_PER_LAUNCH\s+(\S+)\s+([0-9.eE+]+)", line)
+            if m and m.group(1) == workload:
+                return float(m.group(2))
+    return None
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the extra small-M (HBM-bound) figure")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the W4A8-FP GEMM of one linear layer on one "
+              "MI355X); --gpus %d is not supported." % args.gpus, file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2505_20839_amd import binding as fq, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    fq.lib()
+
+    def upload(name):
+        w = workloads.WORKLOADS[name]
+        d = workloads.draw_workload(name)
+        X = torch.from_numpy(d["X_bf16"].view(np.int16)).cuda().view(torch.bfloat16)
+        packed = fq.fq_pack_weights(torch.from_numpy(d["q"]).cuda())
+        gs = torch.from_numpy(d["gscale"]).cuda()
+        return w, d, X, packed, gs
+
+    def run(name, steps, warmup, copies):
+        """Times `steps` steps; returns (seconds for all steps, mean GEMM kernel seconds, mean quantiser seconds)."""
+        w, d, X, packed, gs = upload(name)
+        packs = [packed] + [packed.clone() for _ in range(copies - 1)]
+        gss = [gs] + [gs.clone() for _ in range(copies - 1)]
+        Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+
+        def step(i, evs=None):
+            if evs is not None:
+                evs[0].record()
+            A, s = fq.fq_quantize_act(X)
+            if evs is not None:
+                evs[1].record()
+            fq.fq_w4a8_gemm(A, s, packs[i % copies], gss[i % copies], d["w_tscale"], w.N, out=Y)
+            if evs is not None:
+                evs[2].record()
+
+        for i in range(warmup):
+            step(i)
+        events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(steps):
+            step(i, events[i])
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        gemm_s = sum(e[1].elapsed_time(e[2]) for e in events) * 1e-3 / steps
+        quant_s = sum(e[0].elapsed_time(e[1]) for e in events) * 1e-3 / steps
+        return w, d, (t1 - t0), gemm_s, quant_s
+
+    name = args.workload
+    w0 = workloads.WORKLOADS[name]
+    decode_like = w0.M <= 64
+    steps = args.steps if args.steps is not None else (2000 if decode_like else 200)
+    warmup = args.warmup if args.warmup is not None else (50 if decode_like else 20)
+    w, d, total_s, gemm_s, quant_s = run(name, steps, warmup, DECODE_COPIES if decode_like else 1)
+
+    flop = 2.0 * w.M * w.N * w.K
+    G = w.K // 128
+    wbytes = w.N * w.K / 2 + w.N * G                      # packed INT4 + group scales
+    gemm_bytes = wbytes + w.M * w.K + 4 * w.M + 2 * w.M * w.N
+    if decode_like:
+        metric, unit = "W4A8 GEMM packed-weight GB/s at small M", "GB/s"
+        value = wbytes * steps / total_s / 1e9
+        roof = {"bound": "hbm", "achieved": wbytes / gemm_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s"}
+    else:
+        metric, unit = "W4A8 GEMM TFLOPS at M=%d" % w.M, "TFLOP/s"
+        value = flop * steps / total_s / 1e12
+        roof = {"bound": "mfma", "achieved": flop / gemm_s / 1e12, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s"}
+    roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["traffic"] = _traffic_from_profiles(name)
+    roof["kernel"] = "fq_gemm_small_kernel" if decode_like else "fq_gemm_large_kernel"
+    roof["kernel_us"] = gemm_s * 1e6
+    roof["quantize_us"] = quant_s * 1e6
+    roof["algorithmic_bytes"] = gemm_bytes
+
+    out = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": total_s * 1e3 / steps, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp8_e4m3 x int4 -> f32", "data": "synthetic",
+        "config": {"workload": name, "M": w.M, "N": w.N, "K": w.K, "group": 128,
+                   "step": "fq_quantize_act + fq_w4a8_gemm (weights packed once, offline)"},
+        "roofline": roof,
+    }
+
+    if not decode_like and not args.no_decode:
+        # second half of the metric: packed-weight GB/s at M = 16 against the HBM roofline
+        wd, dd, tot_d, gemm_d, _ = run("c5_decode_m16", 1500, 50, DECODE_COPIES)
+        wb = wd.N * wd.K / 2 + wd.N * (wd.K // 128)
+        out["decode_m16"] = {"workload": "c5_decode_m16", "kernel_us": gemm_d * 1e6,
+                             "weight_GBps": wb / gemm_d / 1e9, "frac_hbm": wb / gemm_d / 1e9 / PEAK_HBM_GBPS,
+                             "weight_copies_rotated": DECODE_COPIES}
+
+    if not args.no_cpu_baseline:
+        import oracle
+        rows = min(w.M, 1024 if not decode_like else w.M)
+        Xs = d["X_bf16"][:rows]
+        c0 = time.perf_counter()
+        A_ref, s_ref = oracle.quantize_act(Xs)
+        oracle.w4a8_gemm(A_ref, s_ref, d["q"], d["gscale"], d["w_tscale"])
+        c1 = time.perf_counter()
+        if decode_like:
+            cv, cu = wbytes / (c1 - c0) / 1e9, "GB/s"
+        else:
+            cv, cu = 2.0 * rows * w.N * w.K / (c1 - c0) / 1e12, "TFLOP/s"
+        out["cpu_baseline"] = {"value": cv, "unit": cu, "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": "first %d of %d rows of %s, all %d columns; FP64 C oracle (quantiser + GEMM), %.1f s"
+                                         % (rows, w.M, name, w.N, c1 - c0)}
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

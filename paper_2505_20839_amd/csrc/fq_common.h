@@ -11,6 +11,8 @@ typedef int   fq_v8i  __attribute__((ext_vector_type(8)));
 typedef int   fq_v2i  __attribute__((ext_vector_type(2)));
 typedef float fq_v16f __attribute__((ext_vector_type(16)));
 typedef float fq_v4f  __attribute__((ext_vector_type(4)));
+typedef float fq_v2f  __attribute__((ext_vector_type(2)));
+typedef __bf16 fq_v2bf __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------------------------
 // Packed weight layout (version 1), made for the B operand of v_mfma_f32_32x32x64_f8f6f4.

@@ -10,47 +10,60 @@
 //     P   = A[:, g, first 64] * Wq[g, first 64]            v_mfma_f32_32x32x64_f8f6f4, C = 0
 //     P  += A[:, g, last 64]  * Wq[g, last 64]             same, C = P
 //     acc += e4m3(gscale[n, g]) * P                        16 v_fma_f32 per 32x32 tile
-// A tiles go global -> registers -> LDS (three stages of 32 KiB), packed weights go global ->
-// registers directly (each wave reads only its own 32 channels).
+// A tiles go global -> LDS directly (global_load_lds_dwordx4, four stages of 32 KiB, two groups per
+// barrier); packed weights go global -> registers (each wave reads only its own 32 channels) and
+// are unpacked one group ahead, a slice under each pair of MFMAs.
 #include "fq_common.h"
 #include "fq_kernels.h"
 
 #define FQL_THREADS 512
 #define FQL_BM 256
 #define FQL_STAGE_BYTES (FQL_BM * FQ_GROUP)          // 32 KiB: 256 rows x 128 E4M3 bytes
-#define FQL_STAGES 3
+#define FQL_STAGE_CHUNKS (FQL_STAGE_BYTES / 16)
+#define FQL_STAGES 4                                 // two pairs of groups: one in use, one in flight
 
 #define FQ_MFMA(a, b, c) __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4((a), (b), (c), 0, 0, 0, 0, 0, 0)
 
 namespace {
 
-// LDS layout of one A stage: 16-byte chunks ordered [row tile mt (8)][half h (2)][part (2)][lane (64)],
-// lane = 32*kh + (row % 32), holding A[row][64*h + 32*kh + 16*part .. +16] of the current group.
-// A wave reads the two parts of (mt, h) with two ds_read_b128 whose addresses are linear in the lane.
-__device__ __forceinline__ int fql_lds_chunk(int row, int kc) {
-    int h = kc >> 2, kh = (kc >> 1) & 1, part = kc & 1;
-    return ((((row >> 5) * 2 + h) * 2 + part) << 6) + (kh << 5) + (row & 31);
-}
+typedef __attribute__((address_space(3))) void* fql_lds_ptr;
+typedef const __attribute__((address_space(1))) void* fql_glb_ptr;
 
-struct AStage { fq_v4i v[4]; };
-
-__device__ __forceinline__ void fql_load_a(AStage& st, const uint8_t* __restrict__ A, int M, int K,
-                                           int m0, int g) {
+// LDS layout of one A stage (one 128-wide group of 256 rows): row-major, 8 slots of 16 bytes per
+// row; slot c of row r holds bytes 16*x .. 16*x+15 of the row's group with x = c ^ ((r >> 1) & 7).
+// The XOR makes the operand reads (lane = row, fixed x) hit 16 different bank groups per 16 lanes,
+// while the global->LDS transfer (global_load_lds_dwordx4, LDS address linear in the lane) still
+// fetches whole 128-byte rows: 8 rows per instruction, 4 instructions per wave and stage.
+__device__ __forceinline__ void fql_issue_a(fq_v4i* lds_stage, const uint8_t* __restrict__ A, int M, int K,
+                                            int m0, int g) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int c = threadIdx.x + i * FQL_THREADS;            // 2048 chunks: row = c / 8, kc = c % 8
-        int row = m0 + (c >> 3);
-        row = row < M ? row : M - 1;
-        st.v[i] = *reinterpret_cast<const fq_v4i*>(A + (size_t)row * K + (size_t)g * FQ_GROUP + (c & 7) * 16);
+    for (int j = 0; j < 4; ++j) {
+        const int row = wave * 32 + j * 8 + (lane >> 3);
+        const int x = (lane & 7) ^ ((row >> 1) & 7);
+        int grow = m0 + row;
+        grow = grow < M ? grow : M - 1;                   // rows past M are duplicates, never stored
+        const uint8_t* src = A + (size_t)grow * K + (size_t)g * FQ_GROUP + x * 16;
+        fq_v4i* dst = lds_stage + (wave * 32 + j * 8) * 8;    // wave-uniform; lane l lands at dst + l
+        __builtin_amdgcn_global_load_lds((fql_glb_ptr)src, (fql_lds_ptr)dst, 16, 0, 0);
     }
 }
 
-__device__ __forceinline__ void fql_store_a(const AStage& st, fq_v4i* lds_stage) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        int c = threadIdx.x + i * FQL_THREADS;
-        lds_stage[fql_lds_chunk(c >> 3, c & 7)] = st.v[i];
-    }
+// One group of this wave's packed weights (2 KiB: two halves of 64 lanes x 16 bytes) -> LDS.
+__device__ __forceinline__ void fql_issue_b(fq_v4i* dst, const uint8_t* __restrict__ src_lane) {
+    __builtin_amdgcn_global_load_lds((fql_glb_ptr)src_lane, (fql_lds_ptr)dst, 16, 0, 0);
+    __builtin_amdgcn_global_load_lds((fql_glb_ptr)(src_lane + 1024), (fql_lds_ptr)(dst + 64), 16, 0, 0);
+}
+
+// s_waitcnt immediate (gfx9 encoding) that waits until at most n vector-memory transfers are pending
+// and leaves the other counters alone.
+#define FQL_WAIT_VM(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
+
+__device__ __forceinline__ fq_v8i fql_join(fq_v4i lo, fq_v4i hi) {
+    fq_v8i r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return r;
 }
 
 }  // namespace
@@ -58,16 +71,22 @@ __device__ __forceinline__ void fql_store_a(const AStage& st, fq_v4i* lds_stage)
 __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K) {
-    extern __shared__ fq_v4i lds[];                       // FQL_STAGES stages of 2048 chunks
+    extern __shared__ fq_v4i lds[];                       // 4 A stages (128 KiB) + 8 x 4 KiB of packed weights
     const int G = K / FQ_GROUP;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const int m0 = blockIdx.y * FQL_BM;
     const int nw0 = blockIdx.x * 256 + wave * 32;         // first output channel of this wave
-    const bool wave_on = nw0 < N;                         // waves past N only help moving A
+    const bool wave_on = nw0 < N;                         // waves past N compute a duplicate tile and store nothing
     const int n = nw0 + (lane & 31);                      // this lane's output channel
     const bool n_ok = n < N;
-    const uint8_t* wblk = wp + fq_block_offset(nw0 >> 5, 0, G) + (size_t)lane * 16u;
-    const uint8_t* gsrow = gs + (size_t)(n_ok ? n : 0) * G;
+    const int nt = wave_on ? (nw0 >> 5) : ((N - 1) >> 5);
+    const uint8_t* wblk = wp + fq_block_offset(nt, 0, G) + (size_t)lane * 16u;
+    const uint8_t* gsrow = gs + (size_t)(n_ok ? n : N - 1) * G;
+
+    // operand read offsets (in chunks) of this lane inside a 32-row tile: (half h, part) -> slot
+    const int r32 = lane & 31, sw = (r32 >> 1) & 7;
+    const int o00 = r32 * 8 + ((2 * (lane >> 5)) ^ sw);   // h = 0, bytes 0..15 of the lane's 32
+    const int o01 = o00 ^ 1, o10 = o00 ^ 4, o11 = o00 ^ 5;
 
     fq_v16f acc[8];
 #pragma unroll
@@ -78,74 +97,181 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 
-    // ---- prologue: A stages 0 and 1, packed weights and scale of group 0 ----
-    AStage st;
-    fql_load_a(st, A, M, K, m0, 0);
-    fql_store_a(st, lds);
-    if (G > 1) {
-        fql_load_a(st, A, M, K, m0, 1);
-        fql_store_a(st, lds + 2048);
-    }
-    fq_v4i bp0 = {0, 0, 0, 0}, bp1 = {0, 0, 0, 0};
-    unsigned sbyte = 0;
-    if (wave_on) {
-        bp0 = *reinterpret_cast<const fq_v4i*>(wblk);
-        bp1 = *reinterpret_cast<const fq_v4i*>(wblk + 1024);
-        sbyte = gsrow[0];
-    }
+    // ---- prologue ----
+    fql_issue_a(lds, A, M, K, m0, 0);
+    fql_issue_a(lds + FQL_STAGE_CHUNKS, A, M, K, m0, G > 1 ? 1 : 0);
+    // Packed weights also travel global -> LDS directly, into two 2 KiB buffers private to the wave
+    // ([half h][lane][16 bytes], the order they have in memory); buffer g & 1 holds group g.
+    fq_v4i* wbuf = lds + FQL_STAGES * FQL_STAGE_CHUNKS + wave * 256;
+    fql_issue_b(wbuf, wblk);
+    fql_issue_b(wbuf + 128, wblk + (size_t)(G > 1 ? 1 : 0) * 2048u);
+    unsigned psb[2];                                      // scale bytes in flight (group g+1, g+2)
+    psb[0] = gsrow[0];
+    psb[1] = gsrow[G > 1 ? 1 : 0];
+    fq_v8i b0[2], b1[2];                                  // unpacked operands: [u] current, [u^1] next
+    float sc[2];
+    __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
+    b0[0] = fq_unpack_chunk(wbuf[lane]);
+    b1[0] = fq_unpack_chunk(wbuf[64 + lane]);
+    sc[0] = __builtin_amdgcn_cvt_f32_fp8((int)psb[0], 0);
+    b0[1] = b0[0]; b1[1] = b1[0]; sc[1] = 0.f;
     __syncthreads();
 
     fq_v16f pprev = zero;                                 // partial sums of the previous row tile
     float sprev = 0.f;                                    // and their group scale
-    for (int g = 0; g < G; ++g) {
-        const fq_v4i* cur = lds + (g % FQL_STAGES) * 2048;
-        const bool more2 = g + 2 < G;
-        if (more2) fql_load_a(st, A, M, K, m0, g + 2);
-        fq_v8i b0 = fq_unpack_chunk(bp0);
-        fq_v8i b1 = fq_unpack_chunk(bp1);
-        float s = __builtin_amdgcn_cvt_f32_fp8((int)sbyte, 0);
-        if (wave_on && g + 1 < G) {
-            const uint8_t* nb = wblk + (size_t)(g + 1) * 2048u;
-            bp0 = *reinterpret_cast<const fq_v4i*>(nb);
-            bp1 = *reinterpret_cast<const fq_v4i*>(nb + 1024);
-            sbyte = gsrow[g + 1];
+    // Two groups per barrier.  Every load is unconditional (group indices are clamped at G-1
+    // instead of skipped; a clamped "ghost" group is multiplied by a zero scale).
+    //
+    // The body is software-pipelined by hand, one step per MFMA: the step fetches the A operand of
+    // the next step from LDS, issues its MFMA, and fills the MFMA's shadow with half of the previous
+    // row tile's scale-accumulate (8 v_fma) and a share of the next group's unpack.  Scheduling
+    // barriers keep the compiler from undoing that order.
+    const int npairs = (G + 1) >> 1;
+    fq_v8i an = fql_join(lds[o00], lds[o01]);             // operand of the very first step
+    for (int p = 0; p < npairs; ++p) {
+        {   // A tiles of the next pair -> the two stages the previous pair used (8 transfers)
+            const int ga = 2 * p + 2 < G ? 2 * p + 2 : G - 1;
+            const int gb = 2 * p + 3 < G ? 2 * p + 3 : G - 1;
+            fq_v4i* nx = lds + ((p + 1) & 1) * 2 * FQL_STAGE_CHUNKS;
+            fql_issue_a(nx, A, M, K, m0, ga);
+            fql_issue_a(nx + FQL_STAGE_CHUNKS, A, M, K, m0, gb);
         }
-        if (wave_on) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const int g = 2 * p + u;
+            const fq_v4i* cur = lds + ((p & 1) * 2 + u) * FQL_STAGE_CHUNKS;
+            // Group g+1 sits in buffer u^1 (requested one group ago) and is unpacked slice by slice
+            // under the MFMAs below; buffer u (group g, already unpacked) is refilled with group g+2.
+            const unsigned qs = psb[u ^ 1];
+            {
+                const int g2 = g + 2 < G ? g + 2 : G - 1;
+                fql_issue_b(wbuf + u * 128, wblk + (size_t)g2 * 2048u);
+                psb[u] = gsrow[g2];
+            }
+            // Transfers requested after group g+1's: its scale byte, (first group of a pair) the 8 A
+            // transfers, and the 3 just above -> once at most that many are pending, g+1 has landed.
+            if (u == 0) __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(11));
+            else        __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(3));
+            const fq_v4i* nxt = wbuf + (u ^ 1) * 128 + lane;
+            const float s = sc[u];
+            fq_v4i q = nxt[0];
+            fq_v16f pt;
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
-                const fq_v4i* ap = cur + mt * 256 + lane;
-                fq_v8i a0, a1;
-                fq_v4i t0 = ap[0], t1 = ap[64], t2 = ap[128], t3 = ap[192];
-                a0[0] = t0[0]; a0[1] = t0[1]; a0[2] = t0[2]; a0[3] = t0[3];
-                a0[4] = t1[0]; a0[5] = t1[1]; a0[6] = t1[2]; a0[7] = t1[3];
-                a1[0] = t2[0]; a1[1] = t2[1]; a1[2] = t2[2]; a1[3] = t2[3];
-                a1[4] = t3[0]; a1[5] = t3[1]; a1[6] = t3[2]; a1[7] = t3[3];
-                fq_v16f p = FQ_MFMA(a0, b0, zero);
-                p = FQ_MFMA(a1, b1, p);
-                // scale-accumulate the previous tile while these two MFMAs run
                 const int tp = (mt + 7) & 7;
+                const float sp = (mt == 0) ? sprev : s;   // row tile 7 of the previous group used the old scale
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[tp][r] = fmaf(sprev, pprev[r], acc[tp][r]);
-                pprev = p;
-                if (mt == 0) sprev = s;                   // tiles 0..7 of this group use s; tile 7 of the previous group used the old value
+                for (int h = 0; h < 2; ++h) {
+                    const fq_v8i ac = an;
+                    // A operand of the next step (none after the last step of a pair: the next
+                    // pair's stages are only complete after the barrier)
+                    if (h == 0) {
+                        an = fql_join(cur[mt * 256 + o10], cur[mt * 256 + o11]);
+                    } else if (mt < 7) {
+                        an = fql_join(cur[(mt + 1) * 256 + o00], cur[(mt + 1) * 256 + o01]);
+                    } else if (u == 0) {
+                        an = fql_join(cur[FQL_STAGE_CHUNKS + o00], cur[FQL_STAGE_CHUNKS + o01]);
+                    }
+                    if (h == 0) pt = FQ_MFMA(ac, b0[u], zero);
+                    else        pt = FQ_MFMA(ac, b1[u], pt);
+#pragma unroll
+                    for (int r = 8 * h; r < 8 * h + 8; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
+                    {   // one sixteenth of the next group's unpack: half a packed word
+                        const unsigned w = (unsigned)q[mt & 3];
+                        const unsigned x = (h == 0 ? w : (w >> 4)) & 0x0F0F0F0Fu;
+                        const int e = (int)fq_codes_to_e4m3x4(x);
+                        if (mt < 4) b0[u ^ 1][4 * h + (mt & 3)] = e;
+                        else        b1[u ^ 1][4 * h + (mt & 3)] = e;
+                    }
+                    if (mt == 3 && h == 1) q = nxt[64];
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // the two LDS reads
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // the MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);  // its shadow: VALU work
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                pprev = pt;
+            }
+            sprev = s;
+            {
+                const float t = __builtin_amdgcn_cvt_f32_fp8((int)qs, 0);
+                sc[u ^ 1] = (g + 1 < G) ? t : 0.f;
             }
         }
-        if (more2) fql_store_a(st, lds + ((g + 2) % FQL_STAGES) * 2048);
         __syncthreads();
+        {
+            const fq_v4i* nxs = lds + ((p + 1) & 1) * 2 * FQL_STAGE_CHUNKS;
+            an = fql_join(nxs[o00], nxs[o01]);
+        }
     }
     // last pending tile (row tile 7 of the last group)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[7][r] = fmaf(sprev, pprev[r], acc[7][r]);
 
-    // ---- epilogue: per-token and per-tensor factors (x 2^9: weights were fed as q * 2^-9), bf16 ----
+    // ---- epilogue: per-token and per-tensor factors, one rounding to bf16, store ----
+    // The stages are free now: bytes [0, 67584) become the output tile, [67584, 68608) the row factors.
+    float* osc = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + 128 * 528);
+    if (threadIdx.x < FQL_BM) {                           // x 2^9: the weights were fed as q * 2^-9
+        int m = m0 + threadIdx.x;
+        osc[threadIdx.x] = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);
+    }
+    __syncthreads();
+    const int nblk = blockIdx.x * 256;
+    const bool full_tile = (m0 + FQL_BM <= M) && (nblk + 256 <= N) && ((N & 7) == 0);
+    if (full_tile) {
+        // Transpose through LDS so that every store instruction writes whole 512-byte rows.
+        // Tile of 128 rows x 256 bf16, row stride 528 bytes; two passes (row tiles 0-3, 4-7).
+        char* tile = reinterpret_cast<char*>(lds);
+        const int colb = (wave * 32 + (lane & 31)) * 2;   // byte offset of this lane's column
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (half) __syncthreads();                    // readers of the first pass are done
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const int mt = half * 4 + t;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {             // rows 8j + 4*(lane/32) + 0..3 of the 32x32 tile
+                    const int rl = 8 * j + 4 * (lane >> 5);
+                    fq_v4f sc = *reinterpret_cast<const fq_v4f*>(&osc[mt * 32 + rl]);
+#pragma unroll
+                    for (int e = 0; e < 4; e += 2) {
+                        float f0 = acc[mt][4 * j + e] * sc[e];          // row rl + e
+                        float f1 = acc[mt][4 * j + e + 1] * sc[e + 1];  // row rl + e + 1
+                        // lanes pair up: the even lane keeps row rl+e (its column and the next),
+                        // the odd lane keeps row rl+e+1 (the previous column and its own)
+                        float send = (lane & 1) ? f0 : f1;
+                        float got = __int_as_float(__builtin_amdgcn_update_dpp(
+                            0, __float_as_int(send), 0xB1, 0xF, 0xF, false));
+                        fq_v2f pr = (lane & 1) ? (fq_v2f){got, f1} : (fq_v2f){f0, got};
+                        fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+                        const int row = t * 32 + rl + e + (lane & 1);
+                        *reinterpret_cast<fq_v2bf*>(tile + row * 528 + (colb & ~3)) = pk;
+                    }
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {                 // wave w stores rows 16w .. 16w+15, two per instruction
+                const int row = wave * 16 + 2 * j + (lane >> 5);
+                fq_v4i v = *reinterpret_cast<const fq_v4i*>(tile + row * 528 + (lane & 31) * 16);
+                const size_t m = (size_t)(m0 + half * 128 + row);
+                *reinterpret_cast<fq_v4i*>(Y + m * N + nblk + (lane & 31) * 8) = v;
+            }
+        }
+        return;
+    }
+    // ragged tile: element-wise stores with bounds checks
     if (!wave_on || !n_ok) return;
-    const float outer = tscale * 512.0f;
 #pragma unroll
     for (int mt = 0; mt < 8; ++mt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-            int m = m0 + mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-            if (m < M) Y[(size_t)m * N + n] = (uint16_t)fq_float_to_bf16(acc[mt][r] * (a_scale[m] * outer));
+            int ml = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+            if (m0 + ml < M) {
+                fq_v2f pr = {acc[mt][r] * osc[ml], 0.f};
+                fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+                Y[(size_t)(m0 + ml) * N + n] = __builtin_bit_cast(unsigned short, pk[0]);
+            }
         }
     }
 }
@@ -153,7 +279,7 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
     static bool attr_set = false;
-    const int lds_bytes = FQL_STAGES * FQL_STAGE_BYTES;
+    const int lds_bytes = FQL_STAGES * FQL_STAGE_BYTES + 8 * 4096;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
