@@ -50,6 +50,9 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the extra small-M (HBM-bound) figure")
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="only run a plain device-to-device copy of BYTES bytes three times (reference "
+                         "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the W4A8-FP GEMM of one linear layer on one "
@@ -64,6 +67,14 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        src = torch.empty(args.copy_calibration, dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration_bytes": args.copy_calibration, "copies": 3}))
+        return 0
     fq.lib()
 
     def upload(name):
@@ -75,7 +86,14 @@ def main() -> int:
         return w, d, X, packed, gs
 
     def run(name, steps, warmup, copies):
-        """Times `steps` steps; returns (seconds for all steps, mean GEMM kernel seconds, mean quantiser seconds)."""
+        """Times `steps` steps; returns (workload, inputs, steps timed, seconds for all of them,
+        mean GEMM kernel seconds, mean quantiser seconds).
+
+        Large-M steps are launched one by one with HIP events around each kernel (the GPU is the
+        bottleneck, launches queue up).  Small-M steps finish faster than Python can launch them, so
+        they are captured into a HIP graph (`copies` steps, each on its own copy of the weights) and
+        the graph is replayed; the GEMM kernel's mean duration then comes from a second graph that
+        holds only the GEMM launches."""
         w, d, X, packed, gs = upload(name)
         packs = [packed] + [packed.clone() for _ in range(copies - 1)]
         gss = [gs] + [gs.clone() for _ in range(copies - 1)]
@@ -90,26 +108,66 @@ def main() -> int:
             fq.fq_w4a8_gemm(A, s, packs[i % copies], gss[i % copies], d["w_tscale"], w.N, out=Y)
             if evs is not None:
                 evs[2].record()
+            return A, s
 
         for i in range(warmup):
-            step(i)
-        events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+            A_last, s_last = step(i)
         torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(steps):
-            step(i, events[i])
-        torch.cuda.synchronize()
-        t1 = time.perf_counter()
-        gemm_s = sum(e[1].elapsed_time(e[2]) for e in events) * 1e-3 / steps
-        quant_s = sum(e[0].elapsed_time(e[1]) for e in events) * 1e-3 / steps
-        return w, d, (t1 - t0), gemm_s, quant_s
+        if copies == 1:
+            events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(steps):
+                step(i, events[i])
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            gemm_s = sum(e[1].elapsed_time(e[2]) for e in events) * 1e-3 / steps
+            quant_s = sum(e[0].elapsed_time(e[1]) for e in events) * 1e-3 / steps
+            return w, d, steps, (t1 - t0), gemm_s, quant_s
+
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            g_steps = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_steps, stream=side):
+                for i in range(copies):
+                    step(i)
+            g_gemm = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_gemm, stream=side):
+                for i in range(copies):
+                    fq.fq_w4a8_gemm(A_last, s_last, packs[i], gss[i], d["w_tscale"], w.N, out=Y)
+            g_quant = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g_quant, stream=side):
+                for i in range(copies):
+                    fq.fq_quantize_act(X)
+            reps = max(1, (steps + copies - 1) // copies)
+
+            def timed(graph):
+                graph.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                side.synchronize()
+                t0 = time.perf_counter()
+                e0.record(side)
+                for _ in range(reps):
+                    graph.replay()
+                e1.record(side)
+                side.synchronize()
+                t1 = time.perf_counter()
+                return t1 - t0, e0.elapsed_time(e1) * 1e-3
+
+            wall, _ = timed(g_steps)
+            _, gemm_all = timed(g_gemm)
+            _, quant_all = timed(g_quant)
+        torch.cuda.current_stream().wait_stream(side)
+        n = reps * copies
+        return w, d, n, wall, gemm_all / n, quant_all / n
 
     name = args.workload
     w0 = workloads.WORKLOADS[name]
     decode_like = w0.M <= 64
     steps = args.steps if args.steps is not None else (2000 if decode_like else 200)
     warmup = args.warmup if args.warmup is not None else (50 if decode_like else 20)
-    w, d, total_s, gemm_s, quant_s = run(name, steps, warmup, DECODE_COPIES if decode_like else 1)
+    w, d, steps, total_s, gemm_s, quant_s = run(name, steps, warmup, DECODE_COPIES if decode_like else 1)
 
     flop = 2.0 * w.M * w.N * w.K
     G = w.K // 128
@@ -120,12 +178,15 @@ def main() -> int:
         value = wbytes * steps / total_s / 1e9
         roof = {"bound": "hbm", "achieved": wbytes / gemm_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s"}
     else:
-        metric, unit = "W4A8 GEMM TFLOPS at M=%d" % w.M, "TFLOP/s"
+        metric = ("W4A8 GEMM TFLOPS (% FP8 MFMA peak) at M=2048; GB/s (% HBM) at M=16" if name == DEFAULT_WORKLOAD
+                  else "W4A8 GEMM TFLOPS at M=%d" % w.M)
+        unit = "TFLOP/s"
         value = flop * steps / total_s / 1e12
         roof = {"bound": "mfma", "achieved": flop / gemm_s / 1e12, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = _traffic_from_profiles(name)
-    roof["kernel"] = "fq_gemm_small_kernel" if decode_like else "fq_gemm_large_kernel"
+    roof["kernel"] = ("fq_gemm_small16_kernel" if w.M <= 16 else "fq_gemm_small_kernel") if decode_like \
+        else "fq_gemm_large_kernel"
     roof["kernel_us"] = gemm_s * 1e6
     roof["quantize_us"] = quant_s * 1e6
     roof["algorithmic_bytes"] = gemm_bytes
@@ -141,15 +202,15 @@ def main() -> int:
 
     if not decode_like and not args.no_decode:
         # second half of the metric: packed-weight GB/s at M = 16 against the HBM roofline
-        wd, dd, tot_d, gemm_d, _ = run("c5_decode_m16", 1500, 50, DECODE_COPIES)
+        wd, dd, n_d, tot_d, gemm_d, _ = run("c5_decode_m16", 1500, 50, DECODE_COPIES)
         wb = wd.N * wd.K / 2 + wd.N * (wd.K // 128)
-        out["decode_m16"] = {"workload": "c5_decode_m16", "kernel_us": gemm_d * 1e6,
+        out["decode_m16"] = {"workload": "c5_decode_m16", "kernel_us": gemm_d * 1e6, "step_us": tot_d / n_d * 1e6,
                              "weight_GBps": wb / gemm_d / 1e9, "frac_hbm": wb / gemm_d / 1e9 / PEAK_HBM_GBPS,
                              "weight_copies_rotated": DECODE_COPIES}
 
     if not args.no_cpu_baseline:
         import oracle
-        rows = min(w.M, 1024 if not decode_like else w.M)
+        rows = min(w.M, 2048)
         Xs = d["X_bf16"][:rows]
         c0 = time.perf_counter()
         A_ref, s_ref = oracle.quantize_act(Xs)

@@ -27,32 +27,44 @@
 namespace {
 
 typedef __attribute__((address_space(3))) void* fql_lds_ptr;
-typedef const __attribute__((address_space(1))) void* fql_glb_ptr;
 
 // LDS layout of one A stage (one 128-wide group of 256 rows): row-major, 8 slots of 16 bytes per
 // row; slot c of row r holds bytes 16*x .. 16*x+15 of the row's group with x = c ^ ((r >> 1) & 7).
 // The XOR makes the operand reads (lane = row, fixed x) hit 16 different bank groups per 16 lanes,
-// while the global->LDS transfer (global_load_lds_dwordx4, LDS address linear in the lane) still
+// while the global->LDS transfer (buffer_load_dwordx4 ... lds, LDS address linear in the lane) still
 // fetches whole 128-byte rows: 8 rows per instruction, 4 instructions per wave and stage.
-__device__ __forceinline__ void fql_issue_a(fq_v4i* lds_stage, const uint8_t* __restrict__ A, int M, int K,
-                                            int m0, int g) {
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+// Addressing: the buffer descriptor covers all of A, so rows past M read as zero; the per-lane
+// byte offset is fixed for the whole kernel (one register per transfer), the group travels in
+// the scalar offset.
+struct fql_a_addr {
+    unsigned v[4];                                        // byte offset of each of the 4 transfers
+};
+
+__device__ __forceinline__ fql_a_addr fql_a_setup(int wave, int lane, int m0, int K) {
+    const int row = wave * 32 + (lane >> 3);              // tile row of transfer 0
+    const int c0 = (lane & 7) ^ ((row >> 1) & 7);         // == (lane & 7) ^ (lane >> 4): wave*32 drops out
+    fql_a_addr a;
+    // (the bounds check of a buffer load looks at this per-lane offset only, not at the scalar
+    // offset, so the row must be part of it)
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-        const int row = wave * 32 + j * 8 + (lane >> 3);
-        const int x = (lane & 7) ^ ((row >> 1) & 7);
-        int grow = m0 + row;
-        grow = grow < M ? grow : M - 1;                   // rows past M are duplicates, never stored
-        const uint8_t* src = A + (size_t)grow * K + (size_t)g * FQ_GROUP + x * 16;
-        fq_v4i* dst = lds_stage + (wave * 32 + j * 8) * 8;    // wave-uniform; lane l lands at dst + l
-        __builtin_amdgcn_global_load_lds((fql_glb_ptr)src, (fql_lds_ptr)dst, 16, 0, 0);
-    }
+    for (int j = 0; j < 4; ++j)
+        a.v[j] = (unsigned)(m0 + row + 8 * j) * (unsigned)K + (unsigned)(c0 ^ (4 * (j & 1))) * 16u;
+    return a;
+}
+
+__device__ __forceinline__ void fql_issue_a(__amdgpu_buffer_rsrc_t rsrc, const fql_a_addr& a, fq_v4i* lds_stage,
+                                            int wave, int g) {
+    fq_v4i* dst = lds_stage + wave * 256;                 // this wave's 32 rows
+    const int sg = g * FQ_GROUP;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fql_lds_ptr)(dst + 64 * j), 16, a.v[j], sg, 0, 0);
 }
 
 // One group of this wave's packed weights (2 KiB: two halves of 64 lanes x 16 bytes) -> LDS.
-__device__ __forceinline__ void fql_issue_b(fq_v4i* dst, const uint8_t* __restrict__ src_lane) {
-    __builtin_amdgcn_global_load_lds((fql_glb_ptr)src_lane, (fql_lds_ptr)dst, 16, 0, 0);
-    __builtin_amdgcn_global_load_lds((fql_glb_ptr)(src_lane + 1024), (fql_lds_ptr)(dst + 64), 16, 0, 0);
+__device__ __forceinline__ void fql_issue_b(__amdgpu_buffer_rsrc_t rsrc, fq_v4i* dst, unsigned lane16, unsigned blk_off) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fql_lds_ptr)dst, 16, lane16, blk_off, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fql_lds_ptr)(dst + 64), 16, lane16, blk_off + 1024u, 0, 0);
 }
 
 // s_waitcnt immediate (gfx9 encoding) that waits until at most n vector-memory transfers are pending
@@ -73,14 +85,21 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
     const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K) {
     extern __shared__ fq_v4i lds[];                       // 4 A stages (128 KiB) + 8 x 4 KiB of packed weights
     const int G = K / FQ_GROUP;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     const int m0 = blockIdx.y * FQL_BM;
     const int nw0 = blockIdx.x * 256 + wave * 32;         // first output channel of this wave
     const bool wave_on = nw0 < N;                         // waves past N compute a duplicate tile and store nothing
     const int n = nw0 + (lane & 31);                      // this lane's output channel
     const bool n_ok = n < N;
     const int nt = wave_on ? (nw0 >> 5) : ((N - 1) >> 5);
-    const uint8_t* wblk = wp + fq_block_offset(nt, 0, G) + (size_t)lane * 16u;
+    const unsigned wblk = (unsigned)nt * (unsigned)G * 2048u;     // byte offset of this wave's block (nt, 0)
+    const unsigned lane16 = (unsigned)lane * 16u;
+    // buffer descriptors (raw, no stride): out-of-range bytes read as zero
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(A), 0, (int)((unsigned)M * (unsigned)K), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(wp), 0, (int)((unsigned)((N + 31) >> 5) * (unsigned)G * 2048u), 0x00020000);
+    const fql_a_addr aaddr = fql_a_setup(wave, lane, m0, K);
     const uint8_t* gsrow = gs + (size_t)(n_ok ? n : N - 1) * G;
 
     // operand read offsets (in chunks) of this lane inside a 32-row tile: (half h, part) -> slot
@@ -98,13 +117,13 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
     for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 
     // ---- prologue ----
-    fql_issue_a(lds, A, M, K, m0, 0);
-    fql_issue_a(lds + FQL_STAGE_CHUNKS, A, M, K, m0, G > 1 ? 1 : 0);
+    fql_issue_a(rsA, aaddr, lds, wave, 0);
+    fql_issue_a(rsA, aaddr, lds + FQL_STAGE_CHUNKS, wave, G > 1 ? 1 : 0);
     // Packed weights also travel global -> LDS directly, into two 2 KiB buffers private to the wave
     // ([half h][lane][16 bytes], the order they have in memory); buffer g & 1 holds group g.
     fq_v4i* wbuf = lds + FQL_STAGES * FQL_STAGE_CHUNKS + wave * 256;
-    fql_issue_b(wbuf, wblk);
-    fql_issue_b(wbuf + 128, wblk + (size_t)(G > 1 ? 1 : 0) * 2048u);
+    fql_issue_b(rsW, wbuf, lane16, wblk);
+    fql_issue_b(rsW, wbuf + 128, lane16, wblk + (G > 1 ? 2048u : 0u));
     unsigned psb[2];                                      // scale bytes in flight (group g+1, g+2)
     psb[0] = gsrow[0];
     psb[1] = gsrow[G > 1 ? 1 : 0];
@@ -122,19 +141,22 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
     // Two groups per barrier.  Every load is unconditional (group indices are clamped at G-1
     // instead of skipped; a clamped "ghost" group is multiplied by a zero scale).
     //
-    // The body is software-pipelined by hand, one step per MFMA: the step fetches the A operand of
-    // the next step from LDS, issues its MFMA, and fills the MFMA's shadow with half of the previous
-    // row tile's scale-accumulate (8 v_fma) and a share of the next group's unpack.  Scheduling
-    // barriers keep the compiler from undoing that order.
+    // The body is software-pipelined by hand, one step per 32x32 row tile: the two chained MFMAs of
+    // the tile are issued back to back, then the step fetches the A operands of the next tile from
+    // LDS and fills the MFMAs' shadow with the previous tile's scale-accumulate (16 v_fma) and an
+    // eighth of the next group's unpack.  Keeping the non-MFMA part of a step longer than one MFMA
+    // makes the two waves of a SIMD take turns on the matrix pipe instead of the older one hogging
+    // it.  Scheduling barriers keep the compiler from undoing that order.
     const int npairs = (G + 1) >> 1;
-    fq_v8i an = fql_join(lds[o00], lds[o01]);             // operand of the very first step
+    fq_v8i an0 = fql_join(lds[o00], lds[o01]);            // operands of the very first tile
+    fq_v8i an1 = fql_join(lds[o10], lds[o11]);
     for (int p = 0; p < npairs; ++p) {
         {   // A tiles of the next pair -> the two stages the previous pair used (8 transfers)
             const int ga = 2 * p + 2 < G ? 2 * p + 2 : G - 1;
             const int gb = 2 * p + 3 < G ? 2 * p + 3 : G - 1;
             fq_v4i* nx = lds + ((p + 1) & 1) * 2 * FQL_STAGE_CHUNKS;
-            fql_issue_a(nx, A, M, K, m0, ga);
-            fql_issue_a(nx + FQL_STAGE_CHUNKS, A, M, K, m0, gb);
+            fql_issue_a(rsA, aaddr, nx, wave, ga);
+            fql_issue_a(rsA, aaddr, nx + FQL_STAGE_CHUNKS, wave, gb);
         }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
@@ -145,7 +167,7 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
             const unsigned qs = psb[u ^ 1];
             {
                 const int g2 = g + 2 < G ? g + 2 : G - 1;
-                fql_issue_b(wbuf + u * 128, wblk + (size_t)g2 * 2048u);
+                fql_issue_b(rsW, wbuf + u * 128, lane16, wblk + (unsigned)g2 * 2048u);
                 psb[u] = gsrow[g2];
             }
             // Transfers requested after group g+1's: its scale byte, (first group of a pair) the 8 A
@@ -155,41 +177,42 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
             const fq_v4i* nxt = wbuf + (u ^ 1) * 128 + lane;
             const float s = sc[u];
             fq_v4i q = nxt[0];
-            fq_v16f pt;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int mt = 0; mt < 8; ++mt) {
                 const int tp = (mt + 7) & 7;
                 const float sp = (mt == 0) ? sprev : s;   // row tile 7 of the previous group used the old scale
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const fq_v8i ac = an;
-                    // A operand of the next step (none after the last step of a pair: the next
-                    // pair's stages are only complete after the barrier)
-                    if (h == 0) {
-                        an = fql_join(cur[mt * 256 + o10], cur[mt * 256 + o11]);
-                    } else if (mt < 7) {
-                        an = fql_join(cur[(mt + 1) * 256 + o00], cur[(mt + 1) * 256 + o01]);
-                    } else if (u == 0) {
-                        an = fql_join(cur[FQL_STAGE_CHUNKS + o00], cur[FQL_STAGE_CHUNKS + o01]);
-                    }
-                    if (h == 0) pt = FQ_MFMA(ac, b0[u], zero);
-                    else        pt = FQ_MFMA(ac, b1[u], pt);
-#pragma unroll
-                    for (int r = 8 * h; r < 8 * h + 8; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
-                    {   // one sixteenth of the next group's unpack: half a packed word
-                        const unsigned w = (unsigned)q[mt & 3];
-                        const unsigned x = (h == 0 ? w : (w >> 4)) & 0x0F0F0F0Fu;
-                        const int e = (int)fq_codes_to_e4m3x4(x);
-                        if (mt < 4) b0[u ^ 1][4 * h + (mt & 3)] = e;
-                        else        b1[u ^ 1][4 * h + (mt & 3)] = e;
-                    }
-                    if (mt == 3 && h == 1) q = nxt[64];
-                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // the two LDS reads
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // the MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);  // its shadow: VALU work
-                    __builtin_amdgcn_sched_barrier(0);
+                const fq_v8i ac0 = an0, ac1 = an1;
+                fq_v16f pt = FQ_MFMA(ac0, b0[u], zero);
+                __builtin_amdgcn_s_setprio(1);            // mid-chain: win the pipe over a wave that is starting a tile
+                pt = FQ_MFMA(ac1, b1[u], pt);
+                __builtin_amdgcn_s_setprio(0);
+                // A operands of the next tile (none after the last tile of a pair: the next pair's
+                // stages are only complete after the barrier)
+                if (mt < 7) {
+                    an0 = fql_join(cur[(mt + 1) * 256 + o00], cur[(mt + 1) * 256 + o01]);
+                    an1 = fql_join(cur[(mt + 1) * 256 + o10], cur[(mt + 1) * 256 + o11]);
+                } else if (u == 0) {
+                    an0 = fql_join(cur[FQL_STAGE_CHUNKS + o00], cur[FQL_STAGE_CHUNKS + o01]);
+                    an1 = fql_join(cur[FQL_STAGE_CHUNKS + o10], cur[FQL_STAGE_CHUNKS + o11]);
                 }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
+                {   // one eighth of the next group's unpack: one packed word
+                    const unsigned w = (unsigned)q[mt & 3];
+                    const int lo = (int)fq_codes_to_e4m3x4(w & 0x0F0F0F0Fu);
+                    const int hi = (int)fq_codes_to_e4m3x4((w >> 4) & 0x0F0F0F0Fu);
+                    if (mt < 4) { b0[u ^ 1][mt & 3] = lo; b0[u ^ 1][4 + (mt & 3)] = hi; }
+                    else        { b1[u ^ 1][mt & 3] = lo; b1[u ^ 1][4 + (mt & 3)] = hi; }
+                }
+                if (mt == 3) q = nxt[64];
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA, raise priority,
+                __builtin_amdgcn_sched_group_barrier(0x004, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA, lower priority
+                __builtin_amdgcn_sched_group_barrier(0x004, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);   // LDS reads for the next tile
+                __builtin_amdgcn_sched_group_barrier(0x002, 32, 0);  // the MFMAs' shadow: VALU work
+                __builtin_amdgcn_sched_barrier(0);
                 pprev = pt;
             }
             sprev = s;
@@ -201,7 +224,8 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
         __syncthreads();
         {
             const fq_v4i* nxs = lds + ((p + 1) & 1) * 2 * FQL_STAGE_CHUNKS;
-            an = fql_join(nxs[o00], nxs[o01]);
+            an0 = fql_join(nxs[o00], nxs[o01]);
+            an1 = fql_join(nxs[o10], nxs[o11]);
         }
     }
     // last pending tile (row tile 7 of the last group)
