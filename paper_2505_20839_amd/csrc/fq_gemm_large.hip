@@ -4,23 +4,39 @@
 // into a rounded FP8 table but applied exactly, in FP32, to each group's partial sum; all output
 // scaling is FP32 with a single rounding to bf16.
 //
-// Work split.  A workgroup of 8 waves owns a 256 x (32*NW*...) output tile; wave w owns 32
-// output channels and all 256 rows (8 MFMA tiles of 32x32), so every weight is unpacked exactly
-// once per workgroup and each unpacked operand is reused by 8 row tiles.  Per 128-wide group g:
+// Work split.  A workgroup of 4 waves owns one output tile of 256 (or 128) rows x 128 channels;
+// wave w owns 32 channels and all rows of the tile (NMT = 8 or 4 MFMA tiles of 32x32), so every
+// weight is unpacked exactly once per workgroup and each unpacked operand is reused by all row tiles.
+// Two workgroups share a compute unit (80 KiB of LDS and one wave per SIMD each): the two waves of
+// a SIMD belong to different workgroups, so no barrier couples them, and one workgroup's prologue,
+// epilogue and load stalls are covered by the other's MFMAs.
+// Per 128-wide group g:
 //     P   = A[:, g, first 64] * Wq[g, first 64]            v_mfma_f32_32x32x64_f8f6f4, C = 0
 //     P  += A[:, g, last 64]  * Wq[g, last 64]             same, C = P
 //     acc += e4m3(gscale[n, g]) * P                        16 v_fma_f32 per 32x32 tile
-// A tiles go global -> LDS directly (global_load_lds_dwordx4, four stages of 32 KiB, two groups per
-// barrier); packed weights go global -> registers (each wave reads only its own 32 channels) and
-// are unpacked one group ahead, a slice under each pair of MFMAs.
+// A tiles go global -> LDS directly (buffer_load_dwordx4 ... lds, two stages of 32 KiB, one group
+// per barrier); packed weights go global -> LDS the same way (2 x 2 KiB private to each wave) and
+// are unpacked one group ahead, a slice under each MFMA.
+//
+// Tile order.  Workgroup b runs on XCD b % 8 (round-robin dispatch); each XCD gets a contiguous
+// range of tiles in an order that walks panels of 4 row tiles, row tile fastest, so the workgroups
+// an XCD runs at one time cover a few row tiles x a few channel tiles and share them in its L2.
+// The tiles an XCD cannot fill a whole round of its slots with are cut into two 128-row halves and
+// run by a second launch of the NMT = 4 variant, so that the last round keeps all units busy for
+// half the time.
 #include "fq_common.h"
 #include "fq_kernels.h"
 
-#define FQL_THREADS 512
+#define FQL_WAVES 4
+#define FQL_THREADS (64 * FQL_WAVES)
 #define FQL_BM 256
+#define FQL_BN (32 * FQL_WAVES)
 #define FQL_STAGE_BYTES (FQL_BM * FQ_GROUP)          // 32 KiB: 256 rows x 128 E4M3 bytes
 #define FQL_STAGE_CHUNKS (FQL_STAGE_BYTES / 16)
-#define FQL_STAGES 4                                 // two pairs of groups: one in use, one in flight
+#define FQL_STAGES 2                                 // one group in use, one in flight
+#define FQL_LDS_BYTES (FQL_STAGES * FQL_STAGE_BYTES + FQL_WAVES * 4096)   // 80 KiB: two workgroups per CU
+#define FQL_OUT_STRIDE (FQL_BN * 2 + 16)             // bytes per row of the output tile staged in LDS
+#define FQL_XCDS 8
 
 #define FQ_MFMA(a, b, c) __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4((a), (b), (c), 0, 0, 0, 0, 0, 0)
 
@@ -28,37 +44,33 @@ namespace {
 
 typedef __attribute__((address_space(3))) void* fql_lds_ptr;
 
-// LDS layout of one A stage (one 128-wide group of 256 rows): row-major, 8 slots of 16 bytes per
+// LDS layout of one A stage (one 128-wide group of up to 256 rows): row-major, 8 slots of 16 bytes per
 // row; slot c of row r holds bytes 16*x .. 16*x+15 of the row's group with x = c ^ ((r >> 1) & 7).
 // The XOR makes the operand reads (lane = row, fixed x) hit 16 different bank groups per 16 lanes,
 // while the global->LDS transfer (buffer_load_dwordx4 ... lds, LDS address linear in the lane) still
-// fetches whole 128-byte rows: 8 rows per instruction, 4 instructions per wave and stage.
-// Addressing: the buffer descriptor covers all of A, so rows past M read as zero; the per-lane
-// byte offset is fixed for the whole kernel (one register per transfer), the group travels in
-// the scalar offset.
-struct fql_a_addr {
-    unsigned v[4];                                        // byte offset of each of the 4 transfers
-};
-
-__device__ __forceinline__ fql_a_addr fql_a_setup(int wave, int lane, int m0, int K) {
-    const int row = wave * 32 + (lane >> 3);              // tile row of transfer 0
-    const int c0 = (lane & 7) ^ ((row >> 1) & 7);         // == (lane & 7) ^ (lane >> 4): wave*32 drops out
-    fql_a_addr a;
-    // (the bounds check of a buffer load looks at this per-lane offset only, not at the scalar
-    // offset, so the row must be part of it)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-        a.v[j] = (unsigned)(m0 + row + 8 * j) * (unsigned)K + (unsigned)(c0 ^ (4 * (j & 1))) * 16u;
-    return a;
+// fetches whole 128-byte rows: 8 rows per instruction.
+// Addressing: the buffer descriptor covers all of A, so rows past M read as zero.  The bounds
+// check of a buffer load looks at the per-lane offset only, so the row is part of that offset
+// (a per-lane constant plus a scalar term per transfer); the group travels in the scalar offset.
+// A tile of 32 * NMT rows is fetched by the 4 waves: NT = NMT transfers of 8 rows per wave and group.
+// Per-lane byte offset of transfer 0 without the tile's first row (that part is scalar):
+__device__ __forceinline__ unsigned fql_a_lane_base(int wave, int lane, int K, int nt) {
+    const int row = wave * (8 * nt) + (lane >> 3);        // tile row of transfer 0
+    const int c0 = (lane & 7) ^ ((row >> 1) & 7);         // == (lane & 7) ^ (lane >> 4): the wave's term drops out
+    return (unsigned)row * (unsigned)K + (unsigned)c0 * 16u;
 }
 
-__device__ __forceinline__ void fql_issue_a(__amdgpu_buffer_rsrc_t rsrc, const fql_a_addr& a, fq_v4i* lds_stage,
-                                            int wave, int g) {
-    fq_v4i* dst = lds_stage + wave * 256;                 // this wave's 32 rows
+template <int NT>
+__device__ __forceinline__ void fql_issue_a(__amdgpu_buffer_rsrc_t rsrc, unsigned abase, int m0, int K,
+                                            fq_v4i* lds_stage, int wave, int g) {
+    fq_v4i* dst = lds_stage + wave * (64 * NT);           // this wave's 8 * NT rows
     const int sg = g * FQ_GROUP;
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fql_lds_ptr)(dst + 64 * j), 16, a.v[j], sg, 0, 0);
+    for (int j = 0; j < NT; ++j) {
+        // odd transfers start 8 rows further, where the swizzle flips bit 2 of the column
+        const unsigned v = (abase ^ ((j & 1) ? 64u : 0u)) + (unsigned)(m0 + 8 * j) * (unsigned)K;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fql_lds_ptr)(dst + 64 * j), 16, v, sg, 0, 0);
+    }
 }
 
 // One group of this wave's packed weights (2 KiB: two halves of 64 lanes x 16 bytes) -> LDS.
@@ -78,16 +90,58 @@ __device__ __forceinline__ fq_v8i fql_join(fq_v4i lo, fq_v4i hi) {
     return r;
 }
 
+// Tiles of XCD x: [lo, lo + count) of the row-tile-fastest order; the first `nfull` are run whole
+// by the first launch, the rest as halves by the second.
+struct fql_split {
+    int lo, nfull, nhalf;                                 // nhalf = number of 128-row items (2 per tile)
+};
+
+__host__ __device__ inline fql_split fql_xcd_split(int x, int ntiles, int slots) {
+    const int base = ntiles / FQL_XCDS, rem = ntiles % FQL_XCDS;
+    const int count = base + (x < rem ? 1 : 0);
+    fql_split sp;
+    sp.lo = x * base + (x < rem ? x : rem);
+    const int r = count % slots;                          // tiles of the last, partial round
+    if (r > 0 && 2 * r <= slots) { sp.nfull = count - r; sp.nhalf = 2 * r; }
+    else                         { sp.nfull = count;     sp.nhalf = 0; }
+    return sp;
+}
+
 }  // namespace
 
-__global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
+template <int NMT>                                        // row tiles of 32 rows per item: 8, or 4 for the half tiles
+__global__ __launch_bounds__(FQL_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void fq_gemm_large_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
-    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K) {
-    extern __shared__ fq_v4i lds[];                       // 4 A stages (128 KiB) + 8 x 4 KiB of packed weights
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
+    int tiles_m, int tiles_n, int slots, int pm) {
+    extern __shared__ fq_v4i lds[];                       // 2 A stages (64 KiB) + 4 x 4 KiB of packed weights
+    constexpr int NT = NMT;                               // A transfers per wave and stage
     const int G = K / FQ_GROUP;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    const int m0 = blockIdx.y * FQL_BM;
-    const int nw0 = blockIdx.x * 256 + wave * 32;         // first output channel of this wave
+    // which item: XCD x = blockIdx.x % 8, j-th item of that XCD's list for this launch
+    int m0, n0;
+    {
+        const int x = blockIdx.x % FQL_XCDS, j = blockIdx.x / FQL_XCDS;
+        const fql_split sp = fql_xcd_split(x, tiles_m * tiles_n, slots);
+        int t, half = 0;
+        if (NMT == 8) {
+            if (j >= sp.nfull) return;
+            t = sp.lo + j;
+        } else {
+            if (j >= sp.nhalf) return;
+            t = sp.lo + sp.nfull + (j >> 1);
+            half = j & 1;
+        }
+        // tile order: panels of `pm` row tiles; inside a panel row tile fastest, then channel tile
+        const int per_panel = pm * tiles_n;
+        const int panel = t / per_panel, rem = t - panel * per_panel;
+        const int ph = tiles_m - panel * pm < pm ? tiles_m - panel * pm : pm;   // row tiles of this panel
+        const int tn = rem / ph, tm = panel * pm + (rem - tn * ph);
+        m0 = tm * FQL_BM + half * 128;
+        n0 = tn * FQL_BN;
+    }
+    const int nw0 = n0 + wave * 32;                       // first output channel of this wave
     const bool wave_on = nw0 < N;                         // waves past N compute a duplicate tile and store nothing
     const int n = nw0 + (lane & 31);                      // this lane's output channel
     const bool n_ok = n < N;
@@ -99,7 +153,7 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
         const_cast<uint8_t*>(A), 0, (int)((unsigned)M * (unsigned)K), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(wp), 0, (int)((unsigned)((N + 31) >> 5) * (unsigned)G * 2048u), 0x00020000);
-    const fql_a_addr aaddr = fql_a_setup(wave, lane, m0, K);
+    const unsigned abase = fql_a_lane_base(wave, lane, K, NT);
     const uint8_t* gsrow = gs + (size_t)(n_ok ? n : N - 1) * G;
 
     // operand read offsets (in chunks) of this lane inside a 32-row tile: (half h, part) -> slot
@@ -107,9 +161,9 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
     const int o00 = r32 * 8 + ((2 * (lane >> 5)) ^ sw);   // h = 0, bytes 0..15 of the lane's 32
     const int o01 = o00 ^ 1, o10 = o00 ^ 4, o11 = o00 ^ 5;
 
-    fq_v16f acc[8];
+    fq_v16f acc[NMT];
 #pragma unroll
-    for (int t = 0; t < 8; ++t)
+    for (int t = 0; t < NMT; ++t)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
     fq_v16f zero;
@@ -117,8 +171,7 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
     for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 
     // ---- prologue ----
-    fql_issue_a(rsA, aaddr, lds, wave, 0);
-    fql_issue_a(rsA, aaddr, lds + FQL_STAGE_CHUNKS, wave, G > 1 ? 1 : 0);
+    fql_issue_a<NT>(rsA, abase, m0, K, lds, wave, 0);
     // Packed weights also travel global -> LDS directly, into two 2 KiB buffers private to the wave
     // ([half h][lane][16 bytes], the order they have in memory); buffer g & 1 holds group g.
     fq_v4i* wbuf = lds + FQL_STAGES * FQL_STAGE_CHUNKS + wave * 256;
@@ -138,30 +191,26 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
 
     fq_v16f pprev = zero;                                 // partial sums of the previous row tile
     float sprev = 0.f;                                    // and their group scale
-    // Two groups per barrier.  Every load is unconditional (group indices are clamped at G-1
-    // instead of skipped; a clamped "ghost" group is multiplied by a zero scale).
+    // One group per barrier, unrolled by two so that the register pairs [u] / [u^1] are static.
+    // Every load is unconditional (group indices are clamped at G-1 instead of skipped; a clamped
+    // "ghost" group is multiplied by a zero scale).
     //
-    // The body is software-pipelined by hand, one step per 32x32 row tile: the two chained MFMAs of
-    // the tile are issued back to back, then the step fetches the A operands of the next tile from
-    // LDS and fills the MFMAs' shadow with the previous tile's scale-accumulate (16 v_fma) and an
-    // eighth of the next group's unpack.  Keeping the non-MFMA part of a step longer than one MFMA
-    // makes the two waves of a SIMD take turns on the matrix pipe instead of the older one hogging
-    // it.  Scheduling barriers keep the compiler from undoing that order.
+    // The body is software-pipelined by hand, one step per MFMA: the step fetches the A operand of
+    // the next step from LDS, issues its MFMA, and fills the MFMA's shadow with half of the previous
+    // row tile's scale-accumulate (8 v_fma) and a share of the next group's unpack.  Scheduling
+    // barriers keep the compiler from undoing that order.
     const int npairs = (G + 1) >> 1;
-    fq_v8i an0 = fql_join(lds[o00], lds[o01]);            // operands of the very first tile
-    fq_v8i an1 = fql_join(lds[o10], lds[o11]);
+    fq_v8i an = fql_join(lds[o00], lds[o01]);             // operand of the very first step
     for (int p = 0; p < npairs; ++p) {
-        {   // A tiles of the next pair -> the two stages the previous pair used (8 transfers)
-            const int ga = 2 * p + 2 < G ? 2 * p + 2 : G - 1;
-            const int gb = 2 * p + 3 < G ? 2 * p + 3 : G - 1;
-            fq_v4i* nx = lds + ((p + 1) & 1) * 2 * FQL_STAGE_CHUNKS;
-            fql_issue_a(rsA, aaddr, nx, wave, ga);
-            fql_issue_a(rsA, aaddr, nx + FQL_STAGE_CHUNKS, wave, gb);
-        }
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int g = 2 * p + u;
-            const fq_v4i* cur = lds + ((p & 1) * 2 + u) * FQL_STAGE_CHUNKS;
+            const fq_v4i* cur = lds + u * FQL_STAGE_CHUNKS;
+            {   // A tile of the next group -> the stage the previous group used (all waves are past
+                // the barrier that ended it)
+                const int g1 = g + 1 < G ? g + 1 : G - 1;
+                fql_issue_a<NT>(rsA, abase, m0, K, lds + (u ^ 1) * FQL_STAGE_CHUNKS, wave, g1);
+            }
             // Group g+1 sits in buffer u^1 (requested one group ago) and is unpacked slice by slice
             // under the MFMAs below; buffer u (group g, already unpacked) is refilled with group g+2.
             const unsigned qs = psb[u ^ 1];
@@ -170,49 +219,49 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
                 fql_issue_b(rsW, wbuf + u * 128, lane16, wblk + (unsigned)g2 * 2048u);
                 psb[u] = gsrow[g2];
             }
-            // Transfers requested after group g+1's: its scale byte, (first group of a pair) the 8 A
-            // transfers, and the 3 just above -> once at most that many are pending, g+1 has landed.
-            if (u == 0) __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(11));
-            else        __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(3));
+            // Transfers requested after group g+1's weights and scale byte: the NT A transfers and the
+            // 3 just above -> once at most that many are pending, g+1 has landed.
+            __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(NT + 3));
             const fq_v4i* nxt = wbuf + (u ^ 1) * 128 + lane;
             const float s = sc[u];
-            fq_v4i q = nxt[0];
+            fq_v4i q = nxt[0];                            // packed words 0..3; 4..7 are fetched half-way
+            fq_v16f pt;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int mt = 0; mt < 8; ++mt) {
-                const int tp = (mt + 7) & 7;
-                const float sp = (mt == 0) ? sprev : s;   // row tile 7 of the previous group used the old scale
-                const fq_v8i ac0 = an0, ac1 = an1;
-                fq_v16f pt = FQ_MFMA(ac0, b0[u], zero);
-                __builtin_amdgcn_s_setprio(1);            // mid-chain: win the pipe over a wave that is starting a tile
-                pt = FQ_MFMA(ac1, b1[u], pt);
-                __builtin_amdgcn_s_setprio(0);
-                // A operands of the next tile (none after the last tile of a pair: the next pair's
-                // stages are only complete after the barrier)
-                if (mt < 7) {
-                    an0 = fql_join(cur[(mt + 1) * 256 + o00], cur[(mt + 1) * 256 + o01]);
-                    an1 = fql_join(cur[(mt + 1) * 256 + o10], cur[(mt + 1) * 256 + o11]);
-                } else if (u == 0) {
-                    an0 = fql_join(cur[FQL_STAGE_CHUNKS + o00], cur[FQL_STAGE_CHUNKS + o01]);
-                    an1 = fql_join(cur[FQL_STAGE_CHUNKS + o10], cur[FQL_STAGE_CHUNKS + o11]);
-                }
+            for (int mt = 0; mt < NMT; ++mt) {
+                const int tp = (mt + NMT - 1) % NMT;
+                const float sp = (mt == 0) ? sprev : s;   // the last row tile of the previous group used the old scale
 #pragma unroll
-                for (int r = 0; r < 16; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
-                {   // one eighth of the next group's unpack: one packed word
-                    const unsigned w = (unsigned)q[mt & 3];
-                    const int lo = (int)fq_codes_to_e4m3x4(w & 0x0F0F0F0Fu);
-                    const int hi = (int)fq_codes_to_e4m3x4((w >> 4) & 0x0F0F0F0Fu);
-                    if (mt < 4) { b0[u ^ 1][mt & 3] = lo; b0[u ^ 1][4 + (mt & 3)] = hi; }
-                    else        { b1[u ^ 1][mt & 3] = lo; b1[u ^ 1][4 + (mt & 3)] = hi; }
+                for (int h = 0; h < 2; ++h) {
+                    const fq_v8i ac = an;
+                    // A operand of the next step (none after the last step of a group: the next
+                    // stage is only complete after the barrier)
+                    if (h == 0) {
+                        an = fql_join(cur[mt * 256 + o10], cur[mt * 256 + o11]);
+                    } else if (mt + 1 < NMT) {
+                        an = fql_join(cur[(mt + 1) * 256 + o00], cur[(mt + 1) * 256 + o01]);
+                    }
+                    if (h == 0) pt = FQ_MFMA(ac, b0[u], zero);
+                    else        pt = FQ_MFMA(ac, b1[u], pt);
+#pragma unroll
+                    for (int r = 8 * h; r < 8 * h + 8; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
+                    // a share of the next group's unpack: half a packed word per step with 8 row
+                    // tiles, a whole word's half twice with 4
+#pragma unroll
+                    for (int e = 0; e < 8 / NMT; ++e) {
+                        const int slot = (8 / NMT) * mt + e;                    // packed word 0..7
+                        const unsigned w = (unsigned)q[slot & 3];
+                        const unsigned x = (h == 0 ? w : (w >> 4)) & 0x0F0F0F0Fu;
+                        const int ev = (int)fq_codes_to_e4m3x4(x);
+                        if (slot < 4) b0[u ^ 1][4 * h + (slot & 3)] = ev;
+                        else          b1[u ^ 1][4 * h + (slot & 3)] = ev;
+                    }
+                    if (mt == NMT / 2 - 1 && h == 1) q = nxt[64];
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);   // the two LDS reads
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // the MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);  // its shadow: VALU work
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                if (mt == 3) q = nxt[64];
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA, raise priority,
-                __builtin_amdgcn_sched_group_barrier(0x004, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);   // MFMA, lower priority
-                __builtin_amdgcn_sched_group_barrier(0x004, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x100, 5, 0);   // LDS reads for the next tile
-                __builtin_amdgcn_sched_group_barrier(0x002, 32, 0);  // the MFMAs' shadow: VALU work
-                __builtin_amdgcn_sched_barrier(0);
                 pprev = pt;
             }
             sprev = s;
@@ -220,74 +269,73 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
                 const float t = __builtin_amdgcn_cvt_f32_fp8((int)qs, 0);
                 sc[u ^ 1] = (g + 1 < G) ? t : 0.f;
             }
-        }
-        __syncthreads();
-        {
-            const fq_v4i* nxs = lds + ((p + 1) & 1) * 2 * FQL_STAGE_CHUNKS;
-            an0 = fql_join(nxs[o00], nxs[o01]);
-            an1 = fql_join(nxs[o10], nxs[o11]);
+            // the next group's A tile: this wave's part has landed once only the 3 transfers issued
+            // after it are pending; the barrier then vouches for the other waves' parts
+            __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(3));
+            __syncthreads();
+            {
+                const fq_v4i* nxs = lds + (u ^ 1) * FQL_STAGE_CHUNKS;
+                an = fql_join(nxs[o00], nxs[o01]);
+            }
         }
     }
-    // last pending tile (row tile 7 of the last group)
+    // last pending row tile of the last group
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[7][r] = fmaf(sprev, pprev[r], acc[7][r]);
+    for (int r = 0; r < 16; ++r) acc[NMT - 1][r] = fmaf(sprev, pprev[r], acc[NMT - 1][r]);
 
     // ---- epilogue: per-token and per-tensor factors, one rounding to bf16, store ----
-    // The stages are free now: bytes [0, 67584) become the output tile, [67584, 68608) the row factors.
-    float* osc = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + 128 * 528);
-    if (threadIdx.x < FQL_BM) {                           // x 2^9: the weights were fed as q * 2^-9
-        int m = m0 + threadIdx.x;
-        osc[threadIdx.x] = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);
+    // Every wave is past the last barrier, so the stages are free; the output tile also covers part
+    // of the weight buffers, so the (ghost) weight transfers still in flight must land first.  The
+    // first 32 * NMT * FQL_OUT_STRIDE bytes become the output tile, 1 KiB behind the largest tile
+    // holds the row factors.
+    __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
+    float* osc = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + FQL_BM * FQL_OUT_STRIDE);
+    for (int i = threadIdx.x; i < 32 * NMT; i += FQL_THREADS) {   // x 2^9: the weights were fed as q * 2^-9
+        int m = m0 + i;
+        osc[i] = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);
     }
     __syncthreads();
-    const int nblk = blockIdx.x * 256;
-    const bool full_tile = (m0 + FQL_BM <= M) && (nblk + 256 <= N) && ((N & 7) == 0);
+    const bool full_tile = (m0 + 32 * NMT <= M) && (n0 + FQL_BN <= N) && ((N & 7) == 0);
     if (full_tile) {
-        // Transpose through LDS so that every store instruction writes whole 512-byte rows.
-        // Tile of 128 rows x 256 bf16, row stride 528 bytes; two passes (row tiles 0-3, 4-7).
+        // Transpose through LDS so that every store instruction writes whole 256-byte rows.
+        // Registers r, r+1 of a lane are rows rl, rl+1 of its column: one v_cvt_pk_bf16_f32 rounds
+        // both, and the two halves go to their rows with 16-bit LDS writes.
         char* tile = reinterpret_cast<char*>(lds);
-        const int colb = (wave * 32 + (lane & 31)) * 2;   // byte offset of this lane's column
+        char* wcol = tile + 4 * (lane >> 5) * FQL_OUT_STRIDE + (wave * 32 + (lane & 31)) * 2;
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            if (half) __syncthreads();                    // readers of the first pass are done
+        for (int mt = 0; mt < NMT; ++mt) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int mt = half * 4 + t;
+            for (int j = 0; j < 4; ++j) {                 // rows 8j + 4*(lane/32) + 0..3 of the 32x32 tile
+                const int rl = 8 * j + 4 * (lane >> 5);
+                const fq_v4f sc4 = *reinterpret_cast<const fq_v4f*>(&osc[mt * 32 + rl]);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {             // rows 8j + 4*(lane/32) + 0..3 of the 32x32 tile
-                    const int rl = 8 * j + 4 * (lane >> 5);
-                    fq_v4f sc = *reinterpret_cast<const fq_v4f*>(&osc[mt * 32 + rl]);
-#pragma unroll
-                    for (int e = 0; e < 4; e += 2) {
-                        float f0 = acc[mt][4 * j + e] * sc[e];          // row rl + e
-                        float f1 = acc[mt][4 * j + e + 1] * sc[e + 1];  // row rl + e + 1
-                        // lanes pair up: the even lane keeps row rl+e (its column and the next),
-                        // the odd lane keeps row rl+e+1 (the previous column and its own)
-                        float send = (lane & 1) ? f0 : f1;
-                        float got = __int_as_float(__builtin_amdgcn_update_dpp(
-                            0, __float_as_int(send), 0xB1, 0xF, 0xF, false));
-                        fq_v2f pr = (lane & 1) ? (fq_v2f){got, f1} : (fq_v2f){f0, got};
-                        fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
-                        const int row = t * 32 + rl + e + (lane & 1);
-                        *reinterpret_cast<fq_v2bf*>(tile + row * 528 + (colb & ~3)) = pk;
-                    }
+                for (int e = 0; e < 4; e += 2) {
+                    const fq_v2f pr = {acc[mt][4 * j + e] * sc4[e], acc[mt][4 * j + e + 1] * sc4[e + 1]};
+                    const unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, fq_v2bf));
+                    char* dst = wcol + (mt * 32 + 8 * j + e) * FQL_OUT_STRIDE;
+                    *reinterpret_cast<unsigned short*>(dst) = (unsigned short)pk;
+                    *reinterpret_cast<unsigned short*>(dst + FQL_OUT_STRIDE) = (unsigned short)(pk >> 16);
                 }
             }
-            __syncthreads();
+        }
+        __syncthreads();
+        // wave w stores rows 8*NMT*w ..., four rows of 256 bytes per instruction; the row steps
+        // travel in the scalar offset of the buffer store
+        const __amdgpu_buffer_rsrc_t rsY = __builtin_amdgcn_make_buffer_rsrc(
+            Y + (size_t)(m0 + wave * (8 * NMT)) * N + n0, 0, (int)((unsigned)(8 * NMT) * (unsigned)N * 2u), 0x00020000);
+        const unsigned ylane = (unsigned)(lane >> 4) * (unsigned)N * 2u + (unsigned)(lane & 15) * 16u;
+        const char* rd = tile + (wave * (8 * NMT) + (lane >> 4)) * FQL_OUT_STRIDE + (lane & 15) * 16;
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {                 // wave w stores rows 16w .. 16w+15, two per instruction
-                const int row = wave * 16 + 2 * j + (lane >> 5);
-                fq_v4i v = *reinterpret_cast<const fq_v4i*>(tile + row * 528 + (lane & 31) * 16);
-                const size_t m = (size_t)(m0 + half * 128 + row);
-                *reinterpret_cast<fq_v4i*>(Y + m * N + nblk + (lane & 31) * 8) = v;
-            }
+        for (int j = 0; j < 2 * NMT; ++j) {
+            const fq_v4i v = *reinterpret_cast<const fq_v4i*>(rd + 4 * j * FQL_OUT_STRIDE);
+            __builtin_amdgcn_raw_buffer_store_b128(v, rsY, ylane, 4 * j * N * 2, 0);
         }
         return;
     }
     // ragged tile: element-wise stores with bounds checks
     if (!wave_on || !n_ok) return;
 #pragma unroll
-    for (int mt = 0; mt < 8; ++mt) {
+    for (int mt = 0; mt < NMT; ++mt) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
             int ml = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -303,13 +351,32 @@ __global__ __launch_bounds__(FQL_THREADS) void fq_gemm_large_kernel(
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
     static bool attr_set = false;
-    const int lds_bytes = FQL_STAGES * FQL_STAGE_BYTES + 8 * 4096;
+    static int cus = 256;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel<8>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel<4>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
+        int dev = 0;
+        if (hipGetDevice(&dev) == hipSuccess)
+            (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         attr_set = true;
     }
-    dim3 grid((unsigned)((N + 255) / 256), (unsigned)((M + FQL_BM - 1) / FQL_BM));
-    hipLaunchKernelGGL(fq_gemm_large_kernel, grid, dim3(FQL_THREADS), lds_bytes, stream,
-                       A, a_scale, wp, gs, tscale, Y, M, N, K);
+    const int tiles_m = (M + FQL_BM - 1) / FQL_BM, tiles_n = (N + FQL_BN - 1) / FQL_BN;
+    int slots = 2 * cus / FQL_XCDS;                       // resident workgroups per XCD: two per compute unit
+    if (slots < 1) slots = 1;
+    int pm = 4;                                           // row tiles per panel: an XCD's 64 resident tiles then span
+    if (pm > tiles_m) pm = tiles_m;                       // 4 row tiles x 16 channel tiles, 4 MiB of A and of W at K = 4096
+    int max_full = 0, max_half = 0;
+    for (int x = 0; x < FQL_XCDS; ++x) {
+        const fql_split sp = fql_xcd_split(x, tiles_m * tiles_n, slots);
+        max_full = sp.nfull > max_full ? sp.nfull : max_full;
+        max_half = sp.nhalf > max_half ? sp.nhalf : max_half;
+    }
+    if (max_full > 0)
+        hipLaunchKernelGGL(fq_gemm_large_kernel<8>, dim3((unsigned)(max_full * FQL_XCDS)), dim3(FQL_THREADS),
+                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm);
+    if (max_half > 0)
+        hipLaunchKernelGGL(fq_gemm_large_kernel<4>, dim3((unsigned)(max_half * FQL_XCDS)), dim3(FQL_THREADS),
+                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm);
 }
