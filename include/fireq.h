@@ -32,7 +32,8 @@ enum {
     FQ_ERR_NULL   = -1,  /* a required pointer is NULL                                        */
     FQ_ERR_SHAPE  = -2,  /* negative size, K == 0, K % 128 != 0, N == 0 with M > 0            */
     FQ_ERR_ALIGN  = -3,  /* a base pointer is not 16-byte aligned                             */
-    FQ_ERR_LAUNCH = -4   /* the HIP runtime reported an error when the kernel was launched    */
+    FQ_ERR_LAUNCH = -4,  /* the HIP runtime reported an error when the kernel was launched    */
+    FQ_ERR_MEMORY = -5   /* the library could not allocate its device scratch buffer          */
 };
 
 #define FQ_GROUP 128     /* weights along K share one E4M3 scale per 128 (Sec. 3.1)           */

@@ -38,6 +38,7 @@ const char* fq_status_string(int status) {
         case FQ_ERR_SHAPE: return "invalid shape (sizes must be non-negative, K a positive multiple of 128)";
         case FQ_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
         case FQ_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
+        case FQ_ERR_MEMORY: return "the library could not allocate its device scratch buffer";
         default: return "unknown status";
     }
 }
@@ -90,7 +91,12 @@ int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_p
     switch (k) {
         case GemmKernel::Simple: fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
         case GemmKernel::Small:  fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
-        default:                 fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
+        default:
+            if (fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s) != 0) {
+                (void)hipGetLastError();
+                return FQ_ERR_MEMORY;
+            }
+            break;
     }
     return after_launch();
 }

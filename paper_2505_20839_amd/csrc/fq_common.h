@@ -4,7 +4,7 @@
 #include <stdint.h>
 
 #define FQ_GROUP 128
-#define FQ_LAYOUT_VERSION 1
+#define FQ_LAYOUT_VERSION 2
 
 typedef int   fq_v4i  __attribute__((ext_vector_type(4)));
 typedef int   fq_v8i  __attribute__((ext_vector_type(8)));
@@ -15,7 +15,7 @@ typedef float fq_v2f  __attribute__((ext_vector_type(2)));
 typedef __bf16 fq_v2bf __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------------------------
-// Packed weight layout (version 1), made for the B operand of v_mfma_f32_32x32x64_f8f6f4.
+// Packed weight layout (version 2), made for the B operand of v_mfma_f32_32x32x64_f8f6f4.
 //
 // Unit: one "block" per (tile of 32 output channels, group of 128 input channels) = 2048 bytes,
 // blocks ordered [n/32][k/128].  A block is [h = 0,1][lane = 0..63][16 bytes]: `h` is the 64-wide
@@ -24,11 +24,12 @@ typedef __bf16 fq_v2bf __attribute__((ext_vector_type(2)));
 // Inside the 16 bytes, byte 4*i + j holds two 4-bit codes:
 //     low  nibble -> operand register i,     byte j :  k = 128*g + 64*h + 32*kh +      4*i + j
 //     high nibble -> operand register 4 + i, byte j :  k = 128*g + 64*h + 32*kh + 16 + 4*i + j
-// A 4-bit code is sign-magnitude with the sign in bit 0:  code = 2*q      for q in  0..7
-//                                                          code = 2*(-q-1)+1 for q in -8..-1
-// so that  |q| = (code + (code & 1)) >> 1  is one v_lerp_u8 on four codes at a time, and the byte
-// (sign << 7) | |q| is the E4M3 number q * 2^-9 (E4M3 subnormals and the first binade share one
-// spacing, so the sixteen integers -8..7 times 2^-9 are all exact).  Channels past N hold code 0.
+// A 4-bit code is the weight with a zero point of 8:  code = q + 8  (0..15 for q = -8..7).
+// Zero-extended to a byte it IS an E4M3 number: E4M3 subnormals (codes 0..7) and the first binade
+// (codes 8..15) share one spacing, so byte c reads as c * 2^-9 exactly.  Unpacking is a mask and a
+// shift, and the kernels compute  sum_k a_k * c_k * 2^-9  on the matrix cores and take the zero
+// point out again as  - 2^-6 * sum_k a_k  per (row, group), a term that does not depend on the
+// output channel.  Channels past N hold code 0.
 // ---------------------------------------------------------------------------------------------
 __host__ __device__ inline size_t fq_block_offset(int nt, int g, int G) {
     return ((size_t)nt * (size_t)G + (size_t)g) * 2048u;
@@ -36,13 +37,11 @@ __host__ __device__ inline size_t fq_block_offset(int nt, int g, int G) {
 
 __host__ __device__ inline unsigned fq_code_from_q(int q) {       // q in -8..7 (low 4 bits used)
     q = (q << 28) >> 28;                                            // sign-extend the nibble
-    return q >= 0 ? (unsigned)(2 * q) : (unsigned)(2 * (-q - 1) + 1);
+    return (unsigned)(q + 8);
 }
 
 __host__ __device__ inline int fq_q_from_code(unsigned code) {
-    int s = (int)(code & 1u);
-    int mag = (int)((code + (unsigned)s) >> 1) & 0xF;
-    return s ? -mag : mag;
+    return (int)(code & 0xFu) - 8;
 }
 
 // Byte offset inside the packed buffer and nibble position (0 = low, 1 = high) of weight (n, k).
@@ -56,20 +55,18 @@ __host__ __device__ inline size_t fq_weight_byte(int n, int k, int G, int* hi) {
 }
 
 #ifdef __HIPCC__
-// Four packed bytes of 4-bit codes (already masked to 0x0F per byte) -> four E4M3 bytes q*2^-9.
-__device__ __forceinline__ unsigned fq_codes_to_e4m3x4(unsigned x) {
-    unsigned mag = __builtin_amdgcn_lerp(x, 0u, x);                 // per byte (x + (x & 1)) >> 1
-    return ((x & 0x01010101u) << 7) | mag;
-}
+// E4M3 byte of -2^-6: an all-(-2^-6) B operand turns an MFMA into the zero-point term
+// -2^-6 * sum_k a_k, delivered in every output column.
+#define FQ_ZP_BYTES 0x88888888
 
-// One 16-byte packed chunk -> the 8 operand registers of one MFMA half.
+// One 16-byte packed chunk -> the 8 operand registers of one MFMA half (bytes c * 2^-9).
 __device__ __forceinline__ fq_v8i fq_unpack_chunk(fq_v4i w) {
     fq_v8i r;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         unsigned u = (unsigned)w[i];
-        r[i]     = (int)fq_codes_to_e4m3x4(u & 0x0F0F0F0Fu);
-        r[4 + i] = (int)fq_codes_to_e4m3x4((u >> 4) & 0x0F0F0F0Fu);
+        r[i]     = (int)(u & 0x0F0F0F0Fu);
+        r[4 + i] = (int)((u >> 4) & 0x0F0F0F0Fu);
     }
     return r;
 }

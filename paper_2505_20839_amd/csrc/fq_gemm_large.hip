@@ -14,6 +14,11 @@
 //     P   = A[:, g, first 64] * Wq[g, first 64]            v_mfma_f32_32x32x64_f8f6f4, C = 0
 //     P  += A[:, g, last 64]  * Wq[g, last 64]             same, C = P
 //     acc += e4m3(gscale[n, g]) * P                        16 v_fma_f32 per 32x32 tile
+// The packed codes carry a zero point of 8 (byte c reads as the E4M3 number c * 2^-9), so unpacking
+// is a mask and a shift, and the sum above comes out too large by 2^-6 * gscale[n, g] * sum_k A[m, k]
+// per group.  That excess is a product of a per-(row, group) and a per-(channel, group) factor: a
+// small kernel first writes Z[m, g] = -2^-6 * sum_k A[m, k] (FP32, split exactly into three bf16
+// terms), and each tile ends with  acc += Z * gscale^T  as bf16 MFMAs of depth K / 128.
 // A tiles go global -> LDS directly (buffer_load_dwordx4 ... lds, two stages of 32 KiB, one group
 // per barrier); packed weights go global -> LDS the same way (2 x 2 KiB private to each wave) and
 // are unpacked one group ahead, a slice under each MFMA.
@@ -43,6 +48,15 @@
 namespace {
 
 typedef __attribute__((address_space(3))) void* fql_lds_ptr;
+typedef __bf16 fql_v8bf __attribute__((ext_vector_type(8)));
+
+#define FQ_MFMA_BF16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+
+// Zero-point planes: Z[m, g] = -2^-6 * sum_{k in group g} A[m, k] as three bf16 terms that add up to
+// the FP32 value.  Stored as units of [M rows][8 groups] bf16 (16 bytes per row), unit index
+// u = plane * C2 + g / 8 with C2 = 2 * ceil(G / 16) (groups past G are zero), so that one 16-byte
+// chunk is what one lane of the 32x32x16 bf16 MFMA holds of the A operand.
+__host__ __device__ inline int fql_c2(int G) { return 2 * ((G + 15) / 16); }
 
 // LDS layout of one A stage (one 128-wide group of up to 256 rows): row-major, 8 slots of 16 bytes per
 // row; slot c of row r holds bytes 16*x .. 16*x+15 of the row's group with x = c ^ ((r >> 1) & 7).
@@ -109,12 +123,48 @@ __host__ __device__ inline fql_split fql_xcd_split(int x, int ntiles, int slots)
 
 }  // namespace
 
+// One thread per (row m, group g < 8 * C2): sums the 128 activations of the group, writes the three
+// bf16 terms of -2^-6 * sum (zeros for the padding groups g >= G).
+__global__ __launch_bounds__(256) void fq_zero_point_kernel(const uint8_t* __restrict__ A, uint16_t* __restrict__ planes,
+                                                            int M, int K) {
+    const int G = K / FQ_GROUP, C2 = fql_c2(G), G8 = 8 * C2;
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int g = (int)(idx % (size_t)G8);
+    const size_t m = idx / (size_t)G8;
+    if (m >= (size_t)M) return;
+    float z = 0.f;
+    if (g < G) {
+        const fq_v4i* src = reinterpret_cast<const fq_v4i*>(A + m * (size_t)K + (size_t)g * FQ_GROUP);
+        float part[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const fq_v4i v = src[i];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], false);
+                const fq_v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], true);
+                part[j] += (lo[0] + lo[1]) + (hi[0] + hi[1]);
+            }
+        }
+        z = -0.015625f * ((part[0] + part[1]) + (part[2] + part[3]));
+    }
+    const unsigned t0 = fq_float_to_bf16(z);
+    const float r1 = z - __uint_as_float(t0 << 16);       // exact
+    const unsigned t1 = fq_float_to_bf16(r1);
+    const float r2 = r1 - __uint_as_float(t1 << 16);      // exact
+    const unsigned t2 = fq_float_to_bf16(r2);
+    const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
+    planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = (uint16_t)t0;
+    planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = (uint16_t)t1;
+    planes[(((size_t)2 * C2 + unit) * M + m) * 8 + e] = (uint16_t)t2;
+}
+
 template <int NMT>                                        // row tiles of 32 rows per item: 8, or 4 for the half tiles
 __global__ __launch_bounds__(FQL_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void fq_gemm_large_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
-    int tiles_m, int tiles_n, int slots, int pm) {
+    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes) {
     extern __shared__ fq_v4i lds[];                       // 2 A stages (64 KiB) + 4 x 4 KiB of packed weights
     constexpr int NT = NMT;                               // A transfers per wave and stage
     const int G = K / FQ_GROUP;
@@ -252,7 +302,7 @@ void fq_gemm_large_kernel(
                         const int slot = (8 / NMT) * mt + e;                    // packed word 0..7
                         const unsigned w = (unsigned)q[slot & 3];
                         const unsigned x = (h == 0 ? w : (w >> 4)) & 0x0F0F0F0Fu;
-                        const int ev = (int)fq_codes_to_e4m3x4(x);
+                        const int ev = (int)x;                        // byte c = c * 2^-9 in E4M3
                         if (slot < 4) b0[u ^ 1][4 * h + (slot & 3)] = ev;
                         else          b1[u ^ 1][4 * h + (slot & 3)] = ev;
                     }
@@ -283,14 +333,82 @@ void fq_gemm_large_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[NMT - 1][r] = fmaf(sprev, pprev[r], acc[NMT - 1][r]);
 
+    // ---- zero point: acc += Z * gscale^T over the groups, on the bf16 matrix cores ----
+    // Units of Z (32 * NMT rows x 8 groups, 16 bytes per row) are staged in the A stages, up to 16
+    // at a time; units 2c and 2c + 1 of a plane are the two lane halves of MFMA chunk c (16 groups).
+    {
+        constexpr int RT = 32 * NMT;                      // rows of the item
+        constexpr int SUBS = RT / 64;                     // transfers of 64 rows per unit
+        const int C2 = fql_c2(G), U = 3 * C2;
+        const __amdgpu_buffer_rsrc_t rsZ = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(planes), 0, (int)((unsigned)U * (unsigned)M * 16u), 0x00020000);
+        const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t*>(gs), 0, (int)((unsigned)N * (unsigned)G), 0x00020000);
+        const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : 0xFFFFFF00u;   // channels past N read zeros
+        const bool words = ((G & 3) == 0) && ((reinterpret_cast<uintptr_t>(gs) & 3) == 0);
+        const int hl = lane >> 5;                         // which half of a chunk's 16 groups this lane holds
+        for (int u0 = 0; u0 < U; u0 += 16) {
+            const int nu = U - u0 < 16 ? U - u0 : 16;
+            __syncthreads();                              // the stages (or the previous units) are no longer read
+            for (int q = wave; q < nu * SUBS; q += FQL_WAVES) {
+                const int slot = q / SUBS, sub = q - slot * SUBS;
+                const unsigned v = (unsigned)(m0 + 64 * sub + lane) * 16u;
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsZ, (fql_lds_ptr)(lds + slot * RT + 64 * sub), 16, v,
+                                                         (int)((unsigned)(u0 + slot) * (unsigned)M * 16u), 0, 0);
+            }
+            // gscale operands of this round's chunks: 8 consecutive groups of this lane's channel as bf16
+            fql_v8bf sig[8];
+#pragma unroll
+            for (int ci = 0; ci < 8; ++ci) {
+                const int c = ((u0 + 2 * ci) % C2) >> 1;  // chunk index inside its plane
+                const int g0 = 16 * c + 8 * hl;
+                unsigned w[2] = {0u, 0u};
+                if (2 * ci < nu) {
+                    if (words) {
+#pragma unroll
+                        for (int x = 0; x < 2; ++x)
+                            w[x] = __builtin_amdgcn_raw_buffer_load_b32(rsS, g0 + 4 * x < G ? srow : 0xFFFFFF00u, g0 + 4 * x, 0);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            const unsigned b = __builtin_amdgcn_raw_buffer_load_b8(rsS, g0 + e < G ? srow : 0xFFFFFF00u, g0 + e, 0);
+                            w[e >> 2] |= (b & 0xFFu) << (8 * (e & 3));
+                        }
+                    }
+                }
+                unsigned pk[4];
+#pragma unroll
+                for (int x = 0; x < 2; ++x) {
+                    const unsigned f0 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 0));
+                    const unsigned f1 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 1));
+                    const unsigned f2 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 2));
+                    const unsigned f3 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 3));
+                    pk[2 * x]     = (f0 >> 16) | (f1 & 0xFFFF0000u);   // E4M3 -> bf16 is exact
+                    pk[2 * x + 1] = (f2 >> 16) | (f3 & 0xFFFF0000u);
+                }
+                sig[ci] = __builtin_bit_cast(fql_v8bf, (fq_v4i){(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3]});
+            }
+            __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
+            __syncthreads();
+#pragma unroll
+            for (int ci = 0; ci < 8; ++ci) {
+                if (2 * ci < nu) {
+                    const fq_v4i* unit = lds + (2 * ci + hl) * RT + (lane & 31);
+#pragma unroll
+                    for (int mt = 0; mt < NMT; ++mt)
+                        acc[mt] = FQ_MFMA_BF16(__builtin_bit_cast(fql_v8bf, unit[32 * mt]), sig[ci], acc[mt]);
+                }
+            }
+        }
+    }
+
     // ---- epilogue: per-token and per-tensor factors, one rounding to bf16, store ----
-    // Every wave is past the last barrier, so the stages are free; the output tile also covers part
-    // of the weight buffers, so the (ghost) weight transfers still in flight must land first.  The
-    // first 32 * NMT * FQL_OUT_STRIDE bytes become the output tile, 1 KiB behind the largest tile
-    // holds the row factors.
-    __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
+    // The stages are reused once more (the barrier below orders that after the last read of the
+    // zero-point units): the first 32 * NMT * FQL_OUT_STRIDE bytes become the output tile, which also
+    // covers part of the weight buffers (their ghost transfers have landed: the zero-point rounds
+    // waited for all transfers), 1 KiB behind the largest tile holds the row factors.
     float* osc = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + FQL_BM * FQL_OUT_STRIDE);
-    for (int i = threadIdx.x; i < 32 * NMT; i += FQL_THREADS) {   // x 2^9: the weights were fed as q * 2^-9
+    for (int i = threadIdx.x; i < 32 * NMT; i += FQL_THREADS) {   // x 2^9: the weights were fed in units of 2^-9
         int m = m0 + i;
         osc[i] = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);
     }
@@ -348,10 +466,12 @@ void fq_gemm_large_kernel(
     }
 }
 
-void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                          float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
+int fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                         float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
     static bool attr_set = false;
     static int cus = 256;
+    static uint16_t* planes = nullptr;                    // zero-point planes: grow-only scratch, shared by all calls
+    static size_t planes_cap = 0;
     if (!attr_set) {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel<8>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
@@ -361,6 +481,20 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
         if (hipGetDevice(&dev) == hipSuccess)
             (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         attr_set = true;
+    }
+    const int G = K / FQ_GROUP, C2 = fql_c2(G);
+    const size_t need = (size_t)3 * C2 * M * 16;
+    if (need > planes_cap) {
+        if (planes) (void)hipFree(planes);
+        planes = nullptr;
+        planes_cap = 0;
+        if (hipMalloc(reinterpret_cast<void**>(&planes), need) != hipSuccess) return 1;
+        planes_cap = need;
+    }
+    {
+        const size_t threads = (size_t)M * 8 * C2;
+        hipLaunchKernelGGL(fq_zero_point_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
+                           A, planes, M, K);
     }
     const int tiles_m = (M + FQL_BM - 1) / FQL_BM, tiles_n = (N + FQL_BN - 1) / FQL_BN;
     int slots = 2 * cus / FQL_XCDS;                       // resident workgroups per XCD: two per compute unit
@@ -375,8 +509,11 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
     }
     if (max_full > 0)
         hipLaunchKernelGGL(fq_gemm_large_kernel<8>, dim3((unsigned)(max_full * FQL_XCDS)), dim3(FQL_THREADS),
-                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm);
+                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm,
+                           planes);
     if (max_half > 0)
         hipLaunchKernelGGL(fq_gemm_large_kernel<4>, dim3((unsigned)(max_half * FQL_XCDS)), dim3(FQL_THREADS),
-                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm);
+                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm,
+                           planes);
+    return 0;
 }

@@ -61,6 +61,10 @@ __global__ __launch_bounds__(FQS_THREADS) void fq_gemm_small_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 
+    fq_v8i zp;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) zp[r] = (int)FQ_ZP_BYTES;
+
     fq_v4i bq[FQS_DEPTH][2];
     unsigned sq[FQS_DEPTH];
 #pragma unroll
@@ -102,7 +106,9 @@ __global__ __launch_bounds__(FQS_THREADS) void fq_gemm_small_kernel(
                 }
 #pragma unroll
                 for (int t = 0; t < MT; ++t) {
-                    fq_v16f p = FQ_MFMA(a[t][0], b0, zero);
+                    fq_v16f p = FQ_MFMA(a[t][0], zp, zero);   // zero point: -2^-6 * sum_k a_k in every column
+                    p = FQ_MFMA(a[t][1], zp, p);
+                    p = FQ_MFMA(a[t][0], b0, p);
                     p = FQ_MFMA(a[t][1], b1, p);
 #pragma unroll
                     for (int r = 0; r < 16; ++r) acc[t][r] = fmaf(s, p[r], acc[t][r]);
@@ -117,7 +123,7 @@ __global__ __launch_bounds__(FQS_THREADS) void fq_gemm_small_kernel(
 #pragma unroll
         for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
     __syncthreads();
-    const float outer = tscale * 512.0f;                  // weights were fed as q * 2^-9
+    const float outer = tscale * 512.0f;                  // weights were fed in units of 2^-9
     for (int idx = threadIdx.x; idx < MT * 16 * 64; idx += FQS_THREADS) {
         int l = idx & 63, r = (idx >> 6) & 15, t = idx >> 10;
         float v = 0.f;
@@ -194,11 +200,15 @@ struct fqs16_ring {
     __device__ __forceinline__ void compute(int i, fq_v4f (&acc)[NSUB], const unsigned (&sw)[NSUB]) const {
         const fq_v4f zero4 = {0.f, 0.f, 0.f, 0.f};
         const fq_v8i a = fqs_join(aq[i][0], aq[i][1]);
+        fq_v8i zp;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) zp[r] = (int)FQ_ZP_BYTES;
+        const fq_v4f c0 = FQ_MFMA16(a, zp, zero4);        // zero point: -2^-6 * sum_k a_k in every column
 #pragma unroll
         for (int j = 0; j < NSUB; ++j) {
             const fq_v8i b = fq_unpack_chunk(bq[i][j]);
             const float s = WORDS ? fq_e4m3_byte_to_float(sw[j], i % 4) : __builtin_amdgcn_cvt_f32_fp8((int)sq[i][j], 0);
-            const fq_v4f p = FQ_MFMA16(a, b, zero4);
+            const fq_v4f p = FQ_MFMA16(a, b, c0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[j][r] = fmaf(s, p[r], acc[j][r]);
         }
@@ -283,7 +293,7 @@ void fq_gemm_small16_kernel(
 #pragma unroll
         for (int r = 0; r < 4; ++r) red[wave][j][r][lane] = acc[j][r];
     __syncthreads();
-    const float outer = tscale * 512.0f;                  // weights were fed as q * 2^-9
+    const float outer = tscale * 512.0f;                  // weights were fed in units of 2^-9
 #pragma unroll
     for (int i = 0; i < NOUT; ++i) {
         const int idx = threadIdx.x + i * FQS16_THREADS;  // NSUB * 256 outputs: [sub-tile][reg][lane]

@@ -214,7 +214,10 @@ def test_gemm_invariants_on_gpu(fq, kernel_choice):
     kernel_choice("small")
     Yrow = _run_gemm(fq, A[5:6], a[5:6], q, gs, t)
     d = np.abs(oracle.bf16_bits_to_f64(Yrow)[0] - oracle.bf16_bits_to_f64(Y1)[5])
-    assert np.all(d <= oracle.bf16_ulp_array(oracle.bf16_bits_to_f64(Y1)[5]))             # row independence
+    # row independence: another kernel, other rows around it, same row result up to the FP32
+    # summation order (a small fraction of the bound on the sum of |terms|) and one rounding step
+    _, B = oracle.w4a8_gemm(A[5:6], a[5:6], q, gs, t, want_bound=True)
+    assert np.all(d <= oracle.bf16_ulp_array(oracle.bf16_bits_to_f64(Y1)[5]) + 1e-4 * B[0])
     kernel_choice("auto")
     assert np.array_equal(_run_gemm(fq, A, a, q, gs, t), Y1)
 
