@@ -7,9 +7,9 @@ All inputs are synthetic (seeded) and resident in HBM before the timed region st
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 
-Prints one JSON line: whole-step throughput (`value`), the roofline figure of the GEMM kernel
-measured with HIP events around every GEMM launch of the timed region, and the CPU oracle timed
-on a bounded sample of the same workload.
+Prints one JSON line: whole-step throughput (`value`), the roofline figure of the GEMM call
+measured with HIP events around replays of a graph that holds only the GEMM calls of the timed
+steps, and the CPU oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -29,6 +29,7 @@ PEAK_FP8_TFLOPS = 5033.0      # 256 CU x 2.4 GHz x 8192 flop/clk/CU, dense FP8 M
 PEAK_HBM_GBPS = 8000.0
 DEFAULT_WORKLOAD = "c2_l2_7b_gateup"
 DECODE_COPIES = 12            # rotating weight copies so that small-M launches read HBM, not cache
+LARGE_GRAPH_STEPS = 10        # steps per captured graph at large M (one copy of the weights: they do not fit a cache)
 
 
 def _traffic_from_profiles(workload: str):
@@ -85,62 +86,50 @@ def main() -> int:
         gs = torch.from_numpy(d["gscale"]).cuda()
         return w, d, X, packed, gs
 
-    def run(name, steps, warmup, copies):
+    def run(name, steps, warmup, copies, graph_steps):
         """Times `steps` steps; returns (workload, inputs, steps timed, seconds for all of them,
-        mean GEMM kernel seconds, mean quantiser seconds).
+        mean GEMM seconds, mean quantiser seconds).
 
-        Large-M steps are launched one by one with HIP events around each kernel (the GPU is the
-        bottleneck, launches queue up).  Small-M steps finish faster than Python can launch them, so
-        they are captured into a HIP graph (`copies` steps, each on its own copy of the weights) and
-        the graph is replayed; the GEMM kernel's mean duration then comes from a second graph that
-        holds only the GEMM launches."""
+        A step is two or three short kernels, faster than Python can launch them one by one, so
+        `graph_steps` steps are captured into a HIP graph and the graph is replayed (small M: each step
+        of a graph on its own copy of the weights, `copies` in all, so that the weights come from HBM).
+        The GEMM's mean duration comes from a second graph that holds only the GEMM calls, the
+        quantiser's from a third."""
         w, d, X, packed, gs = upload(name)
         packs = [packed] + [packed.clone() for _ in range(copies - 1)]
         gss = [gs] + [gs.clone() for _ in range(copies - 1)]
         Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+        need = fq.fq_w4a8_gemm_workspace_bytes(w.M, w.N, w.K)
+        ws = torch.empty((max(need, 16),), dtype=torch.uint8, device="cuda")
 
-        def step(i, evs=None):
-            if evs is not None:
-                evs[0].record()
+        def gemm(A, s, i):
+            fq.fq_w4a8_gemm(A, s, packs[i % copies], gss[i % copies], d["w_tscale"], w.N, out=Y, workspace=ws)
+
+        def step(i):
             A, s = fq.fq_quantize_act(X)
-            if evs is not None:
-                evs[1].record()
-            fq.fq_w4a8_gemm(A, s, packs[i % copies], gss[i % copies], d["w_tscale"], w.N, out=Y)
-            if evs is not None:
-                evs[2].record()
+            gemm(A, s, i)
             return A, s
 
-        for i in range(warmup):
+        for i in range(max(warmup, 1)):
             A_last, s_last = step(i)
         torch.cuda.synchronize()
-        if copies == 1:
-            events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
-            torch.cuda.synchronize()
-            t0 = time.perf_counter()
-            for i in range(steps):
-                step(i, events[i])
-            torch.cuda.synchronize()
-            t1 = time.perf_counter()
-            gemm_s = sum(e[1].elapsed_time(e[2]) for e in events) * 1e-3 / steps
-            quant_s = sum(e[0].elapsed_time(e[1]) for e in events) * 1e-3 / steps
-            return w, d, steps, (t1 - t0), gemm_s, quant_s
 
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
             g_steps = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g_steps, stream=side):
-                for i in range(copies):
+                for i in range(graph_steps):
                     step(i)
             g_gemm = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g_gemm, stream=side):
-                for i in range(copies):
-                    fq.fq_w4a8_gemm(A_last, s_last, packs[i], gss[i], d["w_tscale"], w.N, out=Y)
+                for i in range(graph_steps):
+                    gemm(A_last, s_last, i)
             g_quant = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g_quant, stream=side):
-                for i in range(copies):
+                for i in range(graph_steps):
                     fq.fq_quantize_act(X)
-            reps = max(1, (steps + copies - 1) // copies)
+            reps = max(1, (steps + graph_steps - 1) // graph_steps)
 
             def timed(graph):
                 graph.replay()
@@ -159,7 +148,7 @@ def main() -> int:
             _, gemm_all = timed(g_gemm)
             _, quant_all = timed(g_quant)
         torch.cuda.current_stream().wait_stream(side)
-        n = reps * copies
+        n = reps * graph_steps
         return w, d, n, wall, gemm_all / n, quant_all / n
 
     name = args.workload
@@ -167,7 +156,8 @@ def main() -> int:
     decode_like = w0.M <= 64
     steps = args.steps if args.steps is not None else (2000 if decode_like else 200)
     warmup = args.warmup if args.warmup is not None else (50 if decode_like else 20)
-    w, d, steps, total_s, gemm_s, quant_s = run(name, steps, warmup, DECODE_COPIES if decode_like else 1)
+    w, d, steps, total_s, gemm_s, quant_s = run(name, steps, warmup, DECODE_COPIES if decode_like else 1,
+                                                DECODE_COPIES if decode_like else LARGE_GRAPH_STEPS)
 
     flop = 2.0 * w.M * w.N * w.K
     G = w.K // 128
@@ -185,8 +175,9 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": flop / gemm_s / 1e12, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s"}
     roof["frac"] = roof["achieved"] / roof["peak"]
     roof["traffic"] = _traffic_from_profiles(name)
+    # what one fq_w4a8_gemm call launches: kernel_us is the mean duration of the whole call
     roof["kernel"] = ("fq_gemm_small16_kernel" if w.M <= 16 else "fq_gemm_small_kernel") if decode_like \
-        else "fq_gemm_large_kernel"
+        else "fq_zero_point_kernel + fq_gemm_large_kernel<8> (+ <4> for the tail round)"
     roof["kernel_us"] = gemm_s * 1e6
     roof["quantize_us"] = quant_s * 1e6
     roof["algorithmic_bytes"] = gemm_bytes
@@ -202,7 +193,7 @@ def main() -> int:
 
     if not decode_like and not args.no_decode:
         # second half of the metric: packed-weight GB/s at M = 16 against the HBM roofline
-        wd, dd, n_d, tot_d, gemm_d, _ = run("c5_decode_m16", 1500, 50, DECODE_COPIES)
+        wd, dd, n_d, tot_d, gemm_d, _ = run("c5_decode_m16", 1500, 50, DECODE_COPIES, DECODE_COPIES)
         wb = wd.N * wd.K / 2 + wd.N * (wd.K // 128)
         out["decode_m16"] = {"workload": "c5_decode_m16", "kernel_us": gemm_d * 1e6, "step_us": tot_d / n_d * 1e6,
                              "weight_GBps": wb / gemm_d / 1e9, "frac_hbm": wb / gemm_d / 1e9 / PEAK_HBM_GBPS,

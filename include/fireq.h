@@ -33,7 +33,7 @@ enum {
     FQ_ERR_SHAPE  = -2,  /* negative size, K == 0, K % 128 != 0, N == 0 with M > 0            */
     FQ_ERR_ALIGN  = -3,  /* a base pointer is not 16-byte aligned                             */
     FQ_ERR_LAUNCH = -4,  /* the HIP runtime reported an error when the kernel was launched    */
-    FQ_ERR_MEMORY = -5   /* the library could not allocate its device scratch buffer          */
+    FQ_ERR_MEMORY = -5   /* workspace missing or too small / own workspace could not be allocated */
 };
 
 #define FQ_GROUP 128     /* weights along K share one E4M3 scale per 128 (Sec. 3.1)           */
@@ -54,7 +54,22 @@ enum {
  *   w_gscale   [N,K/128] row-major OCP E4M3 codes, any finite value (zero, subnormal, negative)
  *   w_tscale          FP32 per-tensor factor (delta^-1 of Def. 3.2), by value
  *   Y_bf16     [M,N]  row-major bfloat16 bit patterns (output)
+ *
+ * For M > 64 the kernels need device scratch (the packed codes carry a zero point, and the
+ * term that takes it out again, one FP32 number per row and group, is computed first).
+ * fq_w4a8_gemm_ws takes that scratch from the caller: `workspace` is device memory, 16-byte
+ * aligned, at least fq_w4a8_gemm_workspace_bytes(M,N,K) bytes (0 = none needed, NULL is fine
+ * then); its contents are overwritten, and it may be reused or freed once the work enqueued
+ * by the call has finished.  That variant allocates nothing, keeps no state and never
+ * synchronises.  fq_w4a8_gemm is the same call on a workspace the library owns: one device
+ * buffer for the whole process that grows (hipFree + hipMalloc, which synchronise the device)
+ * when a call needs more than any call before it, so calls that overlap on different streams
+ * race on it, and a first call must not be made under stream capture.
  */
+size_t fq_w4a8_gemm_workspace_bytes(int M, int N, int K);
+int fq_w4a8_gemm_ws(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
+                    const uint8_t *w_gscale, float w_tscale, uint16_t *Y_bf16,
+                    int M, int N, int K, void *workspace, size_t workspace_bytes, void *stream);
 int fq_w4a8_gemm(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
                  const uint8_t *w_gscale, float w_tscale, uint16_t *Y_bf16,
                  int M, int N, int K, void *stream);

@@ -36,6 +36,10 @@ def lib() -> ctypes.CDLL:
     vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     L.fq_w4a8_gemm.restype = ci
     L.fq_w4a8_gemm.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
+    L.fq_w4a8_gemm_ws.restype = ci
+    L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, vp]
+    L.fq_w4a8_gemm_workspace_bytes.restype = ctypes.c_size_t
+    L.fq_w4a8_gemm_workspace_bytes.argtypes = [ci, ci, ci]
     L.fq_quantize_act.restype = ci
     L.fq_quantize_act.argtypes = [vp, vp, vp, ci, ci, vp]
     L.fq_packed_weight_bytes.restype = ctypes.c_size_t
@@ -117,8 +121,11 @@ def fq_quantize_act(X: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
 
 def fq_w4a8_gemm(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor,
                  w_gscale: torch.Tensor, w_tscale: float, N: int,
-                 out: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """Y[M,N] (bf16) = W4A8-FP GEMM of E4M3 activations and packed INT4 weights."""
+                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[M,N] (bf16) = W4A8-FP GEMM of E4M3 activations and packed INT4 weights.
+
+    Calls fq_w4a8_gemm_ws; `workspace` (a device tensor of at least
+    fq_w4a8_gemm_workspace_bytes(M, N, K) bytes) is allocated here when not given."""
     A = _dev(A, torch.uint8, "A")
     a_scale = _dev(a_scale, torch.float32, "a_scale")
     Wq_packed = _dev(Wq_packed, torch.uint8, "Wq_packed")
@@ -133,9 +140,18 @@ def fq_w4a8_gemm(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor
         out = _dev(out, torch.bfloat16, "out")
         if tuple(out.shape) != (M, N):
             raise FireqError(-2, "fq_w4a8_gemm")
-    rc = lib().fq_w4a8_gemm(A.data_ptr(), a_scale.data_ptr(), Wq_packed.data_ptr(),
-                            w_gscale.data_ptr(), ctypes.c_float(float(w_tscale)), out.data_ptr(),
-                            M, N, K, _stream())
+    # the workspace comes from torch's caching allocator (stream-ordered, no hipMalloc per call)
+    need = lib().fq_w4a8_gemm_workspace_bytes(M, N, K)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=A.device)
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (0, 0)
+    rc = lib().fq_w4a8_gemm_ws(A.data_ptr(), a_scale.data_ptr(), Wq_packed.data_ptr(),
+                               w_gscale.data_ptr(), ctypes.c_float(float(w_tscale)), out.data_ptr(),
+                               M, N, K, ws_ptr, ws_bytes, _stream())
     if rc != 0:
-        raise FireqError(rc, "fq_w4a8_gemm")
+        raise FireqError(rc, "fq_w4a8_gemm_ws")
     return out
+
+
+def fq_w4a8_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().fq_w4a8_gemm_workspace_bytes(M, N, K))

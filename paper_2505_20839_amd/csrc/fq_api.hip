@@ -25,6 +25,11 @@ GemmKernel forced_kernel() {
     return GemmKernel::Auto;
 }
 
+GemmKernel choose_kernel(int M) {
+    const GemmKernel k = forced_kernel();
+    return k != GemmKernel::Auto ? k : (M <= 64 ? GemmKernel::Small : GemmKernel::Large);
+}
+
 }  // namespace
 
 extern "C" {
@@ -38,7 +43,7 @@ const char* fq_status_string(int status) {
         case FQ_ERR_SHAPE: return "invalid shape (sizes must be non-negative, K a positive multiple of 128)";
         case FQ_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
         case FQ_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
-        case FQ_ERR_MEMORY: return "the library could not allocate its device scratch buffer";
+        case FQ_ERR_MEMORY: return "workspace missing or too small, or the library could not allocate its own";
         default: return "unknown status";
     }
 }
@@ -76,29 +81,52 @@ int fq_quantize_act(const uint16_t* X_bf16, uint8_t* A_fp8, float* a_scale, int 
     return after_launch();
 }
 
-int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
-                 const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
-                 int M, int N, int K, void* stream) {
+size_t fq_w4a8_gemm_workspace_bytes(int M, int N, int K) {
+    if (M <= 0 || N <= 0 || K <= 0 || (K % FQ_GROUP) != 0) return 0;
+    return choose_kernel(M) == GemmKernel::Large ? fq_gemm_large_workspace_bytes(M, K) : 0;
+}
+
+int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                    const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
+                    int M, int N, int K, void* workspace, size_t workspace_bytes, void* stream) {
     if (M < 0 || N < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
     if (M == 0) return FQ_OK;
     if (N == 0) return FQ_ERR_SHAPE;
     if (!A_fp8 || !a_scale || !Wq_packed || !w_gscale || !Y_bf16) return FQ_ERR_NULL;
     if (!aligned16(A_fp8) || !aligned16(Wq_packed) || !aligned16(w_gscale) || !aligned16(Y_bf16))
         return FQ_ERR_ALIGN;
+    const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return FQ_ERR_MEMORY;
+        if (!aligned16(workspace)) return FQ_ERR_ALIGN;
+    }
     hipStream_t s = static_cast<hipStream_t>(stream);
-    GemmKernel k = forced_kernel();
-    if (k == GemmKernel::Auto) k = (M <= 64) ? GemmKernel::Small : GemmKernel::Large;
-    switch (k) {
+    switch (choose_kernel(M)) {
         case GemmKernel::Simple: fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
         case GemmKernel::Small:  fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
-        default:
-            if (fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s) != 0) {
-                (void)hipGetLastError();
-                return FQ_ERR_MEMORY;
-            }
-            break;
+        default: fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace, s); break;
     }
     return after_launch();
+}
+
+int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                 const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
+                 int M, int N, int K, void* stream) {
+    // the library's own workspace: one grow-only device buffer, shared by every call of the process
+    static void* ws = nullptr;
+    static size_t ws_bytes = 0;
+    const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
+    if (need > ws_bytes && A_fp8 && a_scale && Wq_packed && w_gscale && Y_bf16) {
+        if (ws) (void)hipFree(ws);
+        ws = nullptr;
+        ws_bytes = 0;
+        if (hipMalloc(&ws, need) != hipSuccess) {
+            (void)hipGetLastError();
+            return FQ_ERR_MEMORY;
+        }
+        ws_bytes = need;
+    }
+    return fq_w4a8_gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, ws, ws_bytes, stream);
 }
 
 }  // extern "C"

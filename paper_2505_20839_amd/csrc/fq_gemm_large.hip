@@ -17,8 +17,9 @@
 // The packed codes carry a zero point of 8 (byte c reads as the E4M3 number c * 2^-9), so unpacking
 // is a mask and a shift, and the sum above comes out too large by 2^-6 * gscale[n, g] * sum_k A[m, k]
 // per group.  That excess is a product of a per-(row, group) and a per-(channel, group) factor: a
-// small kernel first writes Z[m, g] = -2^-6 * sum_k A[m, k] (FP32, split exactly into three bf16
-// terms), and each tile ends with  acc += Z * gscale^T  as bf16 MFMAs of depth K / 128.
+// small kernel first writes Z[m, g] = -2^-6 * sum_k A[m, k] (FP32, split into two fp16 terms: 22
+// significant bits), and each tile ends with  acc += Z * gscale^T  as fp16 MFMAs of depth K / 128;
+// the first 16 groups' worth of Z is fetched into the idle A stage during the tile's last group.
 // A tiles go global -> LDS directly (buffer_load_dwordx4 ... lds, two stages of 32 KiB, one group
 // per barrier); packed weights go global -> LDS the same way (2 x 2 KiB private to each wave) and
 // are unpacked one group ahead, a slice under each MFMA.
@@ -29,6 +30,7 @@
 // The tiles an XCD cannot fill a whole round of its slots with are cut into two 128-row halves and
 // run by a second launch of the NMT = 4 variant, so that the last round keeps all units busy for
 // half the time.
+#include <type_traits>
 #include "fq_common.h"
 #include "fq_kernels.h"
 
@@ -48,14 +50,16 @@
 namespace {
 
 typedef __attribute__((address_space(3))) void* fql_lds_ptr;
-typedef __bf16 fql_v8bf __attribute__((ext_vector_type(8)));
+typedef _Float16 fql_v8h __attribute__((ext_vector_type(8)));
 
-#define FQ_MFMA_BF16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_bf16((a), (b), (c), 0, 0, 0)
+#define FQ_MFMA_F16(a, b, c) __builtin_amdgcn_mfma_f32_32x32x16_f16((a), (b), (c), 0, 0, 0)
+#define FQL_ZPLANES 2
 
-// Zero-point planes: Z[m, g] = -2^-6 * sum_{k in group g} A[m, k] as three bf16 terms that add up to
-// the FP32 value.  Stored as units of [M rows][8 groups] bf16 (16 bytes per row), unit index
-// u = plane * C2 + g / 8 with C2 = 2 * ceil(G / 16) (groups past G are zero), so that one 16-byte
-// chunk is what one lane of the 32x32x16 bf16 MFMA holds of the A operand.
+// Zero-point planes: Z[m, g] = -2^-6 * sum_{k in group g} A[m, k] as two fp16 terms, hi = fp16(Z) and
+// lo = fp16(Z - hi), 22 significant bits together (what is left, at most 2^-22 |Z|, is far below the
+// FP32 accumulation noise of the main sum).  Stored as units of [M rows][8 groups] fp16 (16 bytes
+// per row), unit index u = plane * C2 + g / 8 with C2 = 2 * ceil(G / 16) (groups past G are zero),
+// so that one 16-byte chunk is what one lane of the 32x32x16 fp16 MFMA holds of the A operand.
 __host__ __device__ inline int fql_c2(int G) { return 2 * ((G + 15) / 16); }
 
 // LDS layout of one A stage (one 128-wide group of up to 256 rows): row-major, 8 slots of 16 bytes per
@@ -93,6 +97,23 @@ __device__ __forceinline__ void fql_issue_b(__amdgpu_buffer_rsrc_t rsrc, fq_v4i*
     __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fql_lds_ptr)(dst + 64), 16, lane16, blk_off + 1024u, 0, 0);
 }
 
+// One round of zero-point units (up to 8, numbers u0 ..) -> an A stage: NMT transfers of 64 rows per
+// wave, the same number as an A tile takes, so that the pipeline's wait counts do not change; slots
+// past the last unit are requested out of range (zeros).  Unit slot s occupies chunks [s * RT, (s+1) * RT).
+template <int NMT>
+__device__ __forceinline__ void fql_issue_z(__amdgpu_buffer_rsrc_t rsZ, fq_v4i* lds_stage, int wave, int lane,
+                                            int m0, int M, int u0, int nu) {
+    constexpr int RT = 32 * NMT, SUBS = RT / 64;
+#pragma unroll
+    for (int t = 0; t < NMT; ++t) {
+        const int q = wave + FQL_WAVES * t;
+        const int slot = q / SUBS, sub = q - slot * SUBS;
+        const unsigned v = slot < nu ? (unsigned)(m0 + 64 * sub + lane) * 16u : 0xFFFFFF00u;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsZ, (fql_lds_ptr)(lds_stage + slot * RT + 64 * sub), 16, v,
+                                                 (int)((unsigned)(u0 + slot) * (unsigned)M * 16u), 0, 0);
+    }
+}
+
 // s_waitcnt immediate (gfx9 encoding) that waits until at most n vector-memory transfers are pending
 // and leaves the other counters alone.
 #define FQL_WAIT_VM(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
@@ -123,56 +144,54 @@ __host__ __device__ inline fql_split fql_xcd_split(int x, int ntiles, int slots)
 
 }  // namespace
 
-// One thread per (row m, group g < 8 * C2): sums the 128 activations of the group, writes the three
-// bf16 terms of -2^-6 * sum (zeros for the padding groups g >= G).
+// Eight lanes per (row m, group g < 8 * C2): each sums 16 of the group's 128 activations, the eight
+// partial sums are added across lanes, and the first lane writes the two fp16 terms of -2^-6 * sum
+// (zeros for the padding groups g >= G).
 __global__ __launch_bounds__(256) void fq_zero_point_kernel(const uint8_t* __restrict__ A, uint16_t* __restrict__ planes,
                                                             int M, int K) {
     const int G = K / FQ_GROUP, C2 = fql_c2(G), G8 = 8 * C2;
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int g = (int)(idx % (size_t)G8);
-    const size_t m = idx / (size_t)G8;
-    if (m >= (size_t)M) return;
+    const int sub = (int)(idx & 7);
+    const size_t pair = idx >> 3;
+    const int g = (int)(pair % (size_t)G8);
+    const size_t m = pair / (size_t)G8;
     float z = 0.f;
-    if (g < G) {
-        const fq_v4i* src = reinterpret_cast<const fq_v4i*>(A + m * (size_t)K + (size_t)g * FQ_GROUP);
-        float part[4] = {0.f, 0.f, 0.f, 0.f};
+    if (m < (size_t)M && g < G) {
+        const fq_v4i v = *reinterpret_cast<const fq_v4i*>(A + m * (size_t)K + (size_t)g * FQ_GROUP + 16 * sub);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const fq_v4i v = src[i];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], false);
-                const fq_v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], true);
-                part[j] += (lo[0] + lo[1]) + (hi[0] + hi[1]);
-            }
+        for (int j = 0; j < 4; ++j) {
+            const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], false);
+            const fq_v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], true);
+            z += (lo[0] + lo[1]) + (hi[0] + hi[1]);
         }
-        z = -0.015625f * ((part[0] + part[1]) + (part[2] + part[3]));
     }
-    const unsigned t0 = fq_float_to_bf16(z);
-    const float r1 = z - __uint_as_float(t0 << 16);       // exact
-    const unsigned t1 = fq_float_to_bf16(r1);
-    const float r2 = r1 - __uint_as_float(t1 << 16);      // exact
-    const unsigned t2 = fq_float_to_bf16(r2);
+    z += __shfl_xor(z, 1, 64);
+    z += __shfl_xor(z, 2, 64);
+    z += __shfl_xor(z, 4, 64);
+    if (sub != 0 || m >= (size_t)M) return;
+    z *= -0.015625f;
+    const _Float16 hi = (_Float16)z;                      // round to nearest even
+    const _Float16 lo = (_Float16)(z - (float)hi);        // the difference is exact in FP32
     const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
-    planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = (uint16_t)t0;
-    planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = (uint16_t)t1;
-    planes[(((size_t)2 * C2 + unit) * M + m) * 8 + e] = (uint16_t)t2;
+    planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, hi);
+    planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, lo);
 }
 
-template <int NMT>                                        // row tiles of 32 rows per item: 8, or 4 for the half tiles
-__global__ __launch_bounds__(FQL_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void fq_gemm_large_kernel(
+// One item: NMT row tiles of 32 rows (8, or 4 for the half tiles) x 128 channels.  `bid` counts the
+// workgroups of the item's kind.
+template <int NMT>
+__device__ __forceinline__ void fql_item(
+    fq_v4i* lds, const unsigned bid,
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
     int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes) {
-    extern __shared__ fq_v4i lds[];                       // 2 A stages (64 KiB) + 4 x 4 KiB of packed weights
     constexpr int NT = NMT;                               // A transfers per wave and stage
     const int G = K / FQ_GROUP;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    // which item: XCD x = blockIdx.x % 8, j-th item of that XCD's list for this launch
+    // which item: XCD x = bid % 8 (both kinds start at a multiple of 8 workgroups), j-th item of that XCD's list
     int m0, n0;
     {
-        const int x = blockIdx.x % FQL_XCDS, j = blockIdx.x / FQL_XCDS;
+        const int x = bid % FQL_XCDS, j = bid / FQL_XCDS;
         const fql_split sp = fql_xcd_split(x, tiles_m * tiles_n, slots);
         int t, half = 0;
         if (NMT == 8) {
@@ -203,6 +222,9 @@ void fq_gemm_large_kernel(
         const_cast<uint8_t*>(A), 0, (int)((unsigned)M * (unsigned)K), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(wp), 0, (int)((unsigned)((N + 31) >> 5) * (unsigned)G * 2048u), 0x00020000);
+    const int C2 = fql_c2(G), ZU = FQL_ZPLANES * C2;      // zero-point units of this item's rows
+    const __amdgpu_buffer_rsrc_t rsZ = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint16_t*>(planes), 0, (int)((unsigned)ZU * (unsigned)M * 16u), 0x00020000);
     const unsigned abase = fql_a_lane_base(wave, lane, K, NT);
     const uint8_t* gsrow = gs + (size_t)(n_ok ? n : N - 1) * G;
 
@@ -251,7 +273,10 @@ void fq_gemm_large_kernel(
     // barriers keep the compiler from undoing that order.
     const int npairs = (G + 1) >> 1;
     fq_v8i an = fql_join(lds[o00], lds[o01]);             // operand of the very first step
-    for (int p = 0; p < npairs; ++p) {
+    // One pair of groups; LAST is the tile's last pair, whose second group fetches the first round
+    // of zero-point units instead of a further A tile.
+    auto pair_of_groups = [&](const int p, auto last_tag) __attribute__((always_inline)) {
+        constexpr bool LAST = decltype(last_tag)::value;
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const int g = 2 * p + u;
@@ -259,7 +284,10 @@ void fq_gemm_large_kernel(
             {   // A tile of the next group -> the stage the previous group used (all waves are past
                 // the barrier that ended it)
                 const int g1 = g + 1 < G ? g + 1 : G - 1;
-                fql_issue_a<NT>(rsA, abase, m0, K, lds + (u ^ 1) * FQL_STAGE_CHUNKS, wave, g1);
+                if (LAST && u == 1)
+                    fql_issue_z<NMT>(rsZ, lds + (u ^ 1) * FQL_STAGE_CHUNKS, wave, lane, m0, M, 0, ZU < 8 ? ZU : 8);
+                else
+                    fql_issue_a<NT>(rsA, abase, m0, K, lds + (u ^ 1) * FQL_STAGE_CHUNKS, wave, g1);
             }
             // Group g+1 sits in buffer u^1 (requested one group ago) and is unpacked slice by slice
             // under the MFMAs below; buffer u (group g, already unpacked) is refilled with group g+2.
@@ -328,38 +356,35 @@ void fq_gemm_large_kernel(
                 an = fql_join(nxs[o00], nxs[o01]);
             }
         }
-    }
+    };
+    for (int p = 0; p < npairs - 1; ++p) pair_of_groups(p, std::false_type());
+    pair_of_groups(npairs - 1, std::true_type());
     // last pending row tile of the last group
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[NMT - 1][r] = fmaf(sprev, pprev[r], acc[NMT - 1][r]);
 
-    // ---- zero point: acc += Z * gscale^T over the groups, on the bf16 matrix cores ----
-    // Units of Z (32 * NMT rows x 8 groups, 16 bytes per row) are staged in the A stages, up to 16
-    // at a time; units 2c and 2c + 1 of a plane are the two lane halves of MFMA chunk c (16 groups).
+    // ---- zero point: acc += Z * gscale^T over the groups, on the fp16 matrix cores ----
+    // Rounds of up to 8 units of Z (32 * NMT rows x 8 groups, 16 bytes per row); round r sits in A
+    // stage r & 1 (round 0 arrived during the last group) while the next round is on its way to
+    // the other stage.  Units 2c and 2c + 1 of a plane are the two lane halves of MFMA chunk c.
     {
         constexpr int RT = 32 * NMT;                      // rows of the item
-        constexpr int SUBS = RT / 64;                     // transfers of 64 rows per unit
-        const int C2 = fql_c2(G), U = 3 * C2;
-        const __amdgpu_buffer_rsrc_t rsZ = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint16_t*>(planes), 0, (int)((unsigned)U * (unsigned)M * 16u), 0x00020000);
         const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t*>(gs), 0, (int)((unsigned)N * (unsigned)G), 0x00020000);
         const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : 0xFFFFFF00u;   // channels past N read zeros
         const bool words = ((G & 3) == 0) && ((reinterpret_cast<uintptr_t>(gs) & 3) == 0);
         const int hl = lane >> 5;                         // which half of a chunk's 16 groups this lane holds
-        for (int u0 = 0; u0 < U; u0 += 16) {
-            const int nu = U - u0 < 16 ? U - u0 : 16;
-            __syncthreads();                              // the stages (or the previous units) are no longer read
-            for (int q = wave; q < nu * SUBS; q += FQL_WAVES) {
-                const int slot = q / SUBS, sub = q - slot * SUBS;
-                const unsigned v = (unsigned)(m0 + 64 * sub + lane) * 16u;
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rsZ, (fql_lds_ptr)(lds + slot * RT + 64 * sub), 16, v,
-                                                         (int)((unsigned)(u0 + slot) * (unsigned)M * 16u), 0, 0);
-            }
-            // gscale operands of this round's chunks: 8 consecutive groups of this lane's channel as bf16
-            fql_v8bf sig[8];
+        const int rounds = (ZU + 7) >> 3;
+        for (int r = 0; r < rounds; ++r) {
+            const int u0 = 8 * r;
+            const int nu = ZU - u0 < 8 ? ZU - u0 : 8;
+            if (r + 1 < rounds)                           // that stage was last read before the previous barrier
+                fql_issue_z<NMT>(rsZ, lds + ((r + 1) & 1) * FQL_STAGE_CHUNKS, wave, lane, m0, M, u0 + 8,
+                                 ZU - u0 - 8 < 8 ? ZU - u0 - 8 : 8);
+            // gscale operands of this round's chunks: 8 consecutive groups of this lane's channel as fp16
+            fql_v8h sig[4];
 #pragma unroll
-            for (int ci = 0; ci < 8; ++ci) {
+            for (int ci = 0; ci < 4; ++ci) {
                 const int c = ((u0 + 2 * ci) % C2) >> 1;  // chunk index inside its plane
                 const int g0 = 16 * c + 8 * hl;
                 unsigned w[2] = {0u, 0u};
@@ -376,29 +401,28 @@ void fq_gemm_large_kernel(
                         }
                     }
                 }
-                unsigned pk[4];
+                fq_v4i pk;                                // E4M3 -> fp16 is exact, whatever the rounding mode
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
-                    const unsigned f0 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 0));
-                    const unsigned f1 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 1));
-                    const unsigned f2 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 2));
-                    const unsigned f3 = __float_as_uint(__builtin_amdgcn_cvt_f32_fp8((int)w[x], 3));
-                    pk[2 * x]     = (f0 >> 16) | (f1 & 0xFFFF0000u);   // E4M3 -> bf16 is exact
-                    pk[2 * x + 1] = (f2 >> 16) | (f3 & 0xFFFF0000u);
+                    pk[2 * x]     = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
+                        __builtin_amdgcn_cvt_f32_fp8((int)w[x], 0), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 1)));
+                    pk[2 * x + 1] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
+                        __builtin_amdgcn_cvt_f32_fp8((int)w[x], 2), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 3)));
                 }
-                sig[ci] = __builtin_bit_cast(fql_v8bf, (fq_v4i){(int)pk[0], (int)pk[1], (int)pk[2], (int)pk[3]});
+                sig[ci] = __builtin_bit_cast(fql_v8h, pk);
             }
-            __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
-            __syncthreads();
+            const fq_v4i* stage = lds + (r & 1) * FQL_STAGE_CHUNKS;
 #pragma unroll
-            for (int ci = 0; ci < 8; ++ci) {
+            for (int ci = 0; ci < 4; ++ci) {
                 if (2 * ci < nu) {
-                    const fq_v4i* unit = lds + (2 * ci + hl) * RT + (lane & 31);
+                    const fq_v4i* unit = stage + (2 * ci + hl) * RT + (lane & 31);
 #pragma unroll
                     for (int mt = 0; mt < NMT; ++mt)
-                        acc[mt] = FQ_MFMA_BF16(__builtin_bit_cast(fql_v8bf, unit[32 * mt]), sig[ci], acc[mt]);
+                        acc[mt] = FQ_MFMA_F16(__builtin_bit_cast(fql_v8h, unit[32 * mt]), sig[ci], acc[mt]);
                 }
             }
+            __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));   // the next round (and, the first time, the last ghost weights)
+            __syncthreads();
         }
     }
 
@@ -466,33 +490,39 @@ void fq_gemm_large_kernel(
     }
 }
 
-int fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                         float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
+// Workgroups [0, full_wgs) run whole tiles, the rest the half tiles of the tail round: one launch, so
+// the halves start as soon as the first compute units run out of whole tiles.
+__global__ __launch_bounds__(FQL_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void fq_gemm_large_kernel(
+    const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
+    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, unsigned full_wgs) {
+    extern __shared__ fq_v4i lds[];                       // 2 A stages (64 KiB) + 4 x 4 KiB of packed weights
+    if (blockIdx.x < full_wgs)
+        fql_item<8>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes);
+    else
+        fql_item<4>(lds, blockIdx.x - full_wgs, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes);
+}
+
+size_t fq_gemm_large_workspace_bytes(int M, int K) {
+    return (size_t)FQL_ZPLANES * fql_c2(K / FQ_GROUP) * (size_t)M * 16;
+}
+
+void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                          float tscale, uint16_t* Y, int M, int N, int K, void* workspace, hipStream_t stream) {
     static bool attr_set = false;
     static int cus = 256;
-    static uint16_t* planes = nullptr;                    // zero-point planes: grow-only scratch, shared by all calls
-    static size_t planes_cap = 0;
     if (!attr_set) {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel<8>),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel<4>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
         int dev = 0;
         if (hipGetDevice(&dev) == hipSuccess)
             (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
         attr_set = true;
     }
-    const int G = K / FQ_GROUP, C2 = fql_c2(G);
-    const size_t need = (size_t)3 * C2 * M * 16;
-    if (need > planes_cap) {
-        if (planes) (void)hipFree(planes);
-        planes = nullptr;
-        planes_cap = 0;
-        if (hipMalloc(reinterpret_cast<void**>(&planes), need) != hipSuccess) return 1;
-        planes_cap = need;
-    }
+    uint16_t* planes = static_cast<uint16_t*>(workspace); // zero-point planes
     {
-        const size_t threads = (size_t)M * 8 * C2;
+        const size_t threads = (size_t)M * 8 * fql_c2(K / FQ_GROUP) * 8;
         hipLaunchKernelGGL(fq_zero_point_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
                            A, planes, M, K);
     }
@@ -507,13 +537,7 @@ int fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* 
         max_full = sp.nfull > max_full ? sp.nfull : max_full;
         max_half = sp.nhalf > max_half ? sp.nhalf : max_half;
     }
-    if (max_full > 0)
-        hipLaunchKernelGGL(fq_gemm_large_kernel<8>, dim3((unsigned)(max_full * FQL_XCDS)), dim3(FQL_THREADS),
-                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm,
-                           planes);
-    if (max_half > 0)
-        hipLaunchKernelGGL(fq_gemm_large_kernel<4>, dim3((unsigned)(max_half * FQL_XCDS)), dim3(FQL_THREADS),
-                           FQL_LDS_BYTES, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm,
-                           planes);
-    return 0;
+    const unsigned full_wgs = (unsigned)(max_full * FQL_XCDS), half_wgs = (unsigned)(max_half * FQL_XCDS);
+    hipLaunchKernelGGL(fq_gemm_large_kernel, dim3(full_wgs + half_wgs), dim3(FQL_THREADS), FQL_LDS_BYTES, stream,
+                       A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, full_wgs);
 }

@@ -12,10 +12,10 @@ void fq_launch_quantize(const uint16_t* X, uint8_t* A, float* a_scale, int M, in
 // GEMM kernels.  `which` selects the kernel: see fq_api.hip.
 void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                            float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);
-// The large-M launcher keeps a grow-only device scratch buffer (3 * 2 * ceil(K / 2048) * M * 16 bytes) that
-// all calls of the process share: calls on different streams that overlap would race on it.  It
-// returns non-zero when that buffer cannot be allocated (nothing is enqueued then).
-int fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                         float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);
+// The large-M kernels need fq_gemm_large_workspace_bytes(M, K) bytes of device scratch (16-byte aligned):
+// a first kernel writes the zero-point term of every (row, group) there, the GEMM kernels read it.
+size_t fq_gemm_large_workspace_bytes(int M, int K);
+void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                          float tscale, uint16_t* Y, int M, int N, int K, void* workspace, hipStream_t stream);
 void fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);

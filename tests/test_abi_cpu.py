@@ -20,7 +20,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     L = binding.lib()
     names = _declared_functions()
-    assert names == sorted(["fq_w4a8_gemm", "fq_quantize_act", "fq_packed_weight_bytes", "fq_pack_weights",
+    assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_packed_weight_bytes", "fq_pack_weights",
                             "fq_unpack_weights", "fq_layout_version", "fq_status_string"])
     for name in names:
         assert hasattr(L, name), name
@@ -34,8 +34,13 @@ def test_sizes_version_and_status_strings():
     assert binding.fq_packed_weight_bytes(16, 100) == 0                  # K not a multiple of 128
     assert binding.fq_packed_weight_bytes(0, 128) == 0
     assert binding.fq_layout_version() >= 1
-    seen = {binding.status_string(s) for s in (0, -1, -2, -3, -4)}
-    assert len(seen) == 5 and binding.status_string(0) == "ok"
+    seen = {binding.status_string(s) for s in (0, -1, -2, -3, -4, -5)}
+    assert len(seen) == 6 and binding.status_string(0) == "ok"
+    # workspace: none for the small-M kernels, two fp16 planes of [M][16 * ceil(K / 2048)] for the rest
+    assert binding.fq_w4a8_gemm_workspace_bytes(64, 256, 4096) == 0
+    assert binding.fq_w4a8_gemm_workspace_bytes(65, 256, 4096) == 2 * 4 * 65 * 16
+    assert binding.fq_w4a8_gemm_workspace_bytes(2048, 4096, 11008) == 2 * 12 * 2048 * 16
+    assert binding.fq_w4a8_gemm_workspace_bytes(128, 256, 100) == 0      # invalid shape
     assert binding.status_string(-99) == "unknown status"
 
 
@@ -57,6 +62,15 @@ def test_bad_arguments_are_rejected_without_a_launch():
     assert L.fq_w4a8_gemm(p, p, p, p, f1, null, 4, 32, 128, null) == -1
     assert L.fq_w4a8_gemm(odd, p, p, p, f1, p, 4, 32, 128, null) == -3
     assert L.fq_w4a8_gemm(p, p, odd, p, f1, p, 4, 32, 128, null) == -3
+    # the explicit-workspace variant: same checks, plus the workspace itself
+    ws = (p, ctypes.c_size_t(1 << 30))
+    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 4, 32, 100, *ws, null) == -2
+    assert L.fq_w4a8_gemm_ws(null, null, null, null, f1, null, 0, 32, 128, null, ctypes.c_size_t(0), null) == 0
+    assert L.fq_w4a8_gemm_ws(null, p, p, p, f1, p, 128, 32, 128, *ws, null) == -1
+    assert L.fq_w4a8_gemm_ws(p, p, p, odd, f1, p, 128, 32, 128, *ws, null) == -3
+    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, null, ctypes.c_size_t(0), null) == -5
+    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, p, ctypes.c_size_t(100), null) == -5
+    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, odd, ctypes.c_size_t(1 << 30), null) == -3
     assert L.fq_quantize_act(p, p, p, 4, 12, null) == -2
     assert L.fq_quantize_act(p, p, p, 0, 128, null) == 0
     assert L.fq_quantize_act(null, p, p, 4, 128, null) == -1

@@ -222,6 +222,32 @@ def test_gemm_invariants_on_gpu(fq, kernel_choice):
     assert np.array_equal(_run_gemm(fq, A, a, q, gs, t), Y1)
 
 
+def test_own_workspace_and_callers_workspace_agree(fq):
+    """fq_w4a8_gemm (library-owned workspace) and fq_w4a8_gemm_ws (caller's) give the same bits;
+    a workspace that is too small is refused before anything is launched."""
+    import ctypes
+    M, N, K = 300, 256, 1024
+    A, a, q, gs, t = _rand_codes(M, N, K, seed=21)
+    Ad, ad, gd = _gpu(A), _gpu(a), _gpu(gs)
+    packed = fq.fq_pack_weights(_gpu(q))
+    need = fq.fq_w4a8_gemm_workspace_bytes(M, N, K)
+    assert need > 0
+    Y_ws = fq.fq_w4a8_gemm(Ad, ad, packed, gd, t, N, workspace=torch.empty(need + 64, dtype=torch.uint8, device="cuda"))
+    Y_own = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    L = fq.lib()
+    for _ in range(2):                                   # second call: the library's buffer already exists
+        rc = L.fq_w4a8_gemm(Ad.data_ptr(), ad.data_ptr(), packed.data_ptr(), gd.data_ptr(), ctypes.c_float(t),
+                            Y_own.data_ptr(), M, N, K, ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0
+    torch.cuda.synchronize()
+    assert torch.equal(Y_own.view(torch.int16), Y_ws.view(torch.int16))
+    Y, B = oracle.w4a8_gemm(A, a, q, gs, t, want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Y_own), Y, B, "library-owned workspace")
+    small = torch.empty(need - 16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(fq.FireqError):
+        fq.fq_w4a8_gemm(Ad, ad, packed, gd, t, N, workspace=small)
+
+
 def test_m_zero_is_a_noop(fq):
     packed = torch.zeros(fq.fq_packed_weight_bytes(32, 128), dtype=torch.uint8, device="cuda")
     Y = fq.fq_w4a8_gemm(torch.zeros((0, 128), dtype=torch.uint8, device="cuda"),
