@@ -56,12 +56,14 @@ enum {
  *   Y_bf16     [M,N]  row-major bfloat16 bit patterns (output)
  *
  * For M > 64 the kernels need device scratch (the packed codes carry a zero point, and the
- * term that takes it out again, one FP32 number per row and group, is computed first).
+ * term that takes it out again, one number per row of A_fp8 and group, is computed first).
  * fq_w4a8_gemm_ws takes that scratch from the caller: `workspace` is device memory, 16-byte
  * aligned, at least fq_w4a8_gemm_workspace_bytes(M,N,K) bytes (0 = none needed, NULL is fine
- * then); its contents are overwritten, and it may be reused or freed once the work enqueued
- * by the call has finished.  That variant allocates nothing, keeps no state and never
- * synchronises.  fq_w4a8_gemm is the same call on a workspace the library owns: one device
+ * then); it may be reused or freed once the work enqueued by the call has finished.  With
+ * workspace_prepared == 0 the call fills the workspace itself (one more small kernel); with
+ * workspace_prepared != 0 it takes the contents as they are, which must then have been written
+ * by fq_quantize_act_ws for this very A_fp8 (same M and K).  That variant allocates nothing,
+ * keeps no state and never synchronises.  fq_w4a8_gemm is the same call on a workspace the library owns: one device
  * buffer for the whole process that grows (hipFree + hipMalloc, which synchronise the device)
  * when a call needs more than any call before it, so calls that overlap on different streams
  * race on it, and a first call must not be made under stream capture.
@@ -69,7 +71,8 @@ enum {
 size_t fq_w4a8_gemm_workspace_bytes(int M, int N, int K);
 int fq_w4a8_gemm_ws(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
                     const uint8_t *w_gscale, float w_tscale, uint16_t *Y_bf16,
-                    int M, int N, int K, void *workspace, size_t workspace_bytes, void *stream);
+                    int M, int N, int K, void *workspace, size_t workspace_bytes,
+                    int workspace_prepared, void *stream);
 int fq_w4a8_gemm(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
                  const uint8_t *w_gscale, float w_tscale, uint16_t *Y_bf16,
                  int M, int N, int K, void *stream);
@@ -85,6 +88,15 @@ int fq_w4a8_gemm(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_p
  */
 int fq_quantize_act(const uint16_t *X_bf16, uint8_t *A_fp8, float *a_scale,
                     int M, int K, void *stream);
+
+/*
+ * fq_quantize_act that also prepares the workspace of the GEMM that consumes A_fp8 (see
+ * fq_w4a8_gemm_ws: pass workspace_prepared = 1 there).  K must be a multiple of 128 here;
+ * `workspace` must hold at least fq_w4a8_gemm_workspace_bytes(M, N, K) bytes for an M > 64
+ * (the size does not depend on N), 16-byte aligned; FQ_ERR_MEMORY otherwise.
+ */
+int fq_quantize_act_ws(const uint16_t *X_bf16, uint8_t *A_fp8, float *a_scale, int M, int K,
+                       void *workspace, size_t workspace_bytes, void *stream);
 
 /*
  * Offline weight packing (Sec. 3.1: INT4 weights in groups of 128).  The paper does not

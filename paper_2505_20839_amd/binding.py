@@ -37,7 +37,9 @@ def lib() -> ctypes.CDLL:
     L.fq_w4a8_gemm.restype = ci
     L.fq_w4a8_gemm.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
     L.fq_w4a8_gemm_ws.restype = ci
-    L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, vp]
+    L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
+    L.fq_quantize_act_ws.restype = ci
+    L.fq_quantize_act_ws.argtypes = [vp, vp, vp, ci, ci, vp, ctypes.c_size_t, vp]
     L.fq_w4a8_gemm_workspace_bytes.restype = ctypes.c_size_t
     L.fq_w4a8_gemm_workspace_bytes.argtypes = [ci, ci, ci]
     L.fq_quantize_act.restype = ci
@@ -107,13 +109,20 @@ def fq_unpack_weights(packed: torch.Tensor, N: int, K: int) -> torch.Tensor:
     return out
 
 
-def fq_quantize_act(X: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
-    """bf16 [M,K] -> (uint8 [M,K] E4M3 codes, float32 [M] per-row scales)."""
+def fq_quantize_act(X: torch.Tensor, workspace: Optional[torch.Tensor] = None) -> Tuple[torch.Tensor, torch.Tensor]:
+    """bf16 [M,K] -> (uint8 [M,K] E4M3 codes, float32 [M] per-row scales).
+
+    With `workspace` (a device tensor of fq_w4a8_gemm_workspace_bytes(M, N, K) bytes or more) the call is
+    fq_quantize_act_ws, which also prepares that workspace for fq_w4a8_gemm(..., workspace_prepared=True)."""
     X = _dev(X, torch.bfloat16, "X")
     M, K = X.shape
     A = torch.empty((M, K), dtype=torch.uint8, device=X.device)
     s = torch.empty((M,), dtype=torch.float32, device=X.device)
-    rc = lib().fq_quantize_act(X.data_ptr(), A.data_ptr(), s.data_ptr(), M, K, _stream())
+    if workspace is None:
+        rc = lib().fq_quantize_act(X.data_ptr(), A.data_ptr(), s.data_ptr(), M, K, _stream())
+    else:
+        rc = lib().fq_quantize_act_ws(X.data_ptr(), A.data_ptr(), s.data_ptr(), M, K, workspace.data_ptr(),
+                                      workspace.numel() * workspace.element_size(), _stream())
     if rc != 0:
         raise FireqError(rc, "fq_quantize_act")
     return A, s
@@ -121,11 +130,13 @@ def fq_quantize_act(X: torch.Tensor) -> Tuple[torch.Tensor, torch.Tensor]:
 
 def fq_w4a8_gemm(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor,
                  w_gscale: torch.Tensor, w_tscale: float, N: int,
-                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+                 out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                 workspace_prepared: bool = False) -> torch.Tensor:
     """Y[M,N] (bf16) = W4A8-FP GEMM of E4M3 activations and packed INT4 weights.
 
     Calls fq_w4a8_gemm_ws; `workspace` (a device tensor of at least
-    fq_w4a8_gemm_workspace_bytes(M, N, K) bytes) is allocated here when not given."""
+    fq_w4a8_gemm_workspace_bytes(M, N, K) bytes) is allocated here when not given;
+    `workspace_prepared` says that fq_quantize_act(X, workspace) has filled it for this A."""
     A = _dev(A, torch.uint8, "A")
     a_scale = _dev(a_scale, torch.float32, "a_scale")
     Wq_packed = _dev(Wq_packed, torch.uint8, "Wq_packed")
@@ -147,7 +158,8 @@ def fq_w4a8_gemm(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor
     ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (0, 0)
     rc = lib().fq_w4a8_gemm_ws(A.data_ptr(), a_scale.data_ptr(), Wq_packed.data_ptr(),
                                w_gscale.data_ptr(), ctypes.c_float(float(w_tscale)), out.data_ptr(),
-                               M, N, K, ws_ptr, ws_bytes, _stream())
+                               M, N, K, ws_ptr, ws_bytes, 1 if (workspace_prepared and workspace is not None) else 0,
+                               _stream())
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_ws")
     return out

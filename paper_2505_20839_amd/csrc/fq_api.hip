@@ -86,9 +86,28 @@ size_t fq_w4a8_gemm_workspace_bytes(int M, int N, int K) {
     return choose_kernel(M) == GemmKernel::Large ? fq_gemm_large_workspace_bytes(M, K) : 0;
 }
 
+int fq_quantize_act_ws(const uint16_t* X_bf16, uint8_t* A_fp8, float* a_scale, int M, int K,
+                       void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
+    if (M == 0) return FQ_OK;
+    if (!X_bf16 || !A_fp8 || !a_scale) return FQ_ERR_NULL;
+    if (!aligned16(X_bf16) || !aligned16(A_fp8)) return FQ_ERR_ALIGN;
+    if (!workspace || workspace_bytes < fq_gemm_large_workspace_bytes(M, K)) return FQ_ERR_MEMORY;
+    if (!aligned16(workspace)) return FQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (fq_quantize_can_write_zero_point(K)) {
+        fq_launch_quantize_zp(X_bf16, A_fp8, a_scale, M, K, workspace, s);
+    } else {                                              // very long rows: two kernels
+        fq_launch_quantize(X_bf16, A_fp8, a_scale, M, K, s);
+        fq_launch_zero_point(A_fp8, workspace, M, K, s);
+    }
+    return after_launch();
+}
+
 int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
                     const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
-                    int M, int N, int K, void* workspace, size_t workspace_bytes, void* stream) {
+                    int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
+                    void* stream) {
     if (M < 0 || N < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
     if (M == 0) return FQ_OK;
     if (N == 0) return FQ_ERR_SHAPE;
@@ -104,7 +123,10 @@ int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* W
     switch (choose_kernel(M)) {
         case GemmKernel::Simple: fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
         case GemmKernel::Small:  fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
-        default: fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace, s); break;
+        default:
+            fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace,
+                                 workspace_prepared != 0, s);
+            break;
     }
     return after_launch();
 }
@@ -126,7 +148,7 @@ int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_p
         }
         ws_bytes = need;
     }
-    return fq_w4a8_gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, ws, ws_bytes, stream);
+    return fq_w4a8_gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, ws, ws_bytes, 0, stream);
 }
 
 }  // extern "C"

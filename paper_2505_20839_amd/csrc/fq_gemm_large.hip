@@ -144,37 +144,38 @@ __host__ __device__ inline fql_split fql_xcd_split(int x, int ntiles, int slots)
 
 }  // namespace
 
-// Eight lanes per (row m, group g < 8 * C2): each sums 16 of the group's 128 activations, the eight
-// partial sums are added across lanes, and the first lane writes the two fp16 terms of -2^-6 * sum
-// (zeros for the padding groups g >= G).
+// One workgroup per row m; eight lanes per group g < 8 * C2: each sums 16 of the group's 128
+// activations, the eight partial sums are added across lanes, and the first lane writes the two
+// fp16 terms of -2^-6 * sum (zeros for the padding groups g >= G).
 __global__ __launch_bounds__(256) void fq_zero_point_kernel(const uint8_t* __restrict__ A, uint16_t* __restrict__ planes,
                                                             int M, int K) {
     const int G = K / FQ_GROUP, C2 = fql_c2(G), G8 = 8 * C2;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const int sub = (int)(idx & 7);
-    const size_t pair = idx >> 3;
-    const int g = (int)(pair % (size_t)G8);
-    const size_t m = pair / (size_t)G8;
-    float z = 0.f;
-    if (m < (size_t)M && g < G) {
-        const fq_v4i v = *reinterpret_cast<const fq_v4i*>(A + m * (size_t)K + (size_t)g * FQ_GROUP + 16 * sub);
+    const int m = blockIdx.x;
+    const int sub = threadIdx.x & 7;
+    const uint8_t* row = A + (size_t)m * K + 16 * sub;
+    for (int g = threadIdx.x >> 3; g < G8; g += 32) {
+        float z = 0.f;
+        if (g < G) {
+            const fq_v4i v = *reinterpret_cast<const fq_v4i*>(row + (size_t)g * FQ_GROUP);
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], false);
-            const fq_v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], true);
-            z += (lo[0] + lo[1]) + (hi[0] + hi[1]);
+            for (int j = 0; j < 4; ++j) {
+                const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], false);
+                const fq_v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], true);
+                z += (lo[0] + lo[1]) + (hi[0] + hi[1]);
+            }
+        }
+        z += __shfl_xor(z, 1, 64);
+        z += __shfl_xor(z, 2, 64);
+        z += __shfl_xor(z, 4, 64);
+        if (sub == 0) {
+            z *= -0.015625f;
+            const _Float16 hi = (_Float16)z;                      // round to nearest even
+            const _Float16 lo = (_Float16)(z - (float)hi);        // the difference is exact in FP32
+            const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
+            planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, hi);
+            planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, lo);
         }
     }
-    z += __shfl_xor(z, 1, 64);
-    z += __shfl_xor(z, 2, 64);
-    z += __shfl_xor(z, 4, 64);
-    if (sub != 0 || m >= (size_t)M) return;
-    z *= -0.015625f;
-    const _Float16 hi = (_Float16)z;                      // round to nearest even
-    const _Float16 lo = (_Float16)(z - (float)hi);        // the difference is exact in FP32
-    const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
-    planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, hi);
-    planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, lo);
 }
 
 // One item: NMT row tiles of 32 rows (8, or 4 for the half tiles) x 128 channels.  `bid` counts the
@@ -508,8 +509,14 @@ size_t fq_gemm_large_workspace_bytes(int M, int K) {
     return (size_t)FQL_ZPLANES * fql_c2(K / FQ_GROUP) * (size_t)M * 16;
 }
 
+void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipStream_t stream) {
+    hipLaunchKernelGGL(fq_zero_point_kernel, dim3((unsigned)M), dim3(256), 0, stream, A,
+                       static_cast<uint16_t*>(workspace), M, K);
+}
+
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                          float tscale, uint16_t* Y, int M, int N, int K, void* workspace, hipStream_t stream) {
+                          float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
+                          hipStream_t stream) {
     static bool attr_set = false;
     static int cus = 256;
     if (!attr_set) {
@@ -521,11 +528,7 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
         attr_set = true;
     }
     uint16_t* planes = static_cast<uint16_t*>(workspace); // zero-point planes
-    {
-        const size_t threads = (size_t)M * 8 * fql_c2(K / FQ_GROUP) * 8;
-        hipLaunchKernelGGL(fq_zero_point_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, stream,
-                           A, planes, M, K);
-    }
+    if (!prepared) fq_launch_zero_point(A, workspace, M, K, stream);
     const int tiles_m = (M + FQL_BM - 1) / FQL_BM, tiles_n = (N + FQL_BN - 1) / FQL_BN;
     int slots = 2 * cus / FQL_XCDS;                       // resident workgroups per XCD: two per compute unit
     if (slots < 1) slots = 1;

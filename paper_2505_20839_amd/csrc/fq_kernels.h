@@ -8,14 +8,22 @@
 void fq_launch_pack(const int8_t* q, uint8_t* wp, int N, int K, hipStream_t stream);
 void fq_launch_unpack(const uint8_t* wp, int8_t* q, int N, int K, hipStream_t stream);
 void fq_launch_quantize(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, hipStream_t stream);
+// The same, also filling the large-M GEMM's workspace (fq_gemm_large_workspace_bytes(M, K)) with the
+// zero-point terms of A; only for shapes fq_quantize_can_write_zero_point(K) accepts.
+bool fq_quantize_can_write_zero_point(int K);
+void fq_launch_quantize_zp(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, void* workspace,
+                           hipStream_t stream);
 
 // GEMM kernels.  `which` selects the kernel: see fq_api.hip.
 void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                            float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);
-// The large-M kernels need fq_gemm_large_workspace_bytes(M, K) bytes of device scratch (16-byte aligned):
-// a first kernel writes the zero-point term of every (row, group) there, the GEMM kernels read it.
+// The large-M kernel needs fq_gemm_large_workspace_bytes(M, K) bytes of device scratch (16-byte aligned)
+// holding the zero-point term of every (row, group) of A: fq_launch_zero_point writes it, and
+// fq_launch_gemm_large calls that first unless `prepared` says the workspace already holds it.
 size_t fq_gemm_large_workspace_bytes(int M, int K);
+void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipStream_t stream);
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                          float tscale, uint16_t* Y, int M, int N, int K, void* workspace, hipStream_t stream);
+                          float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
+                          hipStream_t stream);
 void fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);

@@ -34,11 +34,24 @@ __device__ __forceinline__ unsigned fq_quant4(float a, float b, float c, float d
     return (unsigned)r;
 }
 
+// Sum of the eight E4M3 values of two words of codes.
+__device__ __forceinline__ float fq_sum8(fq_v2i o) {
+    const fq_v2f a = __builtin_amdgcn_cvt_pk_f32_fp8(o[0], false), b = __builtin_amdgcn_cvt_pk_f32_fp8(o[0], true);
+    const fq_v2f c = __builtin_amdgcn_cvt_pk_f32_fp8(o[1], false), d = __builtin_amdgcn_cvt_pk_f32_fp8(o[1], true);
+    return ((a[0] + a[1]) + (b[0] + b[1])) + ((c[0] + c[1]) + (d[0] + d[1]));
+}
+
 // One workgroup per row.  The row is read once into registers when it fits (K <= 16384),
 // otherwise it is read a second time for the conversion pass.
+// ZP: also write, for every group of 128 codes of the row, the zero-point term the large-M GEMM
+// kernels take from their workspace: -2^-6 * (sum of the group's E4M3 values) as two fp16 terms,
+// laid out as that kernel reads it ([plane][group / 8][M rows][group % 8]; groups up to the next
+// multiple of 16 are zero).  Needs K % 128 == 0 and the row in registers.
+template <bool ZP>
 __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_t* __restrict__ X,
                                                                    uint8_t* __restrict__ A,
-                                                                   float* __restrict__ a_scale, int K) {
+                                                                   float* __restrict__ a_scale, int K,
+                                                                   uint16_t* __restrict__ planes, int M) {
     __shared__ float red[FQ_Q_THREADS / 64];
     const int m = blockIdx.x;
     const fq_v4i* x = reinterpret_cast<const fq_v4i*>(X + (size_t)m * K);
@@ -82,6 +95,32 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
                 o[0] = (int)fq_quant4(fq_bf16_lo(v[0]), fq_bf16_hi(v[0]), fq_bf16_lo(v[1]), fq_bf16_hi(v[1]), s);
                 o[1] = (int)fq_quant4(fq_bf16_lo(v[2]), fq_bf16_hi(v[2]), fq_bf16_lo(v[3]), fq_bf16_hi(v[3]), s);
                 a[c] = o;
+                if (ZP) {
+                    // a group is 16 consecutive chunks = 16 consecutive lanes (nchunk is a multiple of 16,
+                    // so a group's lanes are all here or all absent)
+                    float z = fq_sum8(o);
+                    z += __shfl_xor(z, 1, 64);
+                    z += __shfl_xor(z, 2, 64);
+                    z += __shfl_xor(z, 4, 64);
+                    z += __shfl_xor(z, 8, 64);
+                    if ((threadIdx.x & 15) == 0) {
+                        const int g = c >> 4, C2 = 2 * (((K >> 7) + 15) >> 4);
+                        z *= -0.015625f;
+                        const _Float16 hi = (_Float16)z;                  // round to nearest even
+                        const _Float16 lo = (_Float16)(z - (float)hi);    // the difference is exact in FP32
+                        const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
+                        planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, hi);
+                        planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, lo);
+                    }
+                }
+            }
+        }
+        if (ZP) {                                         // padding groups
+            const int G = K >> 7, C2 = 2 * ((G + 15) >> 4);
+            for (int g = G + threadIdx.x; g < 8 * C2; g += FQ_Q_THREADS) {
+                const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
+                planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = 0;
+                planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = 0;
             }
         }
     } else {
@@ -96,5 +135,16 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
 }
 
 void fq_launch_quantize(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, hipStream_t stream) {
-    hipLaunchKernelGGL(fq_quantize_kernel, dim3((unsigned)M), dim3(FQ_Q_THREADS), 0, stream, X, A, a_scale, K);
+    hipLaunchKernelGGL(fq_quantize_kernel<false>, dim3((unsigned)M), dim3(FQ_Q_THREADS), 0, stream, X, A, a_scale, K,
+                       static_cast<uint16_t*>(nullptr), M);
+}
+
+bool fq_quantize_can_write_zero_point(int K) {
+    return (K % FQ_GROUP) == 0 && (K >> 3) <= FQ_Q_THREADS * FQ_Q_MAXCHUNK;
+}
+
+void fq_launch_quantize_zp(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, void* workspace,
+                           hipStream_t stream) {
+    hipLaunchKernelGGL(fq_quantize_kernel<true>, dim3((unsigned)M), dim3(FQ_Q_THREADS), 0, stream, X, A, a_scale, K,
+                       static_cast<uint16_t*>(workspace), M);
 }

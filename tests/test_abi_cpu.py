@@ -20,7 +20,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     L = binding.lib()
     names = _declared_functions()
-    assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_packed_weight_bytes", "fq_pack_weights",
+    assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_quantize_act_ws", "fq_packed_weight_bytes", "fq_pack_weights",
                             "fq_unpack_weights", "fq_layout_version", "fq_status_string"])
     for name in names:
         assert hasattr(L, name), name
@@ -63,14 +63,20 @@ def test_bad_arguments_are_rejected_without_a_launch():
     assert L.fq_w4a8_gemm(odd, p, p, p, f1, p, 4, 32, 128, null) == -3
     assert L.fq_w4a8_gemm(p, p, odd, p, f1, p, 4, 32, 128, null) == -3
     # the explicit-workspace variant: same checks, plus the workspace itself
-    ws = (p, ctypes.c_size_t(1 << 30))
+    ws = (p, ctypes.c_size_t(1 << 30), 0)
     assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 4, 32, 100, *ws, null) == -2
-    assert L.fq_w4a8_gemm_ws(null, null, null, null, f1, null, 0, 32, 128, null, ctypes.c_size_t(0), null) == 0
+    assert L.fq_w4a8_gemm_ws(null, null, null, null, f1, null, 0, 32, 128, null, ctypes.c_size_t(0), 0, null) == 0
     assert L.fq_w4a8_gemm_ws(null, p, p, p, f1, p, 128, 32, 128, *ws, null) == -1
     assert L.fq_w4a8_gemm_ws(p, p, p, odd, f1, p, 128, 32, 128, *ws, null) == -3
-    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, null, ctypes.c_size_t(0), null) == -5
-    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, p, ctypes.c_size_t(100), null) == -5
-    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, odd, ctypes.c_size_t(1 << 30), null) == -3
+    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, null, ctypes.c_size_t(0), 0, null) == -5
+    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, p, ctypes.c_size_t(100), 1, null) == -5
+    assert L.fq_w4a8_gemm_ws(p, p, p, p, f1, p, 128, 32, 128, odd, ctypes.c_size_t(1 << 30), 0, null) == -3
+    assert L.fq_quantize_act_ws(p, p, p, 4, 100, p, ctypes.c_size_t(1 << 30), null) == -2      # K % 128
+    assert L.fq_quantize_act_ws(p, p, p, 0, 128, null, ctypes.c_size_t(0), null) == 0
+    assert L.fq_quantize_act_ws(null, p, p, 4, 128, p, ctypes.c_size_t(1 << 30), null) == -1
+    assert L.fq_quantize_act_ws(p, p, p, 4, 128, null, ctypes.c_size_t(0), null) == -5
+    assert L.fq_quantize_act_ws(p, p, p, 4, 128, p, ctypes.c_size_t(8), null) == -5
+    assert L.fq_quantize_act_ws(p, p, p, 4, 128, odd, ctypes.c_size_t(1 << 30), null) == -3
     assert L.fq_quantize_act(p, p, p, 4, 12, null) == -2
     assert L.fq_quantize_act(p, p, p, 0, 128, null) == 0
     assert L.fq_quantize_act(null, p, p, 4, 128, null) == -1

@@ -248,6 +248,30 @@ def test_own_workspace_and_callers_workspace_agree(fq):
         fq.fq_w4a8_gemm(Ad, ad, packed, gd, t, N, workspace=small)
 
 
+@pytest.mark.parametrize("M,N,K", [(300, 256, 1024), (130, 96, 11008), (257, 160, 128)])
+def test_quantiser_prepares_the_gemm_workspace(fq, M, N, K):
+    """fq_quantize_act_ws writes the same codes and scales as fq_quantize_act, and the workspace it
+    prepares gives the GEMM the oracle's result (and, up to FP32 summation order, the result of the
+    GEMM that prepares the workspace itself)."""
+    d = workloads.draw(M, N, K, seed=M + K)
+    X = to_gpu_bf16(d["X_bf16"])
+    A0, s0 = fq.fq_quantize_act(X)
+    need = fq.fq_w4a8_gemm_workspace_bytes(M, N, K)
+    ws = torch.full((need + 32,), 0xFF, dtype=torch.uint8, device="cuda")    # stale contents must not matter
+    A1, s1 = fq.fq_quantize_act(X, workspace=ws)
+    assert torch.equal(A0, A1) and torch.equal(s0, s1)
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    gd = _gpu(d["gscale"])
+    Y_prep = fq.fq_w4a8_gemm(A1, s1, packed, gd, d["w_tscale"], N, workspace=ws, workspace_prepared=True)
+    Y_self = fq.fq_w4a8_gemm(A0, s0, packed, gd, d["w_tscale"], N)
+    torch.cuda.synchronize()
+    Y, B = oracle.w4a8_gemm(A0.cpu().numpy(), s0.cpu().numpy(), d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Y_prep), Y, B, "prepared workspace")
+    check_gemm(bf16_bits_from_gpu(Y_self), Y, B, "own pre-pass")
+    diff = np.abs(oracle.bf16_bits_to_f64(bf16_bits_from_gpu(Y_prep)) - oracle.bf16_bits_to_f64(bf16_bits_from_gpu(Y_self)))
+    assert np.all(diff <= oracle.bf16_ulp_array(Y) + 1e-5 * B)
+
+
 def test_m_zero_is_a_noop(fq):
     packed = torch.zeros(fq.fq_packed_weight_bytes(32, 128), dtype=torch.uint8, device="cuda")
     Y = fq.fq_w4a8_gemm(torch.zeros((0, 128), dtype=torch.uint8, device="cuda"),
