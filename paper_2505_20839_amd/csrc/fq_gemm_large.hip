@@ -144,37 +144,49 @@ __host__ __device__ inline fql_split fql_xcd_split(int x, int ntiles, int slots)
 
 }  // namespace
 
-// One workgroup per row m; eight lanes per group g < 8 * C2: each sums 16 of the group's 128
-// activations, the eight partial sums are added across lanes, and the first lane writes the two
-// fp16 terms of -2^-6 * sum (zeros for the padding groups g >= G).
+// One workgroup per row m; eight lanes per group: each sums 16 of the group's 128 activations, the
+// eight partial sums are added across lanes, the two fp16 terms of -2^-6 * sum are collected in LDS
+// (zeros for the padding groups g >= G) and leave as one 16-byte store per (plane, 8 groups).
+#define FQL_ZP_MAXG 1024                                  // groups per row the LDS row buffer holds
 __global__ __launch_bounds__(256) void fq_zero_point_kernel(const uint8_t* __restrict__ A, uint16_t* __restrict__ planes,
                                                             int M, int K) {
+    __shared__ __attribute__((aligned(16))) uint16_t zrow[2][FQL_ZP_MAXG];
     const int G = K / FQ_GROUP, C2 = fql_c2(G), G8 = 8 * C2;
     const int m = blockIdx.x;
     const int sub = threadIdx.x & 7;
     const uint8_t* row = A + (size_t)m * K + 16 * sub;
-    for (int g = threadIdx.x >> 3; g < G8; g += 32) {
-        float z = 0.f;
-        if (g < G) {
-            const fq_v4i v = *reinterpret_cast<const fq_v4i*>(row + (size_t)g * FQ_GROUP);
+    for (int g0 = 0; g0 < G8; g0 += FQL_ZP_MAXG) {        // (one pass unless K > 131072)
+        const int gn = G8 - g0 < FQL_ZP_MAXG ? G8 - g0 : FQL_ZP_MAXG;
+        for (int gl = threadIdx.x >> 3; gl < gn; gl += 32) {
+            const int g = g0 + gl;
+            float z = 0.f;
+            if (g < G) {
+                const fq_v4i v = *reinterpret_cast<const fq_v4i*>(row + (size_t)g * FQ_GROUP);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], false);
-                const fq_v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], true);
-                z += (lo[0] + lo[1]) + (hi[0] + hi[1]);
+                for (int j = 0; j < 4; ++j) {
+                    const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], false);
+                    const fq_v2f hi = __builtin_amdgcn_cvt_pk_f32_fp8(v[j], true);
+                    z += (lo[0] + lo[1]) + (hi[0] + hi[1]);
+                }
+            }
+            z += __shfl_xor(z, 1, 64);
+            z += __shfl_xor(z, 2, 64);
+            z += __shfl_xor(z, 4, 64);
+            if (sub == 0) {
+                z *= -0.015625f;
+                const _Float16 hi = (_Float16)z;                  // round to nearest even
+                const _Float16 lo = (_Float16)(z - (float)hi);    // the difference is exact in FP32
+                zrow[0][gl] = __builtin_bit_cast(uint16_t, hi);
+                zrow[1][gl] = __builtin_bit_cast(uint16_t, lo);
             }
         }
-        z += __shfl_xor(z, 1, 64);
-        z += __shfl_xor(z, 2, 64);
-        z += __shfl_xor(z, 4, 64);
-        if (sub == 0) {
-            z *= -0.015625f;
-            const _Float16 hi = (_Float16)z;                      // round to nearest even
-            const _Float16 lo = (_Float16)(z - (float)hi);        // the difference is exact in FP32
-            const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
-            planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, hi);
-            planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, lo);
+        __syncthreads();
+        for (int t = threadIdx.x; t < 2 * (gn >> 3); t += 256) {
+            const int plane = t / (gn >> 3), ul = t - plane * (gn >> 3);
+            const fq_v4i v = *reinterpret_cast<const fq_v4i*>(&zrow[plane][8 * ul]);
+            *reinterpret_cast<fq_v4i*>(planes + (((size_t)plane * C2 + (g0 >> 3) + ul) * M + m) * 8) = v;
         }
+        __syncthreads();
     }
 }
 

@@ -53,6 +53,7 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
                                                                    float* __restrict__ a_scale, int K,
                                                                    uint16_t* __restrict__ planes, int M) {
     __shared__ float red[FQ_Q_THREADS / 64];
+    __shared__ __attribute__((aligned(16))) uint16_t zrow[2][FQ_Q_THREADS * FQ_Q_MAXCHUNK / 16 + 16];   // [plane][group]
     const int m = blockIdx.x;
     const fq_v4i* x = reinterpret_cast<const fq_v4i*>(X + (size_t)m * K);
     fq_v2i* a = reinterpret_cast<fq_v2i*>(A + (size_t)m * K);
@@ -65,11 +66,13 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
         for (int i = 0; i < FQ_Q_MAXCHUNK; ++i) {
             int c = threadIdx.x + i * FQ_Q_THREADS;
             keep[i] = (fq_v4i){0, 0, 0, 0};
-            if (c < nchunk) keep[i] = x[c];
+            if (c < nchunk) {
+                keep[i] = x[c];
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                unsigned w = (unsigned)keep[i][j];
-                amax = fmaxf(amax, fmaxf(fabsf(fq_bf16_lo(w)), fabsf(fq_bf16_hi(w))));
+                for (int j = 0; j < 4; ++j) {
+                    unsigned w = (unsigned)keep[i][j];
+                    amax = fmaxf(amax, fmaxf(fabsf(fq_bf16_lo(w)), fabsf(fq_bf16_hi(w))));
+                }
             }
         }
     } else {
@@ -104,23 +107,24 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
                     z += __shfl_xor(z, 4, 64);
                     z += __shfl_xor(z, 8, 64);
                     if ((threadIdx.x & 15) == 0) {
-                        const int g = c >> 4, C2 = 2 * (((K >> 7) + 15) >> 4);
                         z *= -0.015625f;
                         const _Float16 hi = (_Float16)z;                  // round to nearest even
                         const _Float16 lo = (_Float16)(z - (float)hi);    // the difference is exact in FP32
-                        const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
-                        planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, hi);
-                        planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = __builtin_bit_cast(uint16_t, lo);
+                        zrow[0][c >> 4] = __builtin_bit_cast(uint16_t, hi);
+                        zrow[1][c >> 4] = __builtin_bit_cast(uint16_t, lo);
                     }
                 }
             }
         }
-        if (ZP) {                                         // padding groups
+        if (ZP) {
+            // padding groups are zero; then one 16-byte store per (plane, 8 groups) of this row
             const int G = K >> 7, C2 = 2 * ((G + 15) >> 4);
-            for (int g = G + threadIdx.x; g < 8 * C2; g += FQ_Q_THREADS) {
-                const size_t unit = (size_t)(g >> 3), e = (size_t)(g & 7);
-                planes[(((size_t)0 * C2 + unit) * M + m) * 8 + e] = 0;
-                planes[(((size_t)1 * C2 + unit) * M + m) * 8 + e] = 0;
+            for (int g = G + threadIdx.x; g < 8 * C2; g += FQ_Q_THREADS) zrow[0][g] = zrow[1][g] = 0;
+            __syncthreads();
+            for (int t = threadIdx.x; t < 2 * C2; t += FQ_Q_THREADS) {
+                const int plane = t / C2, unit = t - plane * C2;
+                const fq_v4i v = *reinterpret_cast<const fq_v4i*>(&zrow[plane][8 * unit]);
+                *reinterpret_cast<fq_v4i*>(planes + (((size_t)plane * C2 + unit) * M + m) * 8) = v;
             }
         }
     } else {
