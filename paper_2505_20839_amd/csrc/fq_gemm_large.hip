@@ -457,20 +457,26 @@ __device__ __forceinline__ void fql_item(
         // both, and the two halves go to their rows with 16-bit LDS writes.
         char* tile = reinterpret_cast<char*>(lds);
         char* wcol = tile + 4 * (lane >> 5) * FQL_OUT_STRIDE + (wave * 32 + (lane & 31)) * 2;
+        // The row factors are fetched from LDS three steps (of four rows) ahead of their use: the
+        // compiler may not move these reads across the tile writes, so the distance is spelled out.
+        constexpr int AHEAD = 3;
+        const float* oscl = osc + 4 * (lane >> 5);
+        fq_v4f scq[AHEAD + 1];
 #pragma unroll
-        for (int mt = 0; mt < NMT; ++mt) {
+        for (int it = 0; it < AHEAD; ++it) scq[it] = *reinterpret_cast<const fq_v4f*>(&oscl[8 * it]);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {                 // rows 8j + 4*(lane/32) + 0..3 of the 32x32 tile
-                const int rl = 8 * j + 4 * (lane >> 5);
-                const fq_v4f sc4 = *reinterpret_cast<const fq_v4f*>(&osc[mt * 32 + rl]);
+        for (int it = 0; it < 4 * NMT; ++it) {            // step it: rows 8 * it + 4 * (lane / 32) + 0..3 of the item
+            const int mt = it >> 2, j = it & 3;
+            if (it + AHEAD < 4 * NMT)
+                scq[(it + AHEAD) % (AHEAD + 1)] = *reinterpret_cast<const fq_v4f*>(&oscl[8 * (it + AHEAD)]);
+            const fq_v4f sc4 = scq[it % (AHEAD + 1)];
 #pragma unroll
-                for (int e = 0; e < 4; e += 2) {
-                    const fq_v2f pr = {acc[mt][4 * j + e] * sc4[e], acc[mt][4 * j + e + 1] * sc4[e + 1]};
-                    const unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, fq_v2bf));
-                    char* dst = wcol + (mt * 32 + 8 * j + e) * FQL_OUT_STRIDE;
-                    *reinterpret_cast<unsigned short*>(dst) = (unsigned short)pk;
-                    *reinterpret_cast<unsigned short*>(dst + FQL_OUT_STRIDE) = (unsigned short)(pk >> 16);
-                }
+            for (int e = 0; e < 4; e += 2) {
+                const fq_v2f pr = {acc[mt][4 * j + e] * sc4[e], acc[mt][4 * j + e + 1] * sc4[e + 1]};
+                const unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, fq_v2bf));
+                char* dst = wcol + (8 * it + e) * FQL_OUT_STRIDE;
+                *reinterpret_cast<unsigned short*>(dst) = (unsigned short)pk;
+                *reinterpret_cast<unsigned short*>(dst + FQL_OUT_STRIDE) = (unsigned short)(pk >> 16);
             }
         }
         __syncthreads();
