@@ -222,6 +222,7 @@ __device__ __forceinline__ void fql_item(
         const int tn = rem / ph, tm = panel * pm + (rem - tn * ph);
         m0 = tm * FQL_BM + half * 128;
         n0 = tn * FQL_BN;
+        if (m0 >= M) return;                              // a second half without rows
     }
     const int nw0 = n0 + wave * 32;                       // first output channel of this wave
     const bool wave_on = nw0 < N;                         // waves past N compute a duplicate tile and store nothing
