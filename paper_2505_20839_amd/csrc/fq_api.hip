@@ -122,7 +122,10 @@ int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* W
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (choose_kernel(M)) {
         case GemmKernel::Simple: fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
-        case GemmKernel::Small:  fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
+        case GemmKernel::Small:
+            if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s))
+                fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s);
+            break;
         default:
             fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace,
                                  workspace_prepared != 0, s);

@@ -1,21 +1,17 @@
 // W4A8-FP GEMM for small M (decode, M <= 64): bound by streaming the packed INT4 weights from HBM
 // once (Sec. 1: memory bandwidth is what motivates 4-bit weights).  Same arithmetic as the
 // large-M kernel (Sec. 3.1.1): unpack INT4 to E4M3 in registers, FP8 MFMA with FP32 accumulation,
-// exact FP32 group scale, one rounding to bf16.
+// exact FP32 group scale, one rounding to bf16.  The packed codes carry a zero point of 8; each
+// group's MFMA chain starts from -2^-6 * sum_k a_k, which one more MFMA against a constant operand
+// delivers (the matrix cores are idle at these sizes).
 //
-// Work split.  One workgroup per 32 output channels; its waves split K: wave w takes a contiguous
-// range of 128-wide groups, keeps up to FQS_DEPTH groups of packed weights (2 KiB each) in flight,
-// and accumulates a 32 x 32 (x MT row tiles) partial result.  The partial results of the waves are
-// summed through LDS and written as bf16.  Activations are tiny (M x K bytes) and are read straight
-// from L2 in MFMA operand order.
+// Work split (both kernels).  The output channels are dealt out evenly to one workgroup per compute
+// unit; its 8 waves split K into contiguous slices of groups, so every weight byte is read once
+// overall and every activation byte once per workgroup; the partial sums of the waves are added
+// through LDS.  Activations are tiny (M x K bytes) and come straight from L2 in MFMA operand order.
+#include <cstdlib>
 #include "fq_common.h"
 #include "fq_kernels.h"
-
-#define FQS_THREADS 256
-#define FQS_WAVES (FQS_THREADS / 64)
-#define FQS_DEPTH 8
-
-#define FQ_MFMA(a, b, c) __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4((a), (b), (c), 0, 0, 0, 0, 0, 0)
 
 namespace {
 
@@ -27,113 +23,6 @@ __device__ __forceinline__ fq_v8i fqs_join(fq_v4i lo, fq_v4i hi) {
 }
 
 }  // namespace
-
-template <int MT>
-__global__ __launch_bounds__(FQS_THREADS) void fq_gemm_small_kernel(
-    const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
-    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K) {
-    __shared__ float red[FQS_WAVES][MT][16][64];
-    const int G = K / FQ_GROUP;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int nt = blockIdx.x;
-    const int n = nt * 32 + (lane & 31);
-    const bool n_ok = n < N;
-    const int per = (G + FQS_WAVES - 1) / FQS_WAVES;
-    const int g_begin = wave * per;
-    const int g_end = (g_begin + per < G) ? g_begin + per : G;
-    const uint8_t* wblk = wp + fq_block_offset(nt, 0, G) + (size_t)lane * 16u;
-    const uint8_t* gsrow = gs + (size_t)(n_ok ? n : 0) * G;
-    // this lane's activation rows (clamped: rows past M are computed and dropped)
-    const uint8_t* arow[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t) {
-        int m = t * 32 + (lane & 31);
-        m = m < M ? m : M - 1;
-        arow[t] = A + (size_t)m * K + (lane >> 5) * 32;
-    }
-
-    fq_v16f acc[MT];
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-    fq_v16f zero;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) zero[r] = 0.f;
-
-    fq_v8i zp;
-#pragma unroll
-    for (int r = 0; r < 8; ++r) zp[r] = (int)FQ_ZP_BYTES;
-
-    fq_v4i bq[FQS_DEPTH][2];
-    unsigned sq[FQS_DEPTH];
-#pragma unroll
-    for (int i = 0; i < FQS_DEPTH; ++i) {
-        bq[i][0] = (fq_v4i){0, 0, 0, 0};
-        bq[i][1] = (fq_v4i){0, 0, 0, 0};
-        sq[i] = 0;
-        int g = g_begin + i;
-        if (g < g_end) {
-            const uint8_t* p = wblk + (size_t)g * 2048u;
-            bq[i][0] = __builtin_nontemporal_load(reinterpret_cast<const fq_v4i*>(p));
-            bq[i][1] = __builtin_nontemporal_load(reinterpret_cast<const fq_v4i*>(p + 1024));
-            sq[i] = gsrow[g];
-        }
-    }
-
-    for (int gb = g_begin; gb < g_end; gb += FQS_DEPTH) {
-#pragma unroll
-        for (int i = 0; i < FQS_DEPTH; ++i) {
-            const int g = gb + i;
-            if (g < g_end) {
-                // activations of this group, in operand order: lane (row, kh) holds 32 consecutive k per half
-                fq_v8i a[MT][2];
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    const fq_v4i* ap = reinterpret_cast<const fq_v4i*>(arow[t] + (size_t)g * FQ_GROUP);
-                    a[t][0] = fqs_join(ap[0], ap[1]);
-                    a[t][1] = fqs_join(ap[4], ap[5]);
-                }
-                fq_v8i b0 = fq_unpack_chunk(bq[i][0]);
-                fq_v8i b1 = fq_unpack_chunk(bq[i][1]);
-                float s = __builtin_amdgcn_cvt_f32_fp8((int)sq[i], 0);
-                const int gn = g + FQS_DEPTH;
-                if (gn < g_end) {                         // refill this slot
-                    const uint8_t* p = wblk + (size_t)gn * 2048u;
-                    bq[i][0] = __builtin_nontemporal_load(reinterpret_cast<const fq_v4i*>(p));
-                    bq[i][1] = __builtin_nontemporal_load(reinterpret_cast<const fq_v4i*>(p + 1024));
-                    sq[i] = gsrow[gn];
-                }
-#pragma unroll
-                for (int t = 0; t < MT; ++t) {
-                    fq_v16f p = FQ_MFMA(a[t][0], zp, zero);   // zero point: -2^-6 * sum_k a_k in every column
-                    p = FQ_MFMA(a[t][1], zp, p);
-                    p = FQ_MFMA(a[t][0], b0, p);
-                    p = FQ_MFMA(a[t][1], b1, p);
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) acc[t][r] = fmaf(s, p[r], acc[t][r]);
-                }
-            }
-        }
-    }
-
-    // ---- sum the K-slices of the waves through LDS, scale, write bf16 ----
-#pragma unroll
-    for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) red[wave][t][r][lane] = acc[t][r];
-    __syncthreads();
-    const float outer = tscale * 512.0f;                  // weights were fed in units of 2^-9
-    for (int idx = threadIdx.x; idx < MT * 16 * 64; idx += FQS_THREADS) {
-        int l = idx & 63, r = (idx >> 6) & 15, t = idx >> 10;
-        float v = 0.f;
-#pragma unroll
-        for (int w = 0; w < FQS_WAVES; ++w) v += red[w][t][r][l];
-        int m = t * 32 + 8 * (r >> 2) + 4 * (l >> 5) + (r & 3);
-        int nn = nt * 32 + (l & 31);
-        if (m < M && nn < N) Y[(size_t)m * N + nn] = (uint16_t)fq_float_to_bf16(v * (a_scale[m] * outer));
-    }
-}
 
 // ---------------------------------------------------------------------------------------------
 // M <= 16: one 16-row MFMA tile (v_mfma_f32_16x16x128_f8f6f4 = exactly one group per instruction).
@@ -337,40 +226,260 @@ void fq_launch_small16(bool words, int per, unsigned grid, hipStream_t stream, c
 
 }  // namespace
 
-void fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                          float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
-    if (M <= 16) {
-        // channels per workgroup: an even share of N over the compute units, a multiple of 8, at most 64
-        static int cus = 0;
-        if (cus == 0) {
-            int dev = 0, v = 0;
-            if (hipGetDevice(&dev) == hipSuccess &&
-                hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-            else cus = 256;
+// ---------------------------------------------------------------------------------------------
+// 16 < M <= 64, general form of the kernel above: MT <= 4 row tiles of 16 rows share every unpacked
+// weight operand (the weights are still read from HBM once), and the group scales of the
+// workgroup's channels (cols x K/128 bytes, contiguous in memory) are copied to LDS at the start
+// instead of being fetched per group.
+// ---------------------------------------------------------------------------------------------
+#define FQSM_MAXCOLS 64
+
+template <int MT, int NSUB>
+struct fqsm_ring {
+    static constexpr int BATCH = MT >= 3 ? 2 : (MT == 2 ? 4 : (NSUB <= 2 ? 8 : 4));
+    fq_v4i bq[BATCH][NSUB];
+    fq_v4i aq[BATCH][MT][2];
+
+    // request group g into slot i; groups at or past g_end request nothing and read as zeros
+    __device__ __forceinline__ void issue(int i, __amdgpu_buffer_rsrc_t rsA, __amdgpu_buffer_rsrc_t rsW,
+                                          const unsigned (&aoff)[MT], const unsigned (&woff)[NSUB], int g, int g_end) {
+        const unsigned dead = g < g_end ? 0u : FQS16_OOB;
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            aq[i][t][0] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, aoff[t] | dead, g * FQ_GROUP, 0));
+            aq[i][t][1] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, (aoff[t] + 16u) | dead, g * FQ_GROUP, 0));
         }
-        int cols = ((N + cus - 1) / cus + 7) & ~7;
-        cols = cols < 8 ? 8 : (cols > 64 ? 64 : cols);
-        const unsigned grid = (unsigned)((N + cols - 1) / cols);
-        const int G = K / FQ_GROUP, per = (G + FQS16_WAVES - 1) / FQS16_WAVES;
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j)                    // streamed once: non-temporal
+            bq[i][j] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsW, woff[j] | dead, g * 2048, 2));
+    }
+
+    // slot i (group g) -> accumulators; a dead group is all zeros and adds nothing.  `sc` points at
+    // this lane's first channel in the LDS scale table [group][64 channels].
+    __device__ __forceinline__ void compute(int i, fq_v4f (&acc)[MT][NSUB], const uint8_t* sc, int g) const {
+        const fq_v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+        fq_v8i zp;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) zp[r] = (int)FQ_ZP_BYTES;
+        fq_v8i a[MT];
+        fq_v4f c0[MT];
+#pragma unroll
+        for (int t = 0; t < MT; ++t) {
+            a[t] = fqs_join(aq[i][t][0], aq[i][t][1]);
+            c0[t] = FQ_MFMA16(a[t], zp, zero4);           // zero point: -2^-6 * sum_k a_k in every column
+        }
+        const uint8_t* scg = sc + g * FQSM_MAXCOLS;
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j) {
+            const fq_v8i b = fq_unpack_chunk(bq[i][j]);
+            const float s = __builtin_amdgcn_cvt_f32_fp8((int)scg[16 * j], 0);
+#pragma unroll
+            for (int t = 0; t < MT; ++t) {
+                const fq_v4f p = FQ_MFMA16(a[t], b, c0[t]);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[t][j][r] = fmaf(s, p[r], acc[t][j][r]);
+            }
+        }
+    }
+};
+
+template <int MT, int NSUB, bool ROUNDS>
+__global__ __launch_bounds__(FQS16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void fq_gemm_smallm_kernel(
+    const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K, int cols) {
+    typedef fqsm_ring<MT, NSUB> ring_t;
+    constexpr int BATCH = ring_t::BATCH;
+    // LDS: first the scale table [G][64] bytes, later (after a barrier) the partial sums
+    // [wave][row tile][sub-tile][reg][lane] floats
+    extern __shared__ __attribute__((aligned(16))) uint8_t smem[];
+    float* red = reinterpret_cast<float*>(smem);
+    const int G = K / FQ_GROUP;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int r16 = lane & 15, kq = lane >> 4;
+    const int n_first = blockIdx.x * cols;                // this workgroup owns channels [n_first, n_first + cols)
+    const int per = (G + FQS16_WAVES - 1) / FQS16_WAVES;
+    const int g_begin = wave * per;
+    const int g_end = (g_begin + per < G) ? g_begin + per : G;
+
+    const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(A), 0, (int)((unsigned)M * (unsigned)K), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(wp), 0, (int)((unsigned)((N + 31) >> 5) * (unsigned)G * 2048u), 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsG = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(gs), 0, (int)((unsigned)N * (unsigned)G), 0x00020000);
+    // the scale bytes of this workgroup: (channel c, group g) at gs[(n_first + c) * G + g]; up to 8 per thread now,
+    // the rest (K > 8192) after the ring has been requested
+    const int nsc = FQSM_MAXCOLS * G;
+    unsigned scb[8];
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+        const int idx = threadIdx.x + x * FQS16_THREADS;  // idx = c * G + g
+        const int c = idx / G;
+        const bool on = idx < nsc && c < cols && n_first + c < N;
+        scb[x] = __builtin_amdgcn_raw_buffer_load_b8(rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+    }
+    // per sub-tile: byte offset of this lane's chunk in group 0 of its packed block
+    unsigned woff[NSUB];
+#pragma unroll
+    for (int j = 0; j < NSUB; ++j) {
+        const int c = 16 * j + r16;
+        const int n = n_first + c;
+        const bool on = (c < cols) && (n < N);            // masked lanes request nothing and store nothing
+        woff[j] = on ? (unsigned)(n >> 5) * (unsigned)G * 2048u + (unsigned)(kq >> 1) * 1024u +
+                       (unsigned)((kq & 1) * 32 + (n & 31)) * 16u
+                     : FQS16_OOB;
+    }
+    unsigned aoff[MT];
+#pragma unroll
+    for (int t = 0; t < MT; ++t) {
+        const int m = 16 * t + r16;
+        aoff[t] = (unsigned)(m < M ? m : M - 1) * (unsigned)K + (unsigned)kq * 32u;
+    }
+    // output factors of the elements this thread writes at the end, fetched up front
+    constexpr int NOUT = (MT * NSUB * 256 + FQS16_THREADS - 1) / FQS16_THREADS;
+    float osc[NOUT];
+#pragma unroll
+    for (int i = 0; i < NOUT; ++i) {
+        const int idx = threadIdx.x + i * FQS16_THREADS;
+        const int m = 16 * (idx / (256 * NSUB)) + 4 * ((idx & 63) >> 4) + ((idx >> 6) & 3);
+        osc[i] = a_scale[m < M ? m : M - 1];
+    }
+
+    fq_v4f acc[MT][NSUB];
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j) acc[t][j] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
+
+    ring_t ring;
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) ring.issue(i, rsA, rsW, aoff, woff, g_begin + i, g_end);
+    __builtin_amdgcn_sched_barrier(0);                    // all requests go out before anything else
+    // scale table: transposed to [group][channel] so that a lane's sub-tiles are 16 bytes apart
+#pragma unroll
+    for (int x = 0; x < 8; ++x) {
+        const int idx = threadIdx.x + x * FQS16_THREADS;
+        const int c = idx / G, g = idx - c * G;
+        if (idx < nsc) smem[g * FQSM_MAXCOLS + c] = (uint8_t)scb[x];
+    }
+    for (int idx = threadIdx.x + 8 * FQS16_THREADS; idx < nsc; idx += FQS16_THREADS) {
+        const int c = idx / G, g = idx - c * G;
+        const bool on = c < cols && n_first + c < N;
+        smem[g * FQSM_MAXCOLS + c] = (uint8_t)__builtin_amdgcn_raw_buffer_load_b8(
+            rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+    }
+    __syncthreads();
+    const uint8_t* sc = smem + r16;
+    // ROUNDS == false: no slice is longer than BATCH groups, the ring is used once and never refilled
+    for (int gb = g_begin; gb < g_end; gb += BATCH) {
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const int g = gb + i < G ? gb + i : G - 1;    // (a dead slot may read any scale: its sums are zero)
+            ring.compute(i, acc, sc, g);
+            __builtin_amdgcn_sched_barrier(0);            // slot by slot, as the data lands
+            if (ROUNDS) {
+                ring.issue(i, rsA, rsW, aoff, woff, gb + BATCH + i, g_end);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        if (!ROUNDS) break;
+    }
+
+    // ---- sum the K-slices of the 8 waves through LDS (over the scale table), scale, write bf16 ----
+    __syncthreads();                                      // every wave is done with the scale table
+#pragma unroll
+    for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int j = 0; j < NSUB; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) red[(((wave * MT + t) * NSUB + j) * 4 + r) * 64 + lane] = acc[t][j][r];
+    __syncthreads();
+    const float outer = tscale * 512.0f;                  // weights were fed in units of 2^-9
+#pragma unroll
+    for (int i = 0; i < NOUT; ++i) {
+        const int idx = threadIdx.x + i * FQS16_THREADS;  // MT * NSUB * 256 outputs: [row tile][sub-tile][reg][lane]
+        const int l = idx & 63, r = (idx >> 6) & 3, j = (idx >> 8) % NSUB, t = idx / (256 * NSUB);
+        if (t < MT) {
+            float v = 0.f;
+#pragma unroll
+            for (int w = 0; w < FQS16_WAVES; ++w) v += red[w * (MT * NSUB * 256) + idx];
+            const int m = 16 * t + 4 * (l >> 4) + r;
+            const int c = 16 * j + (l & 15);
+            const int n = n_first + c;
+            if (m < M && c < cols && n < N) {
+                fq_v2f pr = {v * (osc[i] * outer), 0.f};
+                fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+                Y[(size_t)m * N + n] = __builtin_bit_cast(unsigned short, pk[0]);
+            }
+        }
+    }
+}
+
+namespace {
+
+template <int MT, int NSUB>
+bool fq_launch_smallm(int per, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
+                      const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols) {
+    const int G = K / FQ_GROUP;
+    const size_t red_bytes = (size_t)FQS16_WAVES * MT * NSUB * 256 * sizeof(float);
+    const size_t sc_bytes = (size_t)FQSM_MAXCOLS * G;
+    const size_t lds = red_bytes > sc_bytes ? red_bytes : sc_bytes;
+    if (lds > 160 * 1024) return false;
+    const bool rounds = per > fqsm_ring<MT, NSUB>::BATCH;
+    const void* fn = rounds ? reinterpret_cast<const void*>(fq_gemm_smallm_kernel<MT, NSUB, true>)
+                            : reinterpret_cast<const void*>(fq_gemm_smallm_kernel<MT, NSUB, false>);
+    if (lds > 64 * 1024) (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (rounds)
+        hipLaunchKernelGGL((fq_gemm_smallm_kernel<MT, NSUB, true>), dim3(grid), dim3(FQS16_THREADS), lds, stream,
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+    else
+        hipLaunchKernelGGL((fq_gemm_smallm_kernel<MT, NSUB, false>), dim3(grid), dim3(FQS16_THREADS), lds, stream,
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+    return true;
+}
+
+template <int MT>
+bool fq_launch_smallm_mt(int nsub, int per, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
+                         const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols) {
+    switch (nsub) {
+        case 1: return fq_launch_smallm<MT, 1>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+        case 2: return fq_launch_smallm<MT, 2>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+        case 3: return fq_launch_smallm<MT, 3>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+        default: return fq_launch_smallm<MT, 4>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+    }
+}
+
+}  // namespace
+
+bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                          float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
+    // channels per workgroup: an even share of N over the compute units, a multiple of 8, at most 64
+    static int cus = 0;
+    if (cus == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
+        else cus = 256;
+    }
+    int cols = ((N + cus - 1) / cus + 7) & ~7;
+    cols = cols < 8 ? 8 : (cols > 64 ? 64 : cols);
+    const unsigned grid = (unsigned)((N + cols - 1) / cols);
+    const int G = K / FQ_GROUP, per = (G + FQS16_WAVES - 1) / FQS16_WAVES, nsub = (cols + 15) / 16;
+    if (M <= 16) {
         const bool words = (per % 4 == 0) && (G % 4 == 0) && ((reinterpret_cast<uintptr_t>(gs) & 3) == 0);
-        switch ((cols + 15) / 16) {
+        switch (nsub) {
             case 1: fq_launch_small16<1>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols); break;
             case 2: fq_launch_small16<2>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols); break;
             case 3: fq_launch_small16<3>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols); break;
             default: fq_launch_small16<4>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols); break;
         }
-        return;
+        return true;
     }
-    dim3 grid((unsigned)((N + 31) / 32));
-    for (int m0 = 0; m0 < M; m0 += 64) {                  // M > 64 is served in slabs of 64 rows
-        int mm = (M - m0 < 64) ? M - m0 : 64;
-        const uint8_t* Ab = A + (size_t)m0 * K;
-        uint16_t* Yb = Y + (size_t)m0 * N;
-        if (mm <= 32)
-            hipLaunchKernelGGL(fq_gemm_small_kernel<1>, grid, dim3(FQS_THREADS), 0, stream,
-                               Ab, a_scale + m0, wp, gs, tscale, Yb, mm, N, K);
-        else
-            hipLaunchKernelGGL(fq_gemm_small_kernel<2>, grid, dim3(FQS_THREADS), 0, stream,
-                               Ab, a_scale + m0, wp, gs, tscale, Yb, mm, N, K);
+    if (M > 64) return false;
+    switch ((M + 15) / 16) {                              // false: the scale table does not fit LDS (K > 300000)
+        case 2: return fq_launch_smallm_mt<2>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+        case 3: return fq_launch_smallm_mt<3>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
+        default: return fq_launch_smallm_mt<4>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols);
     }
 }

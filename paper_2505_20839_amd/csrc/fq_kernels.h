@@ -25,5 +25,6 @@ void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipSt
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
                           hipStream_t stream);
-void fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+// M <= 64 only; returns false (nothing enqueued) for a shape it does not serve.
+bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream);
