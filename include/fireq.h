@@ -30,7 +30,8 @@ extern "C" {
 enum {
     FQ_OK         = 0,
     FQ_ERR_NULL   = -1,  /* a required pointer is NULL                                        */
-    FQ_ERR_SHAPE  = -2,  /* negative size, K == 0, K % 128 != 0, N == 0 with M > 0            */
+    FQ_ERR_SHAPE  = -2,  /* negative size, K == 0, K % 128 != 0, N == 0 with M > 0, or an     */
+                         /* operand of the GEMM of 4 GiB or more (M*K, N*K/2, N*K/128, 512*N) */
     FQ_ERR_ALIGN  = -3,  /* a base pointer is not 16-byte aligned                             */
     FQ_ERR_LAUNCH = -4,  /* the HIP runtime reported an error when the kernel was launched    */
     FQ_ERR_MEMORY = -5   /* workspace missing or too small / own workspace could not be allocated */

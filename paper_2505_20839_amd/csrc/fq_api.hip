@@ -25,6 +25,27 @@ GemmKernel forced_kernel() {
     return GemmKernel::Auto;
 }
 
+// The GEMM kernels address every operand through 32-bit buffer offsets: each of A, the packed
+// weights, the group scales and the workspace must stay below 4 GiB, and a band of 256 output rows too.
+bool gemm_operands_addressable(int M, int N, int K) {
+    const unsigned long long lim = 0xFFFFFF00ull, m = (unsigned long long)M, n = (unsigned long long)N,
+                             k = (unsigned long long)K, g = k / FQ_GROUP;
+    return m * k < lim && ((n + 31) / 32) * 32 * k / 2 < lim && n * g < lim && 256ull * n * 2 < lim &&
+           (unsigned long long)fq_gemm_large_workspace_bytes(M, K) < lim;
+}
+
+// Argument checks shared by the GEMM entry points (M == 0 is valid and needs no pointers).
+int check_gemm_args(const void* A, const void* a_scale, const void* W, const void* gs, const void* Y,
+                    int M, int N, int K) {
+    if (M < 0 || N < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
+    if (M == 0) return FQ_OK;
+    if (N == 0) return FQ_ERR_SHAPE;
+    if (!A || !a_scale || !W || !gs || !Y) return FQ_ERR_NULL;
+    if (!aligned16(A) || !aligned16(W) || !aligned16(gs) || !aligned16(Y)) return FQ_ERR_ALIGN;
+    if (!gemm_operands_addressable(M, N, K)) return FQ_ERR_SHAPE;
+    return FQ_OK;
+}
+
 GemmKernel choose_kernel(int M) {
     const GemmKernel k = forced_kernel();
     return k != GemmKernel::Auto ? k : (M <= 64 ? GemmKernel::Small : GemmKernel::Large);
@@ -108,12 +129,8 @@ int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* W
                     const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
                     int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
                     void* stream) {
-    if (M < 0 || N < 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
-    if (M == 0) return FQ_OK;
-    if (N == 0) return FQ_ERR_SHAPE;
-    if (!A_fp8 || !a_scale || !Wq_packed || !w_gscale || !Y_bf16) return FQ_ERR_NULL;
-    if (!aligned16(A_fp8) || !aligned16(Wq_packed) || !aligned16(w_gscale) || !aligned16(Y_bf16))
-        return FQ_ERR_ALIGN;
+    const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, Y_bf16, M, N, K);
+    if (rc != FQ_OK || M == 0) return rc;
     const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return FQ_ERR_MEMORY;
@@ -137,11 +154,13 @@ int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* W
 int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
                  const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
                  int M, int N, int K, void* stream) {
+    const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, Y_bf16, M, N, K);
+    if (rc != FQ_OK || M == 0) return rc;
     // the library's own workspace: one grow-only device buffer, shared by every call of the process
     static void* ws = nullptr;
     static size_t ws_bytes = 0;
     const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
-    if (need > ws_bytes && A_fp8 && a_scale && Wq_packed && w_gscale && Y_bf16) {
+    if (need > ws_bytes) {
         if (ws) (void)hipFree(ws);
         ws = nullptr;
         ws_bytes = 0;

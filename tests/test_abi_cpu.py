@@ -55,6 +55,9 @@ def test_bad_arguments_are_rejected_without_a_launch():
     assert L.fq_w4a8_gemm(p, p, p, p, f1, p, -1, 32, 128, null) == -2
     assert L.fq_w4a8_gemm(p, p, p, p, f1, p, 4, 0, 128, null) == -2
     assert L.fq_w4a8_gemm(p, p, p, p, f1, p, 4, 32, 0, null) == -2
+    # operands of 4 GiB or more are not addressable by the kernels
+    assert L.fq_w4a8_gemm(p, p, p, p, f1, p, 1 << 20, 32, 1 << 12, null) == -2      # A: 4 GiB
+    assert L.fq_w4a8_gemm(p, p, p, p, f1, p, 4, 1 << 20, 1 << 13, null) == -2       # packed W: 4 GiB
     # M == 0 is a successful no-op even with NULL pointers
     assert L.fq_w4a8_gemm(null, null, null, null, f1, null, 0, 32, 128, null) == 0
     # NULL and misaligned pointers
