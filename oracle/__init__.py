@@ -61,6 +61,9 @@ def _load():
     lib.fqo_w4a8_gemm.restype = ctypes.c_int
     lib.fqo_w4a8_gemm.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
                                   ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.fqo_w4a8_gemm_swiglu.restype = ctypes.c_int
+    lib.fqo_w4a8_gemm_swiglu.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
+                                         ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.fqo_quantize_act.restype = ctypes.c_int
     lib.fqo_quantize_act.argtypes = [u16p, u8p, f32p, ctypes.c_int, ctypes.c_int]
     lib.fqo_num_threads.restype = ctypes.c_int
@@ -137,6 +140,30 @@ def w4a8_gemm(A, a_scale, q, gscale, w_tscale, want_bound: bool = False):
     if rc != 0:
         raise ValueError("fqo_w4a8_gemm failed with %d" % rc)
     return (Y, B) if want_bound else Y
+
+
+def w4a8_gemm_swiglu(A, a_scale, q, gscale, w_tscale, want_bound: bool = False):
+    """FP64 ``H[M,N/2] = SiLU(Y[:, 0::2]) * Y[:, 1::2]`` of the W4A8-FP GEMM ``Y`` (gate rows at even,
+    up rows at odd indices of ``q``), and optionally the first-order error bound."""
+    A = _c(A, np.uint8)
+    a_scale = _c(a_scale, np.float32)
+    q = _c(q, np.int8)
+    gscale = _c(gscale, np.uint8)
+    M, K = A.shape
+    N = q.shape[0]
+    if N % 2 or q.shape != (N, K) or a_scale.shape != (M,) or gscale.shape != (N, K // 128):
+        raise ValueError("operand shapes do not match")
+    H = np.zeros((M, N // 2), dtype=np.float64)
+    B = np.zeros((M, N // 2), dtype=np.float64) if want_bound else None
+    rc = _load().fqo_w4a8_gemm_swiglu(
+        _ptr(A, ctypes.c_uint8), _ptr(a_scale, ctypes.c_float), _ptr(q, ctypes.c_int8),
+        _ptr(gscale, ctypes.c_uint8), ctypes.c_float(float(np.float32(w_tscale))),
+        _ptr(H, ctypes.c_double),
+        _ptr(B, ctypes.c_double) if want_bound else ctypes.POINTER(ctypes.c_double)(),
+        M, N, K)
+    if rc != 0:
+        raise ValueError("fqo_w4a8_gemm_swiglu failed with %d" % rc)
+    return (H, B) if want_bound else H
 
 
 def quantize_act(X_bf16_bits):

@@ -233,6 +233,58 @@ int fqo_w4a8_gemm(const uint8_t *A, const float *a_scale, const int8_t *q,
 }
 
 /* ---------------------------------------------------------------------------------------
+ * The gate/up pair of a feed-forward block with the epilogue fused (Sec. 3.1.1 step 3: the
+ * kernel's epilogue applies the nonlinear activation, SiLU, and the element-wise
+ * multiplication):
+ *
+ *   H[m,j] = SiLU(Yg[m,j]) * Yu[m,j],   SiLU(x) = x / (1 + exp(-x)),
+ *
+ * where Yg = row 2j and Yu = row 2j+1 of the W4A8-FP GEMM above (the weight matrix holds
+ * the gate and up projections with their rows interleaved; N rows give N/2 outputs).
+ *
+ * Reading: the paper converts the GEMM result to BF16 before the epilogue; as for the plain
+ * GEMM, the task's reading is FP32/FP64 throughout and one rounding at the very end, so
+ * this function applies SiLU and the product to the unrounded sums.
+ *
+ * bound (may be NULL) [M,N/2]: first-order bound of what errors eg, eu of the two sums do
+ * to H:  |dH| <= 1.1 |Yu| eg + |SiLU(Yg)| eu  (|SiLU'| <= 1.1), evaluated with eg, eu set
+ * to the absolute-value bounds of the two sums.
+ * Returns 0, -1 on a bad shape (N odd included), -2 when a temporary cannot be allocated.
+ * ------------------------------------------------------------------------------------- */
+int fqo_w4a8_gemm_swiglu(const uint8_t *A, const float *a_scale, const int8_t *q,
+                         const uint8_t *gscale, float w_tscale,
+                         double *H, double *bound, int M, int N, int K)
+{
+    if (M < 0 || N < 0 || (N & 1) || K < 0 || (K % FQO_GROUP) != 0)
+        return -1;
+    if (M == 0 || N == 0)
+        return 0;
+    double *Y = (double *)malloc((size_t)M * N * sizeof(double));
+    double *B = (double *)malloc((size_t)M * N * sizeof(double));
+    if (!Y || !B) {
+        free(Y);
+        free(B);
+        return -2;
+    }
+    int rc = fqo_w4a8_gemm(A, a_scale, q, gscale, w_tscale, Y, B, M, N, K);
+    if (rc == 0) {
+        const int J = N / 2;
+        for (size_t m = 0; m < (size_t)M; ++m) {
+            for (int j = 0; j < J; ++j) {
+                const double g = Y[m * N + 2 * j], u = Y[m * N + 2 * j + 1];
+                const double silu = g / (1.0 + exp(-g));
+                H[m * J + j] = silu * u;
+                if (bound)
+                    bound[m * J + j] = 1.1 * fabs(u) * B[m * N + 2 * j] + fabs(silu) * B[m * N + 2 * j + 1];
+            }
+        }
+    }
+    free(Y);
+    free(B);
+    return rc;
+}
+
+/* ---------------------------------------------------------------------------------------
  * Activation quantisation (Sec. 2.1 eq. 2):  A = FP8(x / beta), one beta per token.
  *
  *   X [M,K] bf16 bit patterns -> A [M,K] E4M3 codes, a_scale [M] FP32.
