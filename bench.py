@@ -98,13 +98,15 @@ def main() -> int:
         w, d, X, packed, gs = upload(name)
         packs = [packed] + [packed.clone() for _ in range(copies - 1)]
         gss = [gs] + [gs.clone() for _ in range(copies - 1)]
-        Y = torch.empty((w.M, w.N), dtype=torch.bfloat16, device="cuda")
+        swiglu = w.epilogue == "swiglu"
+        Y = torch.empty((w.M, w.N // 2 if swiglu else w.N), dtype=torch.bfloat16, device="cuda")
+        gemm_fn = fq.fq_w4a8_gemm_swiglu if swiglu else fq.fq_w4a8_gemm
         need = fq.fq_w4a8_gemm_workspace_bytes(w.M, w.N, w.K)
         ws = torch.empty((max(need, 16),), dtype=torch.uint8, device="cuda")
 
         def gemm(A, s, i):
-            fq.fq_w4a8_gemm(A, s, packs[i % copies], gss[i % copies], d["w_tscale"], w.N, out=Y, workspace=ws,
-                            workspace_prepared=need > 0)
+            gemm_fn(A, s, packs[i % copies], gss[i % copies], d["w_tscale"], w.N, out=Y, workspace=ws,
+                    workspace_prepared=need > 0)
 
         def step(i):
             # large M: the quantiser also prepares the GEMM's workspace (fq_quantize_act_ws)
@@ -164,14 +166,16 @@ def main() -> int:
     flop = 2.0 * w.M * w.N * w.K
     G = w.K // 128
     wbytes = w.N * w.K / 2 + w.N * G                      # packed INT4 + group scales
-    gemm_bytes = wbytes + w.M * w.K + 4 * w.M + 2 * w.M * w.N
+    swiglu = w.epilogue == "swiglu"
+    gemm_bytes = wbytes + w.M * w.K + 4 * w.M + 2 * w.M * (w.N // 2 if swiglu else w.N)
     if decode_like:
         metric, unit = "W4A8 GEMM packed-weight GB/s at small M", "GB/s"
         value = wbytes * steps / total_s / 1e9
         roof = {"bound": "hbm", "achieved": wbytes / gemm_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s"}
     else:
         metric = ("W4A8 GEMM TFLOPS (% FP8 MFMA peak) at M=2048; GB/s (% HBM) at M=16" if name == DEFAULT_WORKLOAD
-                  else "W4A8 GEMM TFLOPS at M=%d" % w.M)
+                  else ("W4A8 gate/up GEMM with fused SiLU(gate)*up, TFLOPS at M=%d" if swiglu
+                        else "W4A8 GEMM TFLOPS at M=%d") % w.M)
         unit = "TFLOP/s"
         value = flop * steps / total_s / 1e12
         roof = {"bound": "mfma", "achieved": flop / gemm_s / 1e12, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s"}
@@ -190,7 +194,8 @@ def main() -> int:
         "vs_baseline": None, "dtype": "fp8_e4m3 x int4 -> f32", "data": "synthetic",
         "config": {"workload": name, "M": w.M, "N": w.N, "K": w.K, "group": 128,
                    "step": ("fq_quantize_act + fq_w4a8_gemm" if decode_like else
-                            "fq_quantize_act_ws + fq_w4a8_gemm_ws (workspace prepared by the quantiser)") +
+                            "fq_quantize_act_ws + fq_w4a8_gemm%s_ws (workspace prepared by the quantiser)"
+                            % ("_swiglu" if swiglu else "")) +
                            " (weights packed once, offline)"},
         "roofline": roof,
     }

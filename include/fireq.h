@@ -79,6 +79,23 @@ int fq_w4a8_gemm(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_p
                  int M, int N, int K, void *stream);
 
 /*
+ * The gate and up projections of a feed-forward block in one call, with the epilogue fused
+ * (Sec. 3.1.1 step 3: nonlinear activation and element-wise multiplication in the kernel's
+ * epilogue).  The weight matrix holds the two projections with their rows interleaved: row 2j
+ * of q (and of w_gscale) is gate channel j, row 2j+1 is up channel j; N counts these rows and
+ * must be even.  With Y the result fq_w4a8_gemm_ws would give before rounding,
+ *
+ *   H[m,j] = bf16( SiLU(Y[m,2j]) * Y[m,2j+1] ),   SiLU(x) = x / (1 + exp(-x)),
+ *
+ * computed in FP32 and rounded once.  H_bf16 is [M,N/2] row-major.  Everything else
+ * (operands, workspace, status codes) is as for fq_w4a8_gemm_ws.
+ */
+int fq_w4a8_gemm_swiglu_ws(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
+                           const uint8_t *w_gscale, float w_tscale, uint16_t *H_bf16,
+                           int M, int N, int K, void *workspace, size_t workspace_bytes,
+                           int workspace_prepared, void *stream);
+
+/*
  * Per-token FP8 quantisation of activations (Sec. 2.1 eq. 2: A = FP8(x / beta)).
  *
  *   beta[m] = max_k |X[m,k]| / 448 in FP32 (1 for an all-zero row);

@@ -125,12 +125,15 @@ int fq_quantize_act_ws(const uint16_t* X_bf16, uint8_t* A_fp8, float* a_scale, i
     return after_launch();
 }
 
-int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
-                    const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
-                    int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
-                    void* stream) {
-    const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, Y_bf16, M, N, K);
-    if (rc != FQ_OK || M == 0) return rc;
+namespace {
+
+int gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed, const uint8_t* w_gscale,
+            float w_tscale, uint16_t* out, int M, int N, int K, void* workspace, size_t workspace_bytes,
+            int workspace_prepared, bool swiglu, void* stream) {
+    const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, out, M, N, K);
+    if (rc != FQ_OK) return rc;
+    if (swiglu && (N & 1)) return FQ_ERR_SHAPE;
+    if (M == 0) return FQ_OK;
     const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return FQ_ERR_MEMORY;
@@ -138,17 +141,37 @@ int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* W
     }
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (choose_kernel(M)) {
-        case GemmKernel::Simple: fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s); break;
+        case GemmKernel::Simple:
+            fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, s);
+            break;
         case GemmKernel::Small:
-            if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s))
-                fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s);
+            if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, s))
+                fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, s);
             break;
         default:
-            fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace,
-                                 workspace_prepared != 0, s);
+            fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, workspace,
+                                 workspace_prepared != 0, swiglu, s);
             break;
     }
     return after_launch();
+}
+
+}  // namespace
+
+int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                    const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
+                    int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
+                    void* stream) {
+    return gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace, workspace_bytes,
+                   workspace_prepared, false, stream);
+}
+
+int fq_w4a8_gemm_swiglu_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                           const uint8_t* w_gscale, float w_tscale, uint16_t* H_bf16,
+                           int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
+                           void* stream) {
+    return gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, H_bf16, M, N, K, workspace, workspace_bytes,
+                   workspace_prepared, true, stream);
 }
 
 int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,

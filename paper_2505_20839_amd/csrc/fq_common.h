@@ -81,6 +81,13 @@ __device__ __forceinline__ float fq_e4m3_to_float(unsigned b) {
     return __uint_as_float(__float_as_uint(mag) | sign);
 }
 
+// SiLU(g) * u in FP32 (fused gate/up epilogue, Sec. 3.1.1 step 3): g / (1 + e^-g) * u with the
+// hardware exponential and reciprocal (about 2 ulp of FP32 each, far below the bf16 step of the
+// result); a very negative g gives e^-g = inf, 1 / inf = 0 and the result 0.
+__device__ __forceinline__ float fq_silu_mul(float g, float u) {
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
+}
+
 // float -> bf16 bits, round to nearest even (finite or infinite input; NaN not expected).
 __device__ __forceinline__ unsigned fq_float_to_bf16(float f) {
     unsigned u = __float_as_uint(f);

@@ -197,7 +197,7 @@ __device__ __forceinline__ void fql_item(
     fq_v4i* lds, const unsigned bid,
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
-    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes) {
+    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, const int swiglu) {
     constexpr int NT = NMT;                               // A transfers per wave and stage
     const int G = K / FQ_GROUP;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -451,6 +451,72 @@ __device__ __forceinline__ void fql_item(
         osc[i] = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);
     }
     __syncthreads();
+    if (swiglu) {
+        // Fused gate/up epilogue (Sec. 3.1.1 step 3): even channels are gate, odd channels up rows;
+        // H[m, n/2] = bf16(SiLU(gate) * up), H being [M, N/2].  Lanes l and l^1 hold the two channels
+        // of a pair for the same rows: the even lane finishes rows rl, rl+1 of a step, the odd lane
+        // rows rl+2, rl+3, each after getting the other's two values by a lane swap.
+        const int NH = N >> 1;
+        const bool full_h = (m0 + 32 * NMT <= M) && (n0 + FQL_BN <= N) && ((NH & 7) == 0);
+        if (full_h) {
+            constexpr int HS = FQL_BN + 16;               // LDS row stride in bytes: 64 bf16 + pad
+            char* tile = reinterpret_cast<char*>(lds);
+            const int odd = lane & 1;
+            char* wcol = tile + (4 * (lane >> 5) + 2 * odd) * HS + (wave * 16 + ((lane & 31) >> 1)) * 2;
+            constexpr int AHEAD = 3;
+            const float* oscl = osc + 4 * (lane >> 5);
+            fq_v4f scq[AHEAD + 1];
+#pragma unroll
+            for (int it = 0; it < AHEAD; ++it) scq[it] = *reinterpret_cast<const fq_v4f*>(&oscl[8 * it]);
+#pragma unroll
+            for (int it = 0; it < 4 * NMT; ++it) {        // step it: rows 8 * it + 4 * (lane / 32) + 0..3 of the item
+                const int mt = it >> 2, j = it & 3;
+                if (it + AHEAD < 4 * NMT)
+                    scq[(it + AHEAD) % (AHEAD + 1)] = *reinterpret_cast<const fq_v4f*>(&oscl[8 * (it + AHEAD)]);
+                const fq_v4f sc4 = scq[it % (AHEAD + 1)];
+                const float f0 = acc[mt][4 * j] * sc4[0], f1 = acc[mt][4 * j + 1] * sc4[1];
+                const float f2 = acc[mt][4 * j + 2] * sc4[2], f3 = acc[mt][4 * j + 3] * sc4[3];
+                const float s0 = odd ? f0 : f2, s1 = odd ? f1 : f3;       // what the partner lane needs
+                const float r0 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s0), 0xB1, 0xF, 0xF, false));
+                const float r1 = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(s1), 0xB1, 0xF, 0xF, false));
+                const fq_v2f pr = odd ? (fq_v2f){fq_silu_mul(r0, f2), fq_silu_mul(r1, f3)}
+                                      : (fq_v2f){fq_silu_mul(f0, r0), fq_silu_mul(f1, r1)};
+                const unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, fq_v2bf));
+                char* dst = wcol + (8 * it) * HS;
+                *reinterpret_cast<unsigned short*>(dst) = (unsigned short)pk;
+                *reinterpret_cast<unsigned short*>(dst + HS) = (unsigned short)(pk >> 16);
+            }
+            __syncthreads();
+            // wave w stores rows 8*NMT*w ..., eight rows of 128 bytes per instruction
+            const __amdgpu_buffer_rsrc_t rsH = __builtin_amdgcn_make_buffer_rsrc(
+                Y + (size_t)(m0 + wave * (8 * NMT)) * NH + (n0 >> 1), 0, (int)((unsigned)(8 * NMT) * (unsigned)NH * 2u), 0x00020000);
+            const unsigned hlane = (unsigned)(lane >> 3) * (unsigned)NH * 2u + (unsigned)(lane & 7) * 16u;
+            const char* rd = tile + (wave * (8 * NMT) + (lane >> 3)) * HS + (lane & 7) * 16;
+#pragma unroll
+            for (int j = 0; j < NMT; ++j) {
+                const fq_v4i v = *reinterpret_cast<const fq_v4i*>(rd + 8 * j * HS);
+                __builtin_amdgcn_raw_buffer_store_b128(v, rsH, hlane, 8 * j * NH * 2, 0);
+            }
+            return;
+        }
+        // ragged tile: element-wise (both lanes of a pair are inside or both outside, N being even)
+        if (!wave_on || !n_ok) return;
+#pragma unroll
+        for (int mt = 0; mt < NMT; ++mt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int ml = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const float f = acc[mt][r] * osc[ml];
+                const float up = __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(f), 0xB1, 0xF, 0xF, false));
+                if (m0 + ml < M && (lane & 1) == 0) {
+                    fq_v2f pr = {fq_silu_mul(f, up), 0.f};
+                    fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+                    Y[(size_t)(m0 + ml) * NH + (n >> 1)] = __builtin_bit_cast(unsigned short, pk[0]);
+                }
+            }
+        }
+        return;
+    }
     const bool full_tile = (m0 + 32 * NMT <= M) && (n0 + FQL_BN <= N) && ((N & 7) == 0);
     if (full_tile) {
         // Transpose through LDS so that every store instruction writes whole 256-byte rows.
@@ -516,12 +582,14 @@ __global__ __launch_bounds__(FQL_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
 void fq_gemm_large_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
-    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, unsigned full_wgs) {
+    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, unsigned full_wgs,
+    int swiglu) {
     extern __shared__ fq_v4i lds[];                       // 2 A stages (64 KiB) + 4 x 4 KiB of packed weights
     if (blockIdx.x < full_wgs)
-        fql_item<8>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes);
+        fql_item<8>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, swiglu);
     else
-        fql_item<4>(lds, blockIdx.x - full_wgs, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes);
+        fql_item<4>(lds, blockIdx.x - full_wgs, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes,
+                    swiglu);
 }
 
 size_t fq_gemm_large_workspace_bytes(int M, int K) {
@@ -535,7 +603,7 @@ void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipSt
 
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
-                          hipStream_t stream) {
+                          bool swiglu, hipStream_t stream) {
     static bool attr_set = false;
     static int cus = 256;
     if (!attr_set) {
@@ -561,5 +629,6 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
     }
     const unsigned full_wgs = (unsigned)(max_full * FQL_XCDS), half_wgs = (unsigned)(max_half * FQL_XCDS);
     hipLaunchKernelGGL(fq_gemm_large_kernel, dim3(full_wgs + half_wgs), dim3(FQL_THREADS), FQL_LDS_BYTES, stream,
-                       A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, full_wgs);
+                       A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, full_wgs,
+                       swiglu ? 1 : 0);
 }

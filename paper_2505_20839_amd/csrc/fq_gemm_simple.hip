@@ -3,17 +3,13 @@
 // cross-check (selected with FQ_FORCE_KERNEL=simple).  Computes, in FP32,
 //   Y[m,n] = bf16( a_scale[m] * w_tscale * sum_g e4m3(gs[n,g]) * sum_{k in g} e4m3(A[m,k]) * q[n,k] )
 // (Sec. 2.2 eq. 3 with the operands of Sec. 3.1 and the output factor of Def. 3.2).
+// With `swiglu` a thread computes the two sums of channels 2j (gate) and 2j + 1 (up) and stores
+// H[m,j] = bf16(SiLU(gate) * up) (the fused epilogue of Sec. 3.1.1 step 3), H being [M, N/2].
 #include "fq_common.h"
 #include "fq_kernels.h"
 
-__global__ __launch_bounds__(256) void fq_gemm_simple_kernel(const uint8_t* __restrict__ A,
-                                                             const float* __restrict__ a_scale,
-                                                             const uint8_t* __restrict__ wp,
-                                                             const uint8_t* __restrict__ gs, float tscale,
-                                                             uint16_t* __restrict__ Y, int M, int N, int K) {
-    int n = blockIdx.x * 64 + (threadIdx.x & 63);
-    int m = blockIdx.y * 4 + (threadIdx.x >> 6);
-    if (n >= N || m >= M) return;
+__device__ float fq_simple_dot(const uint8_t* __restrict__ A, const uint8_t* __restrict__ wp,
+                               const uint8_t* __restrict__ gs, int m, int n, int K) {
     const int G = K / FQ_GROUP;
     float acc = 0.f;
     for (int g = 0; g < G; ++g) {
@@ -27,11 +23,30 @@ __global__ __launch_bounds__(256) void fq_gemm_simple_kernel(const uint8_t* __re
         }
         acc = fmaf(fq_e4m3_to_float(gs[(size_t)n * G + g]), p, acc);
     }
-    Y[(size_t)m * N + n] = (uint16_t)fq_float_to_bf16(a_scale[m] * tscale * acc);
+    return acc;
+}
+
+__global__ __launch_bounds__(256) void fq_gemm_simple_kernel(const uint8_t* __restrict__ A,
+                                                             const float* __restrict__ a_scale,
+                                                             const uint8_t* __restrict__ wp,
+                                                             const uint8_t* __restrict__ gs, float tscale,
+                                                             uint16_t* __restrict__ Y, int M, int N, int K,
+                                                             int swiglu) {
+    const int c = blockIdx.x * 64 + (threadIdx.x & 63);   // output column
+    const int m = blockIdx.y * 4 + (threadIdx.x >> 6);
+    const int NO = swiglu ? N / 2 : N;
+    if (c >= NO || m >= M) return;
+    const float outer = a_scale[m] * tscale;
+    float v;
+    if (swiglu) v = fq_silu_mul(outer * fq_simple_dot(A, wp, gs, m, 2 * c, K), outer * fq_simple_dot(A, wp, gs, m, 2 * c + 1, K));
+    else        v = outer * fq_simple_dot(A, wp, gs, m, c, K);
+    Y[(size_t)m * NO + c] = (uint16_t)fq_float_to_bf16(v);
 }
 
 void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                           float tscale, uint16_t* Y, int M, int N, int K, hipStream_t stream) {
-    dim3 grid((unsigned)((N + 63) / 64), (unsigned)((M + 3) / 4));
-    hipLaunchKernelGGL(fq_gemm_simple_kernel, grid, dim3(256), 0, stream, A, a_scale, wp, gs, tscale, Y, M, N, K);
+                           float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, hipStream_t stream) {
+    const int NO = swiglu ? N / 2 : N;
+    dim3 grid((unsigned)((NO + 63) / 64), (unsigned)((M + 3) / 4));
+    hipLaunchKernelGGL(fq_gemm_simple_kernel, grid, dim3(256), 0, stream, A, a_scale, wp, gs, tscale, Y, M, N, K,
+                       swiglu ? 1 : 0);
 }

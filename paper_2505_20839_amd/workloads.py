@@ -33,10 +33,11 @@ class Workload:
     gs_hi: float
     w_tscale: float
     seed: int
+    epilogue: str = "none"   # "swiglu": the N weight rows interleave gate (even) and up (odd) channels
 
 
-def _w(name, M, N, K, act, frac, lo, hi, t, seed):
-    return Workload(name, M, N, K, act, frac, lo, hi, t, seed)
+def _w(name, M, N, K, act, frac, lo, hi, t, seed, epilogue="none"):
+    return Workload(name, M, N, K, act, frac, lo, hi, t, seed, epilogue)
 
 
 # The five benchmark configurations (config 4 has two shapes, config 5 four batch sizes).
@@ -50,6 +51,9 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     _w("c5_decode_m4",       4, 14336,  4096, "gauss",   0.0,  0.005, 0.05, 1.0, 6),
     _w("c5_decode_m16",     16, 14336,  4096, "gauss",   0.0,  0.005, 0.05, 1.0, 7),
     _w("c5_decode_m64",     64, 14336,  4096, "gauss",   0.0,  0.005, 0.05, 1.0, 8),
+    # beyond the five configurations: gate and up projection of the Llama2-7B feed-forward block in one
+    # GEMM (rows interleaved) with the SiLU(gate) * up epilogue fused (Sec. 3.1.1 step 3)
+    _w("ffn_l2_7b_gateup_swiglu", 2048, 22016, 4096, "gauss", 0.01, 0.005, 0.05, 1.0, 9, "swiglu"),
 ]}
 
 

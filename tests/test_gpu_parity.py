@@ -277,6 +277,71 @@ def test_quantiser_prepares_the_gemm_workspace(fq, M, N, K):
     assert np.all(diff <= oracle.bf16_ulp_array(Y) + 1e-5 * B)
 
 
+# ---- fused gate/up epilogue ------------------------------------------------------------------------
+
+SWIGLU_SHAPES = {"simple": [(5, 64, 256), (33, 200, 384)],
+                 "small": [(1, 32, 128), (16, 256, 512), (12, 14336, 384), (40, 200, 640), (64, 96, 1408)],
+                 "large": [(65, 32, 128), (300, 256, 1024), (257, 528, 384), (512, 1024, 512), (130, 200, 640)]}
+
+
+@pytest.mark.parametrize("kernel,shape", [(k, s) for k, v in SWIGLU_SHAPES.items() for s in v])
+def test_gemm_swiglu_matches_oracle(fq, kernel_choice, kernel, shape):
+    """H = SiLU(gate) * up against the oracle, gates of order one so that the nonlinear range is used."""
+    M, N, K = shape
+    d = workloads.draw(M, N, K, seed=3 * M + N + K, gs_lo=0.01, gs_hi=0.1, w_tscale=0.25, outlier_frac=0.01)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    kernel_choice(kernel)
+    Hg = fq.fq_w4a8_gemm_swiglu(A, s, packed, _gpu(d["gscale"]), d["w_tscale"], N)
+    torch.cuda.synchronize()
+    assert tuple(Hg.shape) == (M, N // 2)
+    An, sn = A.cpu().numpy(), s.cpu().numpy()
+    H, B = oracle.w4a8_gemm_swiglu(An, sn, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    Y = oracle.w4a8_gemm(An, sn, d["q"], d["gscale"], d["w_tscale"])
+    assert 0.2 < np.median(np.abs(Y[:, 0::2])) < 20            # the gates sit where SiLU bends
+    check_gemm(bf16_bits_from_gpu(Hg), H, B, "swiglu %s %s" % (kernel, shape))
+
+
+def test_gemm_swiglu_pairs_even_gate_with_odd_up(fq, kernel_choice):
+    """One-hot activations read back single weights: H[m, j] = SiLU(w[2j, m]) * w[2j+1, m] exactly as the
+    oracle pairs them, for every kernel; the plain GEMM on the same buffers gives the two sums."""
+    N, K = 64, 256
+    rng = np.random.default_rng(4)
+    q = rng.integers(-8, 8, (N, K), dtype=np.int8)
+    gs = np.full((N, K // 128), 0x30, np.uint8)            # 0.5
+    for kernel, M in (("simple", 8), ("small", 48), ("large", 256)):
+        A = np.zeros((M, K), np.uint8)
+        A[np.arange(M), np.arange(M) % K] = 0x38
+        a = np.ones(M, np.float32)
+        kernel_choice(kernel)
+        packed = fq.fq_pack_weights(_gpu(q))
+        Hg = bf16_bits_from_gpu(fq.fq_w4a8_gemm_swiglu(_gpu(A), _gpu(a), packed, _gpu(gs), 1.0, N))
+        torch.cuda.synchronize()
+        g = 0.5 * q[0::2, :M].T.astype(np.float64)             # [M, N/2]
+        u = 0.5 * q[1::2, :M].T.astype(np.float64)
+        want = g / (1.0 + np.exp(-g)) * u
+        got = oracle.bf16_bits_to_f64(Hg)
+        assert np.all(np.abs(got - want) <= oracle.bf16_ulp_array(want) + 1e-6), kernel
+
+
+def test_ffn_gateup_swiglu_full_size(fq):
+    """The fused gate/up layer at its real size (M=2048, 2 x 11008 interleaved rows, K=4096), through the
+    fused quantiser, on sampled rows against the oracle."""
+    name = "ffn_l2_7b_gateup_swiglu"
+    w = workloads.WORKLOADS[name]
+    d = workloads.draw_workload(name)
+    need = fq.fq_w4a8_gemm_workspace_bytes(w.M, w.N, w.K)
+    ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]), workspace=ws)
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    Hg = fq.fq_w4a8_gemm_swiglu(A, s, packed, _gpu(d["gscale"]), d["w_tscale"], w.N, workspace=ws, workspace_prepared=True)
+    torch.cuda.synchronize()
+    rows = [0, 1, 127, 128, 255, 256, 1111, 2047]
+    An, sn = A.cpu().numpy()[rows], s.cpu().numpy()[rows]
+    H, B = oracle.w4a8_gemm_swiglu(An, sn, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Hg)[rows], H, B, name)
+
+
 def test_m_zero_is_a_noop(fq):
     packed = torch.zeros(fq.fq_packed_weight_bytes(32, 128), dtype=torch.uint8, device="cuda")
     Y = fq.fq_w4a8_gemm(torch.zeros((0, 128), dtype=torch.uint8, device="cuda"),
