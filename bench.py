@@ -51,6 +51,8 @@ def main() -> int:
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the extra small-M (HBM-bound) figure")
+    ap.add_argument("--no-other-configs", action="store_true",
+                    help="skip the brief timing of the other large-M configurations (c3, c4a, c4b, fused gate/up)")
     ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
                     help="only run a plain device-to-device copy of BYTES bytes three times (reference "
                          "for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings) and exit")
@@ -207,6 +209,19 @@ def main() -> int:
         out["decode_m16"] = {"workload": "c5_decode_m16", "kernel_us": gemm_d * 1e6, "step_us": tot_d / n_d * 1e6,
                              "weight_GBps": wb / gemm_d / 1e9, "frac_hbm": wb / gemm_d / 1e9 / PEAK_HBM_GBPS,
                              "weight_copies_rotated": DECODE_COPIES}
+
+    if not args.no_other_configs and not decode_like and name == DEFAULT_WORKLOAD:
+        others = {}
+        for other in ("c3_l2_7b_down", "c4a_l3_8b_qkv", "c4b_l3_8b_up", "ffn_l2_7b_gateup_swiglu"):
+            if other == name:
+                continue
+            wo, _, n_o, tot_o, gemm_o, quant_o = run(other, 50, 5, 1, LARGE_GRAPH_STEPS)
+            fo = 2.0 * wo.M * wo.N * wo.K
+            others[other] = {"M": wo.M, "N": wo.N, "K": wo.K, "kernel_us": gemm_o * 1e6, "quantize_us": quant_o * 1e6,
+                             "step_us": tot_o / n_o * 1e6, "gemm_TFLOPs": fo / gemm_o / 1e12,
+                             "frac_mfma_peak": fo / gemm_o / 1e12 / PEAK_FP8_TFLOPS}
+            torch.cuda.empty_cache()
+        out["other_configs"] = others
 
     if not args.no_cpu_baseline:
         import oracle
