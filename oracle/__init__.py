@@ -64,6 +64,9 @@ def _load():
     lib.fqo_w4a8_gemm_swiglu.restype = ctypes.c_int
     lib.fqo_w4a8_gemm_swiglu.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
                                          ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.fqo_w4a8_gemm_add.restype = ctypes.c_int
+    lib.fqo_w4a8_gemm_add.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, u16p, f64p, f64p,
+                                      ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.fqo_quantize_act.restype = ctypes.c_int
     lib.fqo_quantize_act.argtypes = [u16p, u8p, f32p, ctypes.c_int, ctypes.c_int]
     lib.fqo_num_threads.restype = ctypes.c_int
@@ -164,6 +167,31 @@ def w4a8_gemm_swiglu(A, a_scale, q, gscale, w_tscale, want_bound: bool = False):
     if rc != 0:
         raise ValueError("fqo_w4a8_gemm_swiglu failed with %d" % rc)
     return (H, B) if want_bound else H
+
+
+def w4a8_gemm_add(A, a_scale, q, gscale, w_tscale, R_bf16_bits, want_bound: bool = False):
+    """FP64 ``GEMM + R`` with ``R`` given as uint16 [M,N] bf16 bit patterns (the residual
+    stream added in the epilogue), and optionally the GEMM's absolute-value bound."""
+    A = _c(A, np.uint8)
+    a_scale = _c(a_scale, np.float32)
+    q = _c(q, np.int8)
+    gscale = _c(gscale, np.uint8)
+    R = _c(R_bf16_bits, np.uint16)
+    M, K = A.shape
+    N = q.shape[0]
+    if q.shape != (N, K) or a_scale.shape != (M,) or gscale.shape != (N, K // 128) or R.shape != (M, N):
+        raise ValueError("operand shapes do not match")
+    Y = np.zeros((M, N), dtype=np.float64)
+    B = np.zeros((M, N), dtype=np.float64) if want_bound else None
+    rc = _load().fqo_w4a8_gemm_add(
+        _ptr(A, ctypes.c_uint8), _ptr(a_scale, ctypes.c_float), _ptr(q, ctypes.c_int8),
+        _ptr(gscale, ctypes.c_uint8), ctypes.c_float(float(np.float32(w_tscale))),
+        _ptr(R, ctypes.c_uint16), _ptr(Y, ctypes.c_double),
+        _ptr(B, ctypes.c_double) if want_bound else ctypes.POINTER(ctypes.c_double)(),
+        M, N, K)
+    if rc != 0:
+        raise ValueError("fqo_w4a8_gemm_add failed with %d" % rc)
+    return (Y, B) if want_bound else Y
 
 
 def quantize_act(X_bf16_bits):

@@ -285,6 +285,31 @@ int fqo_w4a8_gemm_swiglu(const uint8_t *A, const float *a_scale, const int8_t *q
 }
 
 /* ---------------------------------------------------------------------------------------
+ * The GEMM with the activation addition of the epilogue (Sec. 3.1.1 step 3: "activation
+ * addition" is the residual stream added to the output of the attention-output and the
+ * down projections, Fig. 1):
+ *
+ *   Y[m,n] = GEMM[m,n] + R[m,n],   R [M,N] bf16 bit patterns, row-major.
+ *
+ * Reading: as for the other epilogues the sum is formed on the unrounded GEMM result and
+ * rounded once by the caller of this function (the paper adds in BF16 after a first
+ * rounding of the GEMM result).  R is exact, so the error bound is that of the GEMM.
+ * Returns what fqo_w4a8_gemm returns.
+ * ------------------------------------------------------------------------------------- */
+int fqo_w4a8_gemm_add(const uint8_t *A, const float *a_scale, const int8_t *q,
+                      const uint8_t *gscale, float w_tscale, const uint16_t *R,
+                      double *Y, double *bound, int M, int N, int K)
+{
+    int rc = fqo_w4a8_gemm(A, a_scale, q, gscale, w_tscale, Y, bound, M, N, K);
+    if (rc != 0 || M == 0 || N == 0)
+        return rc;
+    for (size_t m = 0; m < (size_t)M; ++m)
+        for (size_t n = 0; n < (size_t)N; ++n)
+            Y[m * N + n] += fqo_bf16_decode(R[m * N + n]);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------
  * Activation quantisation (Sec. 2.1 eq. 2):  A = FP8(x / beta), one beta per token.
  *
  *   X [M,K] bf16 bit patterns -> A [M,K] E4M3 codes, a_scale [M] FP32.
