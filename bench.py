@@ -103,6 +103,12 @@ def main() -> int:
         swiglu = w.epilogue == "swiglu"
         Y = torch.empty((w.M, w.N // 2 if swiglu else w.N), dtype=torch.bfloat16, device="cuda")
         gemm_fn = fq.fq_w4a8_gemm_swiglu if swiglu else fq.fq_w4a8_gemm
+        if w.epilogue == "add":
+            # the residual stream is updated in place, step after step (its values grow; timing only)
+            R = torch.from_numpy(workloads.draw_residual(w.M, w.N, scale=workloads.RESIDUAL_SCALE, seed=w.seed)
+                                 .view(np.int16)).cuda().view(torch.bfloat16)
+            Y = R
+            gemm_fn = lambda *a, **k: fq.fq_w4a8_gemm_add(*a, R, **k)   # noqa: E731
         need = fq.fq_w4a8_gemm_workspace_bytes(w.M, w.N, w.K)
         ws = torch.empty((max(need, 16),), dtype=torch.uint8, device="cuda")
 
@@ -169,7 +175,8 @@ def main() -> int:
     G = w.K // 128
     wbytes = w.N * w.K / 2 + w.N * G                      # packed INT4 + group scales
     swiglu = w.epilogue == "swiglu"
-    gemm_bytes = wbytes + w.M * w.K + 4 * w.M + 2 * w.M * (w.N // 2 if swiglu else w.N)
+    gemm_bytes = wbytes + w.M * w.K + 4 * w.M + 2 * w.M * (w.N // 2 if swiglu else w.N) \
+        + (2 * w.M * w.N if w.epilogue == "add" else 0)
     if decode_like:
         metric, unit = "W4A8 GEMM packed-weight GB/s at small M", "GB/s"
         value = wbytes * steps / total_s / 1e9
@@ -177,6 +184,7 @@ def main() -> int:
     else:
         metric = ("W4A8 GEMM TFLOPS (% FP8 MFMA peak) at M=2048; GB/s (% HBM) at M=16" if name == DEFAULT_WORKLOAD
                   else ("W4A8 gate/up GEMM with fused SiLU(gate)*up, TFLOPS at M=%d" if swiglu
+                        else "W4A8 GEMM with the residual added in the epilogue, TFLOPS at M=%d" if w.epilogue == "add"
                         else "W4A8 GEMM TFLOPS at M=%d") % w.M)
         unit = "TFLOP/s"
         value = flop * steps / total_s / 1e12
@@ -197,7 +205,7 @@ def main() -> int:
         "config": {"workload": name, "M": w.M, "N": w.N, "K": w.K, "group": 128,
                    "step": ("fq_quantize_act + fq_w4a8_gemm" if decode_like else
                             "fq_quantize_act_ws + fq_w4a8_gemm%s_ws (workspace prepared by the quantiser)"
-                            % ("_swiglu" if swiglu else "")) +
+                            % ("_swiglu" if swiglu else "_add" if w.epilogue == "add" else "")) +
                            " (weights packed once, offline)"},
         "roofline": roof,
     }
@@ -212,7 +220,8 @@ def main() -> int:
 
     if not args.no_other_configs and not decode_like and name == DEFAULT_WORKLOAD:
         others = {}
-        for other in ("c3_l2_7b_down", "c4a_l3_8b_qkv", "c4b_l3_8b_up", "ffn_l2_7b_gateup_swiglu"):
+        for other in ("c3_l2_7b_down", "c4a_l3_8b_qkv", "c4b_l3_8b_up", "ffn_l2_7b_gateup_swiglu",
+                      "ffn_l2_7b_down_residual"):
             if other == name:
                 continue
             wo, _, n_o, tot_o, gemm_o, quant_o = run(other, 50, 5, 1, LARGE_GRAPH_STEPS)

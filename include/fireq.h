@@ -96,6 +96,22 @@ int fq_w4a8_gemm_swiglu_ws(const uint8_t *A_fp8, const float *a_scale, const uin
                            int workspace_prepared, void *stream);
 
 /*
+ * The GEMM with the residual stream added in its epilogue (Sec. 3.1.1 step 3, "activation
+ * addition"; Fig. 1: after the attention-output and the down projections):
+ *
+ *   Y[m,n] = bf16( GEMM[m,n] + R[m,n] ),
+ *
+ * the sum formed in FP32 on the unrounded GEMM result of fq_w4a8_gemm_ws and rounded once.
+ * R_bf16 is [M,N] row-major bfloat16 bit patterns, finite, 16-byte aligned.  R_bf16 may be
+ * Y_bf16 itself (the residual stream updated in place); any other overlap of the two arrays is
+ * FQ_ERR_SHAPE.  Everything else is as for fq_w4a8_gemm_ws.
+ */
+int fq_w4a8_gemm_add_ws(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
+                        const uint8_t *w_gscale, float w_tscale, const uint16_t *R_bf16,
+                        uint16_t *Y_bf16, int M, int N, int K, void *workspace,
+                        size_t workspace_bytes, int workspace_prepared, void *stream);
+
+/*
  * Per-token FP8 quantisation of activations (Sec. 2.1 eq. 2: A = FP8(x / beta)).
  *
  *   beta[m] = max_k |X[m,k]| / 448 in FP32 (1 for an all-zero row);

@@ -38,6 +38,8 @@ def lib() -> ctypes.CDLL:
     L.fq_w4a8_gemm.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
     L.fq_w4a8_gemm_ws.restype = ci
     L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
+    L.fq_w4a8_gemm_add_ws.restype = ci
+    L.fq_w4a8_gemm_add_ws.argtypes = [vp, vp, vp, vp, cf, vp, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
     L.fq_w4a8_gemm_swiglu_ws.restype = ci
     L.fq_w4a8_gemm_swiglu_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
     L.fq_quantize_act_ws.restype = ci
@@ -197,6 +199,40 @@ def fq_w4a8_gemm_swiglu(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch
                                       1 if (workspace_prepared and workspace is not None) else 0, _stream())
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_swiglu_ws")
+    return out
+
+
+def fq_w4a8_gemm_add(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor,
+                     w_gscale: torch.Tensor, w_tscale: float, N: int, residual: torch.Tensor,
+                     out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                     workspace_prepared: bool = False) -> torch.Tensor:
+    """Y[M,N] (bf16) = GEMM + residual, rounded once.  Calls fq_w4a8_gemm_add_ws; `out` may be
+    `residual` itself (in-place update); workspace handling as in fq_w4a8_gemm."""
+    A = _dev(A, torch.uint8, "A")
+    a_scale = _dev(a_scale, torch.float32, "a_scale")
+    Wq_packed = _dev(Wq_packed, torch.uint8, "Wq_packed")
+    w_gscale = _dev(w_gscale, torch.uint8, "w_gscale")
+    residual = _dev(residual, torch.bfloat16, "residual")
+    M, K = A.shape
+    if a_scale.numel() != M or K % GROUP or w_gscale.numel() != N * (K // GROUP) \
+            or Wq_packed.numel() < fq_packed_weight_bytes(N, K) or tuple(residual.shape) != (M, N):
+        raise FireqError(-2, "fq_w4a8_gemm_add")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    else:
+        out = _dev(out, torch.bfloat16, "out")
+        if tuple(out.shape) != (M, N):
+            raise FireqError(-2, "fq_w4a8_gemm_add")
+    need = lib().fq_w4a8_gemm_workspace_bytes(M, N, K)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=A.device)
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (0, 0)
+    rc = lib().fq_w4a8_gemm_add_ws(A.data_ptr(), a_scale.data_ptr(), Wq_packed.data_ptr(),
+                                   w_gscale.data_ptr(), ctypes.c_float(float(w_tscale)), residual.data_ptr(),
+                                   out.data_ptr(), M, N, K, ws_ptr, ws_bytes,
+                                   1 if (workspace_prepared and workspace is not None) else 0, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_w4a8_gemm_add_ws")
     return out
 
 

@@ -129,11 +129,20 @@ namespace {
 
 int gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed, const uint8_t* w_gscale,
             float w_tscale, uint16_t* out, int M, int N, int K, void* workspace, size_t workspace_bytes,
-            int workspace_prepared, bool swiglu, void* stream) {
+            int workspace_prepared, bool swiglu, const uint16_t* R, bool with_residual, void* stream) {
     const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, out, M, N, K);
     if (rc != FQ_OK) return rc;
     if (swiglu && (N & 1)) return FQ_ERR_SHAPE;
     if (M == 0) return FQ_OK;
+    if (with_residual) {
+        if (!R) return FQ_ERR_NULL;
+        if (!aligned16(R)) return FQ_ERR_ALIGN;
+        if (R != out) {                                   // the very same array is fine, a shifted overlap is not
+            const uintptr_t r0 = reinterpret_cast<uintptr_t>(R), y0 = reinterpret_cast<uintptr_t>(out);
+            const uintptr_t bytes = (uintptr_t)M * (uintptr_t)N * 2u;
+            if (r0 < y0 + bytes && y0 < r0 + bytes) return FQ_ERR_SHAPE;
+        }
+    }
     const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
     if (need > 0) {
         if (!workspace || workspace_bytes < need) return FQ_ERR_MEMORY;
@@ -142,15 +151,15 @@ int gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed
     hipStream_t s = static_cast<hipStream_t>(stream);
     switch (choose_kernel(M)) {
         case GemmKernel::Simple:
-            fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, s);
+            fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s);
             break;
         case GemmKernel::Small:
-            if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, s))
-                fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, s);
+            if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s))
+                fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s);
             break;
         default:
             fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, workspace,
-                                 workspace_prepared != 0, swiglu, s);
+                                 workspace_prepared != 0, swiglu, R, s);
             break;
     }
     return after_launch();
@@ -163,7 +172,15 @@ int fq_w4a8_gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* W
                     int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
                     void* stream) {
     return gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace, workspace_bytes,
-                   workspace_prepared, false, stream);
+                   workspace_prepared, false, nullptr, false, stream);
+}
+
+int fq_w4a8_gemm_add_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                        const uint8_t* w_gscale, float w_tscale, const uint16_t* R_bf16, uint16_t* Y_bf16,
+                        int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
+                        void* stream) {
+    return gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, workspace, workspace_bytes,
+                   workspace_prepared, false, R_bf16, true, stream);
 }
 
 int fq_w4a8_gemm_swiglu_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
@@ -171,7 +188,7 @@ int fq_w4a8_gemm_swiglu_ws(const uint8_t* A_fp8, const float* a_scale, const uin
                            int M, int N, int K, void* workspace, size_t workspace_bytes, int workspace_prepared,
                            void* stream) {
     return gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, H_bf16, M, N, K, workspace, workspace_bytes,
-                   workspace_prepared, true, stream);
+                   workspace_prepared, true, nullptr, false, stream);
 }
 
 int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,

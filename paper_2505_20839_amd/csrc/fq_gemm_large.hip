@@ -196,8 +196,9 @@ template <int NMT>
 __device__ __forceinline__ void fql_item(
     fq_v4i* lds, const unsigned bid,
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
-    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
-    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, const int swiglu) {
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K,
+    int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, const int swiglu,
+    const uint16_t* R) {
     constexpr int NT = NMT;                               // A transfers per wave and stage
     const int G = K / FQ_GROUP;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -377,6 +378,28 @@ __device__ __forceinline__ void fql_item(
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[NMT - 1][r] = fmaf(sprev, pprev[r], acc[NMT - 1][r]);
 
+    // ---- residual tile (activation addition, Sec. 3.1.1 step 3): requested now, used in the epilogue ----
+    // Step `it` of the epilogue handles rows 8 * it + 4 * (lane / 32) + 0..3 of this lane's channel.
+    // Lanes l, l ^ 1 hold neighbouring channels: the even lane fetches the pair's two bf16 of rows
+    // 0, 1 as one dword each, the odd lane those of rows 2, 3, and they swap in the epilogue.
+    // Channels past N wrap into the next row (never stored), rows past M read zero.  All of these
+    // loads have landed before this workgroup's first store (the zero-point rounds wait for every
+    // transfer), and no other workgroup touches this tile: R may be the output array itself.
+    const bool full_tile = (m0 + 32 * NMT <= M) && (n0 + FQL_BN <= N) && ((N & 7) == 0);
+    const bool add_full = R != nullptr && full_tile;
+    unsigned rres[4 * NMT][2];
+    if (add_full) {
+        const __amdgpu_buffer_rsrc_t rsR = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint16_t*>(R) + (size_t)m0 * N + n0, 0, (int)((unsigned)(32 * NMT) * (unsigned)N * 2u), 0x00020000);
+        const unsigned rlane = ((unsigned)(4 * (lane >> 5) + 2 * (lane & 1)) * (unsigned)N +
+                                (unsigned)(wave * 32 + ((lane & 31) & ~1))) * 2u;
+#pragma unroll
+        for (int it = 0; it < 4 * NMT; ++it)
+#pragma unroll
+            for (int x = 0; x < 2; ++x)
+                rres[it][x] = __builtin_amdgcn_raw_buffer_load_b32(rsR, rlane, (8 * it + x) * N * 2, 0);
+    }
+
     // ---- zero point: acc += Z * gscale^T over the groups, on the fp16 matrix cores ----
     // Rounds of up to 8 units of Z (32 * NMT rows x 8 groups, 16 bytes per row); round r sits in A
     // stage r & 1 (round 0 arrived during the last group) while the next round is on its way to
@@ -517,7 +540,6 @@ __device__ __forceinline__ void fql_item(
         }
         return;
     }
-    const bool full_tile = (m0 + 32 * NMT <= M) && (n0 + FQL_BN <= N) && ((N & 7) == 0);
     if (full_tile) {
         // Transpose through LDS so that every store instruction writes whole 256-byte rows.
         // Registers r, r+1 of a lane are rows rl, rl+1 of its column: one v_cvt_pk_bf16_f32 rounds
@@ -537,9 +559,22 @@ __device__ __forceinline__ void fql_item(
             if (it + AHEAD < 4 * NMT)
                 scq[(it + AHEAD) % (AHEAD + 1)] = *reinterpret_cast<const fq_v4f*>(&oscl[8 * (it + AHEAD)]);
             const fq_v4f sc4 = scq[it % (AHEAD + 1)];
+            fq_v4f res = {0.f, 0.f, 0.f, 0.f};
+            if (add_full) {                               // this lane's four residual values (see the loads above)
+                const bool odd = lane & 1;
+                const unsigned d0 = rres[it][0], d1 = rres[it][1];
+                const unsigned p0 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d0, 0xB1, 0xF, 0xF, false);
+                const unsigned p1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d1, 0xB1, 0xF, 0xF, false);
+                const unsigned a[4] = {odd ? p0 : d0, odd ? p1 : d1, odd ? d0 : p0, odd ? d1 : p1};
+                const unsigned sh = odd ? 0u : 16u;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) res[e] = __uint_as_float((a[e] << sh) & 0xFFFF0000u);
+            }
 #pragma unroll
             for (int e = 0; e < 4; e += 2) {
-                const fq_v2f pr = {acc[mt][4 * j + e] * sc4[e], acc[mt][4 * j + e + 1] * sc4[e + 1]};
+                const fq_v2f pr = add_full ? (fq_v2f){fmaf(acc[mt][4 * j + e], sc4[e], res[e]),
+                                                      fmaf(acc[mt][4 * j + e + 1], sc4[e + 1], res[e + 1])}
+                                           : (fq_v2f){acc[mt][4 * j + e] * sc4[e], acc[mt][4 * j + e + 1] * sc4[e + 1]};
                 const unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, fq_v2bf));
                 char* dst = wcol + (8 * it + e) * FQL_OUT_STRIDE;
                 *reinterpret_cast<unsigned short*>(dst) = (unsigned short)pk;
@@ -568,7 +603,9 @@ __device__ __forceinline__ void fql_item(
         for (int r = 0; r < 16; ++r) {
             int ml = mt * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
             if (m0 + ml < M) {
-                fq_v2f pr = {acc[mt][r] * osc[ml], 0.f};
+                float v = acc[mt][r] * osc[ml];
+                if (R) v = fmaf(acc[mt][r], osc[ml], __uint_as_float((unsigned)R[(size_t)(m0 + ml) * N + n] << 16));
+                fq_v2f pr = {v, 0.f};
                 fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
                 Y[(size_t)(m0 + ml) * N + n] = __builtin_bit_cast(unsigned short, pk[0]);
             }
@@ -581,15 +618,15 @@ __device__ __forceinline__ void fql_item(
 __global__ __launch_bounds__(FQL_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void fq_gemm_large_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
-    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K,
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K,
     int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, unsigned full_wgs,
-    int swiglu) {
+    int swiglu, const uint16_t* R) {
     extern __shared__ fq_v4i lds[];                       // 2 A stages (64 KiB) + 4 x 4 KiB of packed weights
     if (blockIdx.x < full_wgs)
-        fql_item<8>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, swiglu);
+        fql_item<8>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, swiglu, R);
     else
         fql_item<4>(lds, blockIdx.x - full_wgs, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes,
-                    swiglu);
+                    swiglu, R);
 }
 
 size_t fq_gemm_large_workspace_bytes(int M, int K) {
@@ -603,7 +640,7 @@ void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipSt
 
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
-                          bool swiglu, hipStream_t stream) {
+                          bool swiglu, const uint16_t* R, hipStream_t stream) {
     static bool attr_set = false;
     static int cus = 256;
     if (!attr_set) {
@@ -630,5 +667,5 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
     const unsigned full_wgs = (unsigned)(max_full * FQL_XCDS), half_wgs = (unsigned)(max_half * FQL_XCDS);
     hipLaunchKernelGGL(fq_gemm_large_kernel, dim3(full_wgs + half_wgs), dim3(FQL_THREADS), FQL_LDS_BYTES, stream,
                        A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, full_wgs,
-                       swiglu ? 1 : 0);
+                       swiglu ? 1 : 0, R);
 }

@@ -5,6 +5,7 @@
 // (Sec. 2.2 eq. 3 with the operands of Sec. 3.1 and the output factor of Def. 3.2).
 // With `swiglu` a thread computes the two sums of channels 2j (gate) and 2j + 1 (up) and stores
 // H[m,j] = bf16(SiLU(gate) * up) (the fused epilogue of Sec. 3.1.1 step 3), H being [M, N/2].
+// With a residual R [M,N] (bf16; may be Y itself) the plain result is Y = bf16(sum + R), rounded once.
 #include "fq_common.h"
 #include "fq_kernels.h"
 
@@ -30,8 +31,8 @@ __global__ __launch_bounds__(256) void fq_gemm_simple_kernel(const uint8_t* __re
                                                              const float* __restrict__ a_scale,
                                                              const uint8_t* __restrict__ wp,
                                                              const uint8_t* __restrict__ gs, float tscale,
-                                                             uint16_t* __restrict__ Y, int M, int N, int K,
-                                                             int swiglu) {
+                                                             uint16_t* Y, int M, int N, int K,
+                                                             int swiglu, const uint16_t* R) {
     const int c = blockIdx.x * 64 + (threadIdx.x & 63);   // output column
     const int m = blockIdx.y * 4 + (threadIdx.x >> 6);
     const int NO = swiglu ? N / 2 : N;
@@ -39,14 +40,16 @@ __global__ __launch_bounds__(256) void fq_gemm_simple_kernel(const uint8_t* __re
     const float outer = a_scale[m] * tscale;
     float v;
     if (swiglu) v = fq_silu_mul(outer * fq_simple_dot(A, wp, gs, m, 2 * c, K), outer * fq_simple_dot(A, wp, gs, m, 2 * c + 1, K));
+    else if (R) v = fmaf(outer, fq_simple_dot(A, wp, gs, m, c, K), __uint_as_float((unsigned)R[(size_t)m * N + c] << 16));
     else        v = outer * fq_simple_dot(A, wp, gs, m, c, K);
     Y[(size_t)m * NO + c] = (uint16_t)fq_float_to_bf16(v);
 }
 
 void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                           float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, hipStream_t stream) {
+                           float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, const uint16_t* R,
+                           hipStream_t stream) {
     const int NO = swiglu ? N / 2 : N;
     dim3 grid((unsigned)((NO + 63) / 64), (unsigned)((M + 3) / 4));
     hipLaunchKernelGGL(fq_gemm_simple_kernel, grid, dim3(256), 0, stream, A, a_scale, wp, gs, tscale, Y, M, N, K,
-                       swiglu ? 1 : 0);
+                       swiglu ? 1 : 0, R);
 }

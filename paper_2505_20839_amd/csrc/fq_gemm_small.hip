@@ -108,8 +108,8 @@ template <int NSUB, bool WORDS, bool ROUNDS>
 __global__ __launch_bounds__(FQS16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void fq_gemm_small16_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
-    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K, int cols,
-    int swiglu) {
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K, int cols,
+    int swiglu, const uint16_t* R) {
     typedef fqs16_ring<NSUB, WORDS> ring_t;
     constexpr int BATCH = ring_t::BATCH;
     __shared__ float red[FQS16_WAVES][NSUB][4][64];
@@ -202,6 +202,7 @@ void fq_gemm_small16_kernel(
                 const float f = osc[i] * outer;
                 if (!swiglu) {
                     fq_v2f pr = {v * f, 0.f};
+                    if (R) pr[0] = fmaf(v, f, __uint_as_float((unsigned)R[(size_t)m * N + n] << 16));   // residual, one rounding
                     fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
                     Y[(size_t)m * N + n] = __builtin_bit_cast(unsigned short, pk[0]);
                 } else if ((l & 1) == 0) {                // fused epilogue: H[m, n/2] = SiLU(gate) * up
@@ -218,21 +219,21 @@ namespace {
 
 template <int NSUB, bool WORDS>
 void fq_launch_small16w(bool rounds, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
-                        const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu) {
+                        const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
     if (rounds)
         hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, true>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
-                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
     else
         hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, false>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
-                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
 }
 
 template <int NSUB>
 void fq_launch_small16(bool words, int per, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
-                       const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu) {
+                       const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
     const bool rounds = per > fqs16_ring<NSUB, true>::BATCH;      // some slice needs the ring more than once
-    if (words) fq_launch_small16w<NSUB, true>(rounds, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
-    else       fq_launch_small16w<NSUB, false>(rounds, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
+    if (words) fq_launch_small16w<NSUB, true>(rounds, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+    else       fq_launch_small16w<NSUB, false>(rounds, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
 }
 
 }  // namespace
@@ -298,8 +299,8 @@ template <int MT, int NSUB, bool ROUNDS>
 __global__ __launch_bounds__(FQS16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void fq_gemm_smallm_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
-    const uint8_t* __restrict__ gs, float tscale, uint16_t* __restrict__ Y, int M, int N, int K, int cols,
-    int swiglu) {
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K, int cols,
+    int swiglu, const uint16_t* R) {
     typedef fqsm_ring<MT, NSUB> ring_t;
     constexpr int BATCH = ring_t::BATCH;
     // LDS: first the scale table [G][64] bytes, later (after a barrier) the partial sums
@@ -426,6 +427,7 @@ void fq_gemm_smallm_kernel(
                 const float f = osc[i] * outer;
                 if (!swiglu) {
                     fq_v2f pr = {v * f, 0.f};
+                    if (R) pr[0] = fmaf(v, f, __uint_as_float((unsigned)R[(size_t)m * N + n] << 16));   // residual, one rounding
                     fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
                     Y[(size_t)m * N + n] = __builtin_bit_cast(unsigned short, pk[0]);
                 } else if ((l & 1) == 0) {                // fused epilogue: H[m, n/2] = SiLU(gate) * up
@@ -442,7 +444,7 @@ namespace {
 
 template <int MT, int NSUB>
 bool fq_launch_smallm(int per, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
-                      const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu) {
+                      const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
     const int G = K / FQ_GROUP;
     const size_t red_bytes = (size_t)FQS16_WAVES * MT * NSUB * 256 * sizeof(float);
     const size_t sc_bytes = (size_t)FQSM_MAXCOLS * G;
@@ -454,28 +456,28 @@ bool fq_launch_smallm(int per, unsigned grid, hipStream_t stream, const uint8_t*
     if (lds > 64 * 1024) (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (rounds)
         hipLaunchKernelGGL((fq_gemm_smallm_kernel<MT, NSUB, true>), dim3(grid), dim3(FQS16_THREADS), lds, stream,
-                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
     else
         hipLaunchKernelGGL((fq_gemm_smallm_kernel<MT, NSUB, false>), dim3(grid), dim3(FQS16_THREADS), lds, stream,
-                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
     return true;
 }
 
 template <int MT>
 bool fq_launch_smallm_mt(int nsub, int per, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
-                         const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu) {
+                         const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
     switch (nsub) {
-        case 1: return fq_launch_smallm<MT, 1>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
-        case 2: return fq_launch_smallm<MT, 2>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
-        case 3: return fq_launch_smallm<MT, 3>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
-        default: return fq_launch_smallm<MT, 4>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
+        case 1: return fq_launch_smallm<MT, 1>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+        case 2: return fq_launch_smallm<MT, 2>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+        case 3: return fq_launch_smallm<MT, 3>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+        default: return fq_launch_smallm<MT, 4>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
     }
 }
 
 }  // namespace
 
 bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                          float tscale, uint16_t* Y, int M, int N, int K, bool swiglu_epilogue, hipStream_t stream) {
+                          float tscale, uint16_t* Y, int M, int N, int K, bool swiglu_epilogue, const uint16_t* R, hipStream_t stream) {
     const int swiglu = swiglu_epilogue ? 1 : 0;
     // channels per workgroup: an even share of N over the compute units, a multiple of 8, at most 64
     static int cus = 0;
@@ -492,17 +494,17 @@ bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t*
     if (M <= 16) {
         const bool words = (per % 4 == 0) && (G % 4 == 0) && ((reinterpret_cast<uintptr_t>(gs) & 3) == 0);
         switch (nsub) {
-            case 1: fq_launch_small16<1>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu); break;
-            case 2: fq_launch_small16<2>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu); break;
-            case 3: fq_launch_small16<3>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu); break;
-            default: fq_launch_small16<4>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu); break;
+            case 1: fq_launch_small16<1>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R); break;
+            case 2: fq_launch_small16<2>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R); break;
+            case 3: fq_launch_small16<3>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R); break;
+            default: fq_launch_small16<4>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R); break;
         }
         return true;
     }
     if (M > 64) return false;
     switch ((M + 15) / 16) {                              // false: the scale table does not fit LDS (K > 300000)
-        case 2: return fq_launch_smallm_mt<2>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
-        case 3: return fq_launch_smallm_mt<3>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
-        default: return fq_launch_smallm_mt<4>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu);
+        case 2: return fq_launch_smallm_mt<2>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+        case 3: return fq_launch_smallm_mt<3>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+        default: return fq_launch_smallm_mt<4>(nsub, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
     }
 }

@@ -33,7 +33,8 @@ class Workload:
     gs_hi: float
     w_tscale: float
     seed: int
-    epilogue: str = "none"   # "swiglu": the N weight rows interleave gate (even) and up (odd) channels
+    epilogue: str = "none"   # "swiglu": the N weight rows interleave gate (even) and up (odd) channels;
+                             # "add": a residual [M,N] is added to the result (draw_residual)
 
 
 def _w(name, M, N, K, act, frac, lo, hi, t, seed, epilogue="none"):
@@ -54,6 +55,8 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     # beyond the five configurations: gate and up projection of the Llama2-7B feed-forward block in one
     # GEMM (rows interleaved) with the SiLU(gate) * up epilogue fused (Sec. 3.1.1 step 3)
     _w("ffn_l2_7b_gateup_swiglu", 2048, 22016, 4096, "gauss", 0.01, 0.005, 0.05, 1.0, 9, "swiglu"),
+    # the down projection of the same block with the residual stream added in the epilogue (step 3)
+    _w("ffn_l2_7b_down_residual", 2048, 4096, 11008, "gauss", 0.01, 0.005, 0.05, 1.0, 10, "add"),
 ]}
 
 
@@ -105,6 +108,16 @@ def draw(M: int, N: int, K: int, *, seed: int, act: str = "gauss", outlier_frac:
         "gscale": f32_to_e4m3_codes(gs),
         "w_tscale": float(w_tscale),
     }
+
+
+RESIDUAL_SCALE = 16.0     # about the standard deviation of the GEMM outputs of the "add" workload
+
+
+def draw_residual(M: int, N: int, *, scale: float, seed: int) -> np.ndarray:
+    """uint16 [M,N] bf16 bit patterns of N(0, scale^2) draws: the residual stream an "add" epilogue takes.
+    A stream of its own, so that the other operands of a problem do not depend on it."""
+    rng = np.random.default_rng([seed, 0x5EED])
+    return f32_to_bf16_bits(rng.standard_normal((M, N), dtype=np.float32) * np.float32(scale))
 
 
 def draw_workload(name: str, rows: Optional[int] = None):

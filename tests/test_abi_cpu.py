@@ -20,7 +20,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     L = binding.lib()
     names = _declared_functions()
-    assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_swiglu_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_quantize_act_ws", "fq_packed_weight_bytes", "fq_pack_weights",
+    assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_swiglu_ws", "fq_w4a8_gemm_add_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_quantize_act_ws", "fq_packed_weight_bytes", "fq_pack_weights",
                             "fq_unpack_weights", "fq_layout_version", "fq_status_string"])
     for name in names:
         assert hasattr(L, name), name
@@ -77,6 +77,16 @@ def test_bad_arguments_are_rejected_without_a_launch():
     assert L.fq_w4a8_gemm_swiglu_ws(p, p, p, p, f1, p, 128, 33, 128, *ws, null) == -2          # N odd
     assert L.fq_w4a8_gemm_swiglu_ws(p, p, p, p, f1, null, 128, 32, 128, *ws, null) == -1
     assert L.fq_w4a8_gemm_swiglu_ws(p, p, p, p, f1, p, 128, 32, 128, null, ctypes.c_size_t(0), 0, null) == -5
+    # the residual variant: the residual is required, aligned, and either the output itself or disjoint
+    p2 = ctypes.c_void_p(p.value + 16)
+    far = ctypes.c_void_p(p.value + (1 << 20))
+    assert L.fq_w4a8_gemm_add_ws(p, p, p, p, f1, null, far, 128, 32, 128, *ws, null) == -1
+    assert L.fq_w4a8_gemm_add_ws(p, p, p, p, f1, odd, far, 128, 32, 128, *ws, null) == -3
+    assert L.fq_w4a8_gemm_add_ws(p, p, p, p, f1, p2, p, 128, 32, 128, *ws, null) == -2          # shifted overlap
+    assert L.fq_w4a8_gemm_add_ws(p, p, p, p, f1, p, p2, 128, 32, 128, *ws, null) == -2
+    assert L.fq_w4a8_gemm_add_ws(p, p, p, p, f1, p, p, 128, 32, 100, *ws, null) == -2           # K % 128
+    assert L.fq_w4a8_gemm_add_ws(p, p, p, p, f1, p, p, 128, 32, 128, null, ctypes.c_size_t(0), 0, null) == -5
+    assert L.fq_w4a8_gemm_add_ws(null, null, null, null, f1, null, null, 0, 32, 128, null, ctypes.c_size_t(0), 0, null) == 0
     assert L.fq_quantize_act_ws(p, p, p, 4, 100, p, ctypes.c_size_t(1 << 30), null) == -2      # K % 128
     assert L.fq_quantize_act_ws(p, p, p, 0, 128, null, ctypes.c_size_t(0), null) == 0
     assert L.fq_quantize_act_ws(null, p, p, 4, 128, p, ctypes.c_size_t(1 << 30), null) == -1

@@ -342,6 +342,84 @@ def test_ffn_gateup_swiglu_full_size(fq):
     check_gemm(bf16_bits_from_gpu(Hg)[rows], H, B, name)
 
 
+# ---- residual added in the epilogue ---------------------------------------------------------------
+
+ADD_SHAPES = {"simple": [(5, 64, 256), (33, 201, 384)],
+              "small": [(1, 32, 128), (16, 256, 512), (12, 14336, 384), (40, 201, 640), (64, 96, 1408)],
+              "large": [(65, 32, 128), (300, 256, 1024), (257, 528, 384), (512, 1024, 512), (130, 201, 640),
+                        (384, 130, 256)]}
+
+
+def _residual_bits(M, N, scale, seed):
+    return workloads.draw_residual(M, N, scale=scale, seed=seed)
+
+
+@pytest.mark.parametrize("kernel,shape", [(k, s) for k, v in ADD_SHAPES.items() for s in v])
+def test_gemm_add_matches_oracle(fq, kernel_choice, kernel, shape):
+    """Y = GEMM + R against the oracle, R of the GEMM's own magnitude; then the same call in place."""
+    M, N, K = shape
+    d = workloads.draw(M, N, K, seed=5 * M + N + K, outlier_frac=0.01)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    An, sn = A.cpu().numpy(), s.cpu().numpy()
+    Y0 = oracle.w4a8_gemm(An, sn, d["q"], d["gscale"], d["w_tscale"])
+    Rb = _residual_bits(M, N, float(np.std(Y0)) + 1e-3, seed=M + N)
+    kernel_choice(kernel)
+    R = to_gpu_bf16(Rb)
+    Yg = fq.fq_w4a8_gemm_add(A, s, packed, _gpu(d["gscale"]), d["w_tscale"], N, R)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits_from_gpu(R), Rb)           # the residual itself is not written
+    Y, B = oracle.w4a8_gemm_add(An, sn, d["q"], d["gscale"], d["w_tscale"], Rb, want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Yg), Y, B, "add %s %s" % (kernel, shape))
+    Yi = fq.fq_w4a8_gemm_add(A, s, packed, _gpu(d["gscale"]), d["w_tscale"], N, R, out=R)
+    torch.cuda.synchronize()
+    assert Yi.data_ptr() == R.data_ptr()
+    assert np.array_equal(bf16_bits_from_gpu(Yi), bf16_bits_from_gpu(Yg)), "in place differs"
+
+
+def test_gemm_add_with_zero_activations_returns_the_residual(fq, kernel_choice):
+    """All-zero activations: every output is bf16(0 + R[m,n]) = R[m,n] bit for bit, so each element of the
+    residual has to arrive at its own place (whole tiles, half tiles and ragged edges of every kernel)."""
+    K = 256
+    for kernel, M, N in (("simple", 9, 70), ("small", 16, 264), ("small", 50, 1000), ("large", 256, 128),
+                         ("large", 384, 392), ("large", 700, 1025)):
+        q = np.random.default_rng(M).integers(-8, 8, (N, K), dtype=np.int8)
+        gs = np.full((N, K // 128), 0x38, np.uint8)
+        A = np.zeros((M, K), np.uint8)
+        Rb = np.random.default_rng(N).integers(0, 0x7F80, (M, N)).astype(np.uint16)
+        Rb |= np.random.default_rng(N + 1).integers(0, 2, (M, N)).astype(np.uint16) << 15
+        Rb[Rb == 0x8000] = 0                                   # 0 + (-0) is +0
+        kernel_choice(kernel)
+        Yg = fq.fq_w4a8_gemm_add(_gpu(A), _gpu(np.ones(M, np.float32)), fq.fq_pack_weights(_gpu(q)), _gpu(gs), 1.0, N,
+                                 to_gpu_bf16(Rb))
+        torch.cuda.synchronize()
+        got = bf16_bits_from_gpu(Yg)
+        bad = np.argwhere(got != Rb)
+        assert bad.size == 0, "%s M=%d N=%d: first wrong element %s" % (kernel, M, N, bad[:1])
+
+
+def test_down_projection_with_residual_full_size(fq):
+    """The down projection at its real size (M=2048, N=4096, K=11008) with the residual stream added in
+    place, through the fused quantiser, on sampled rows against the oracle."""
+    name = "ffn_l2_7b_down_residual"
+    w = workloads.WORKLOADS[name]
+    d = workloads.draw_workload(name)
+    need = fq.fq_w4a8_gemm_workspace_bytes(w.M, w.N, w.K)
+    ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]), workspace=ws)
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    rows = [0, 1, 127, 128, 255, 256, 1111, 2047]
+    An, sn = A.cpu().numpy()[rows], s.cpu().numpy()[rows]
+    Y0 = oracle.w4a8_gemm(An, sn, d["q"], d["gscale"], d["w_tscale"])
+    Rb = _residual_bits(w.M, w.N, workloads.RESIDUAL_SCALE, seed=w.seed)
+    assert 0.3 < np.std(Y0) / workloads.RESIDUAL_SCALE < 3       # residual and GEMM of like size
+    R = to_gpu_bf16(Rb)
+    fq.fq_w4a8_gemm_add(A, s, packed, _gpu(d["gscale"]), d["w_tscale"], w.N, R, out=R, workspace=ws, workspace_prepared=True)
+    torch.cuda.synchronize()
+    Y, B = oracle.w4a8_gemm_add(An, sn, d["q"], d["gscale"], d["w_tscale"], Rb[rows], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(R)[rows], Y, B, name + " + residual")
+
+
 def test_m_zero_is_a_noop(fq):
     packed = torch.zeros(fq.fq_packed_weight_bytes(32, 128), dtype=torch.uint8, device="cuda")
     Y = fq.fq_w4a8_gemm(torch.zeros((0, 128), dtype=torch.uint8, device="cuda"),
