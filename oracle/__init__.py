@@ -69,6 +69,14 @@ def _load():
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.fqo_quantize_act.restype = ctypes.c_int
     lib.fqo_quantize_act.argtypes = [u16p, u8p, f32p, ctypes.c_int, ctypes.c_int]
+    lib.fqo_e4m3_encode_rtz.restype = ctypes.c_uint8
+    lib.fqo_e4m3_encode_rtz.argtypes = [ctypes.c_double]
+    lib.fqo_cas_scales.restype = ctypes.c_int
+    lib.fqo_cas_scales.argtypes = [u16p, ctypes.c_double, f64p, ctypes.c_int, ctypes.c_int]
+    lib.fqo_scaled_weights.restype = None
+    lib.fqo_scaled_weights.argtypes = [u16p, f32p, f32p, ctypes.c_int, ctypes.c_int]
+    lib.fqo_quantize_weights.restype = ctypes.c_int
+    lib.fqo_quantize_weights.argtypes = [u16p, f32p, ctypes.c_int, ctypes.c_int, i8p, u8p, ctypes.c_int, ctypes.c_int]
     lib.fqo_num_threads.restype = ctypes.c_int
     lib.fqo_num_threads.argtypes = []
     _lib = lib
@@ -205,6 +213,62 @@ def quantize_act(X_bf16_bits):
     if rc != 0:
         raise ValueError("fqo_quantize_act failed with %d" % rc)
     return A, s
+
+
+# ---- offline weight quantisation -------------------------------------------------------------
+
+def e4m3_encode_rtz(x: float) -> int:
+    return int(_load().fqo_e4m3_encode_rtz(float(x)))
+
+
+def cas_scales(W_bf16_bits, target: float) -> np.ndarray:
+    """float64 [K]: lambda[k] = target / absmean_n(W[n,k]) (Def. 3.1); W: uint16 [N,K] bf16 bits."""
+    W = _c(W_bf16_bits, np.uint16)
+    N, K = W.shape
+    lam = np.zeros((K,), dtype=np.float64)
+    rc = _load().fqo_cas_scales(_ptr(W, ctypes.c_uint16), float(target), _ptr(lam, ctypes.c_double), N, K)
+    if rc != 0:
+        raise ValueError("fqo_cas_scales failed with %d" % rc)
+    return lam
+
+
+def _lambda_ptr(lam, K):
+    if lam is None:
+        return None, ctypes.POINTER(ctypes.c_float)()
+    lam = _c(lam, np.float32)
+    if lam.shape != (K,):
+        raise ValueError("lambda must be float32 [K]")
+    return lam, _ptr(lam, ctypes.c_float)
+
+
+def scaled_weights(W_bf16_bits, lam=None) -> np.ndarray:
+    """float32 [N,K]: bf16 W[n,k] * float32 lambda[k], rounded once to FP32 (lambda None: W itself)."""
+    W = _c(W_bf16_bits, np.uint16)
+    N, K = W.shape
+    lam, lp = _lambda_ptr(lam, K)
+    out = np.zeros((N, K), dtype=np.float32)
+    _load().fqo_scaled_weights(_ptr(W, ctypes.c_uint16), lp, _ptr(out, ctypes.c_float), N, K)
+    return out
+
+
+def pts_exponent(W_bf16_bits, lam=None) -> int:
+    """n of Def. 3.2 for the (channel-scaled) weights; delta = 2^n, the GEMM's w_tscale is 2^-n."""
+    from . import pts
+    return pts.pts_exponent(scaled_weights(W_bf16_bits, lam))
+
+
+def quantize_weights(W_bf16_bits, lam=None, n_pts: int = 0, sigma_rne: bool = False):
+    """(int8 [N,K] INT4 codes, uint8 [N,K/128] E4M3 group scales) of eq. 1 applied to W * lambda * 2^n."""
+    W = _c(W_bf16_bits, np.uint16)
+    N, K = W.shape
+    lam, lp = _lambda_ptr(lam, K)
+    q = np.zeros((N, K), dtype=np.int8)
+    gs = np.zeros((N, K // 128), dtype=np.uint8)
+    rc = _load().fqo_quantize_weights(_ptr(W, ctypes.c_uint16), lp, int(n_pts), 1 if sigma_rne else 0,
+                                      _ptr(q, ctypes.c_int8), _ptr(gs, ctypes.c_uint8), N, K)
+    if rc != 0:
+        raise ValueError("fqo_quantize_weights failed with %d" % rc)
+    return q, gs
 
 
 def bf16_round_array(Y: np.ndarray) -> np.ndarray:

@@ -24,6 +24,11 @@
  *
  *   Y[m,n] = a_scale[m] * w_tscale * sum_g dec8(gscale[n,g]) * sum_{k in g} dec8(A[m,k]) * q[n,k]
  *
+ *   offline quantiser        Sec. 2.1 eq. 1 (group-wise INT4), Def. 3.1 (channel-wise absmean
+ *                            scaling), Def. 3.2 (per-tensor scaling; its search for n is in
+ *                            pts.py beside this file, in exact integer arithmetic),
+ *                            Lemma B.1 (underflow of the FP8 group scale).
+ *
  * Readings of points the paper leaves open (scale applied exactly in FP64 instead of a
  * rounded FP8 look-up table; one round-to-nearest-even to bf16 at the very end; the
  * activation scale is absmax/448 in FP32; an all-zero row gets scale 1) are stated at the
@@ -338,6 +343,117 @@ int fqo_quantize_act(const uint16_t *X, uint8_t *A, float *a_scale, int M, int K
             double x = fqo_bf16_decode(X[(size_t)m * K + k]);
             float quot = (float)(x / (double)s);   /* = IEEE binary32 division of two floats */
             A[(size_t)m * K + k] = fqo_e4m3_encode_rne((double)quot);
+        }
+    }
+    return 0;
+}
+
+/* =======================================================================================
+ * Offline weight quantisation (the step that produces the GEMM's weight operands).
+ * ===================================================================================== */
+
+/* Largest E4M3 value not above |x| in magnitude (rounding toward zero), saturating at 448.
+ * This is the cast Lemma B.1 (App. B) describes for the group scale: a value below the
+ * smallest subnormal 2^-9 becomes 0.  By definition: scan the finite non-negative codes.  */
+uint8_t fqo_e4m3_encode_rtz(double x)
+{
+    if (isnan(x))
+        return 0x7F;
+    uint8_t sign = (uint8_t)(signbit(x) ? 0x80 : 0x00);
+    double a = fabs(x);
+    int best = 0;
+    for (int c = 1; c <= 0x7E; ++c)
+        if (fqo_e4m3_decode((uint8_t)c) <= a)
+            best = c;                             /* decode is increasing in c on 0..0x7E */
+    return (uint8_t)(sign | best);
+}
+
+/* Channel-wise absmean scaling (Sec. 3.1.2, Def. 3.1): W is [N,K] (output channel n, input
+ * channel k; Y = X W^T), Lambda is diagonal over the K input channels and scales column k,
+ *
+ *   lambda[k] = target / absmean_n(W[n,k]),   absmean = (1/N) sum_n |W[n,k]|.
+ *
+ * Reading: a column that is entirely zero has no absmean to normalise; it keeps lambda = 1.
+ * W holds bf16 bit patterns.  FP64 throughout.  Returns 0, -1 on a bad shape.               */
+int fqo_cas_scales(const uint16_t *W, double target, double *lambda, int N, int K)
+{
+    if (N <= 0 || K <= 0)
+        return -1;
+    for (int k = 0; k < K; ++k) {
+        double s = 0.0;
+        for (int n = 0; n < N; ++n)
+            s += fabs(fqo_bf16_decode(W[(size_t)n * K + k]));
+        lambda[k] = (s == 0.0) ? 1.0 : target / (s / (double)N);
+    }
+    return 0;
+}
+
+/* The scaled weight the quantiser and the per-tensor search work on: bf16 W[n,k] times the
+ * FP32 lambda[k] (NULL = no channel scaling), the product rounded once to FP32.  The product
+ * of a bf16 and an FP32 number has at most 32 significant bits, so the FP64 product is exact
+ * and the conversion below is the single rounding.                                          */
+static float fqo_scaled_weight(const uint16_t *W, const float *lambda, size_t n, int k, int K)
+{
+    double w = fqo_bf16_decode(W[n * (size_t)K + (size_t)k]);
+    return lambda ? (float)(w * (double)lambda[k]) : (float)w;
+}
+
+void fqo_scaled_weights(const uint16_t *W, const float *lambda, float *out, int N, int K)
+{
+    for (size_t n = 0; n < (size_t)N; ++n)
+        for (int k = 0; k < K; ++k)
+            out[n * (size_t)K + (size_t)k] = fqo_scaled_weight(W, lambda, n, k, K);
+}
+
+/* Group-wise INT4 quantisation with an FP8 scale (Sec. 2.1 eq. 1 with b = 4, on groups of 128
+ * consecutive k of one output channel, Sec. 3.1), applied to v = scaled weight * 2^n_pts
+ * (Def. 3.2: the matrix is multiplied by delta = 2^n before quantisation):
+ *
+ *   sigma    = max_group |v| / 7                       FP32 division
+ *   sigma8   = E4M3(sigma)                             toward zero (Lemma B.1) or nearest-even
+ *   q        = clamp(round(v / dec8(sigma8)), -8, 7)   FP32 division, ties to even
+ *   sigma8 = 0  ->  q = 0 for the whole group          (Lemma B.1)
+ *
+ * Readings: eq. 1 gives no rounding rule for the quotient (nearest, ties to even, taken here)
+ * and does not say how sigma becomes FP8.  Lemma B.1 states that a sigma below 2^-9 becomes 0,
+ * which holds for rounding toward zero and not for rounding to nearest (2^-10 < sigma < 2^-9
+ * would round up to 2^-9); sigma_rne = 0 takes the lemma's cast, sigma_rne = 1 the
+ * nearest-even cast of the usual hardware converters.  The quotient can exceed 7 when the
+ * cast lowers sigma, hence the clamp to the INT4 range of eq. 1.  |v| beyond 7 * 448 saturates
+ * sigma8 at 448 (App. C.1: 448 is the overflow threshold).  Inputs are finite.
+ * q [N,K] int8, gscale [N,K/128] E4M3 codes.  Returns 0, -1 on a bad shape.                   */
+int fqo_quantize_weights(const uint16_t *W, const float *lambda, int n_pts, int sigma_rne,
+                         int8_t *q, uint8_t *gscale, int N, int K)
+{
+    if (N < 0 || K <= 0 || (K % FQO_GROUP) != 0 || n_pts < 0 || n_pts > 126)
+        return -1;
+    const int G = K / FQO_GROUP;
+    for (size_t n = 0; n < (size_t)N; ++n) {
+        for (int g = 0; g < G; ++g) {
+            float v[FQO_GROUP];
+            float vmax = 0.0f;
+            for (int i = 0; i < FQO_GROUP; ++i) {
+                /* times 2^n: exact unless it overflows FP32, which finite sane weights do not */
+                v[i] = ldexpf(fqo_scaled_weight(W, lambda, n, g * FQO_GROUP + i, K), n_pts);
+                if (fabsf(v[i]) > vmax)
+                    vmax = fabsf(v[i]);
+            }
+            const float sigma = (float)((double)vmax / 7.0);          /* = IEEE binary32 division */
+            const double sc = sigma >= 448.0f ? 448.0 : (double)sigma;
+            const uint8_t code = sigma_rne ? fqo_e4m3_encode_rne(sc) : fqo_e4m3_encode_rtz(sc);
+            gscale[n * (size_t)G + (size_t)g] = code;
+            const double s8 = fqo_e4m3_decode(code);
+            for (int i = 0; i < FQO_GROUP; ++i) {
+                int c = 0;
+                if (s8 > 0.0) {
+                    const float quot = (float)((double)v[i] / s8);    /* = IEEE binary32 division */
+                    double r = nearbyint((double)quot);               /* default mode: ties to even */
+                    if (r > 7.0) r = 7.0;
+                    if (r < -8.0) r = -8.0;
+                    c = (int)r;
+                }
+                q[n * (size_t)K + (size_t)(g * FQO_GROUP + i)] = (int8_t)c;
+            }
         }
     }
     return 0;
