@@ -3,7 +3,8 @@
  *
  * The library implements the INT4-weight x FP8-activation GEMM that runs every linear layer
  * of FireQ (arXiv 2505.20839, Sec. 3.1.1), the activation quantiser that feeds it
- * (Sec. 2.1 eq. 2) and the offline weight packing it reads.
+ * (Sec. 2.1 eq. 2), the offline weight quantiser (Sec. 2.1 eq. 1, Defs. 3.1 and 3.2) and the
+ * weight packing the GEMM reads.
  *
  * Conventions for every entry point
  *   - All pointers are DEVICE pointers into memory owned by the caller.  The library
@@ -145,6 +146,41 @@ int fq_quantize_act_ws(const uint16_t *X_bf16, uint8_t *A_fp8, float *a_scale, i
 size_t fq_packed_weight_bytes(int N, int K);
 int fq_pack_weights(const int8_t *q, uint8_t *Wq_packed, int N, int K, void *stream);
 int fq_unpack_weights(const uint8_t *Wq_packed, int8_t *q, int N, int K, void *stream);
+
+/*
+ * Offline weight quantisation: from a bfloat16 weight matrix W [N,K] (row n = output channel,
+ * column k = input channel; Y = X W^T) to the operands of the GEMM.  Typical order:
+ * fq_cas_scales, fq_pts_exponent, fq_quantize_weights, fq_pack_weights; the GEMM then takes
+ * w_tscale = 2^-n.  All of it works on v[n,k] = W[n,k] * lambda[k] rounded once to FP32
+ * (lambda == NULL: v = W).
+ *
+ * fq_cas_scales -- channel-wise absmean scaling (Sec. 3.1.2, Def. 3.1):
+ *   lambda[k] = target / ((1/N) * sum_n |W[n,k]|), FP64 sums, result rounded to FP32; a channel
+ *   that is zero throughout keeps lambda = 1.  lambda is [K] FP32 (output); target > 0.  The
+ *   caller merges 1/lambda into whatever produces the layer's input, as the paper does.
+ *
+ * fq_pts_exponent -- per-tensor scaling (Def. 3.2, App. C.1): the smallest n >= 0 such that
+ *   (1) every non-zero |v| * 2^n is at least 7 * 2^-9, the point from which the cumulative
+ *       underflow S(v * 2^n) = sum max(0, 7 * 2^-9 - |v| * 2^n) no longer falls, or
+ *   (2) some element satisfies 7 * 2^(5-n) <= |v| < 7 * 2^(6-n);
+ *   capped at 126 so that 2^n stays an FP32 number.  n_out is DEVICE memory of 64 bytes,
+ *   16-byte aligned: its first int receives n, the rest is scratch of the call.
+ *
+ * fq_quantize_weights -- group-wise INT4 with an FP8 scale (Sec. 2.1 eq. 1 with b = 4, groups
+ *   of 128 along K, Sec. 3.1), on v * 2^n_pts (0 <= n_pts <= 126):
+ *     sigma  = max_group |v * 2^n| / 7             (FP32 division), at most 448
+ *     sigma8 = E4M3 of sigma, rounded toward zero when sigma_nearest == 0 -- the cast of App. B,
+ *              Lemma B.1, under which a group with max < 7 * 2^-9 gets sigma8 = 0 -- or to
+ *              nearest-even when sigma_nearest != 0
+ *     q      = clamp(round_half_even(v * 2^n / sigma8), -8, 7)  (FP32 division); 0 where sigma8 = 0
+ *   q [N,K] int8 (the input format of fq_pack_weights, 16-byte aligned here),
+ *   w_gscale [N,K/128] E4M3 codes.  Weights are finite.
+ */
+int fq_cas_scales(const uint16_t *W_bf16, float target, float *lambda, int N, int K, void *stream);
+int fq_pts_exponent(const uint16_t *W_bf16, const float *lambda, int *n_out, int N, int K,
+                    void *stream);
+int fq_quantize_weights(const uint16_t *W_bf16, const float *lambda, int n_pts, int sigma_nearest,
+                        int8_t *q, uint8_t *w_gscale, int N, int K, void *stream);
 
 /* Changes whenever the byte order written by fq_pack_weights changes. */
 int fq_layout_version(void);

@@ -54,6 +54,12 @@ def lib() -> ctypes.CDLL:
     L.fq_pack_weights.argtypes = [vp, vp, ci, ci, vp]
     L.fq_unpack_weights.restype = ci
     L.fq_unpack_weights.argtypes = [vp, vp, ci, ci, vp]
+    L.fq_cas_scales.restype = ci
+    L.fq_cas_scales.argtypes = [vp, cf, vp, ci, ci, vp]
+    L.fq_pts_exponent.restype = ci
+    L.fq_pts_exponent.argtypes = [vp, vp, vp, ci, ci, vp]
+    L.fq_quantize_weights.restype = ci
+    L.fq_quantize_weights.argtypes = [vp, vp, ci, ci, vp, vp, ci, ci, vp]
     L.fq_layout_version.restype = ci
     L.fq_layout_version.argtypes = []
     L.fq_status_string.restype = ctypes.c_char_p
@@ -86,6 +92,54 @@ def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
 
 def _stream() -> ctypes.c_void_p:
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def fq_cas_scales(W: torch.Tensor, target: float) -> torch.Tensor:
+    """float32 [K]: lambda[k] = target / absmean_n(W[n,k]) of a bf16 weight matrix [N,K]."""
+    W = _dev(W, torch.bfloat16, "W")
+    N, K = W.shape
+    lam = torch.empty((K,), dtype=torch.float32, device=W.device)
+    rc = lib().fq_cas_scales(W.data_ptr(), ctypes.c_float(float(target)), lam.data_ptr(), N, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_cas_scales")
+    return lam
+
+
+def _lambda_ptr(lam, K):
+    if lam is None:
+        return 0
+    lam = _dev(lam, torch.float32, "lam")
+    if lam.numel() != K:
+        raise FireqError(-2, "lambda")
+    return lam.data_ptr()
+
+
+def fq_pts_exponent(W: torch.Tensor, lam: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """int32 device tensor of 16 ints whose first element is the per-tensor exponent n (delta = 2^n) of the
+    bf16 matrix W [N,K] scaled by lam [K]; reading it (``int(t[0])``) synchronises, the call does not."""
+    W = _dev(W, torch.bfloat16, "W")
+    N, K = W.shape
+    out = torch.empty((16,), dtype=torch.int32, device=W.device)
+    rc = lib().fq_pts_exponent(W.data_ptr(), _lambda_ptr(lam, K), out.data_ptr(), N, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_pts_exponent")
+    return out
+
+
+def fq_quantize_weights(W: torch.Tensor, lam: Optional[torch.Tensor] = None, n_pts: int = 0,
+                        sigma_nearest: bool = False):
+    """(int8 [N,K] INT4 codes, uint8 [N,K/128] E4M3 group scales) of W * lam * 2^n_pts."""
+    W = _dev(W, torch.bfloat16, "W")
+    N, K = W.shape
+    if K % GROUP:
+        raise FireqError(-2, "fq_quantize_weights")
+    q = torch.empty((N, K), dtype=torch.int8, device=W.device)
+    gs = torch.empty((N, K // GROUP), dtype=torch.uint8, device=W.device)
+    rc = lib().fq_quantize_weights(W.data_ptr(), _lambda_ptr(lam, K), int(n_pts), 1 if sigma_nearest else 0,
+                                   q.data_ptr(), gs.data_ptr(), N, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_quantize_weights")
+    return q, gs
 
 
 def fq_pack_weights(q: torch.Tensor) -> torch.Tensor:

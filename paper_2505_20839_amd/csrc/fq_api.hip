@@ -102,6 +102,32 @@ int fq_quantize_act(const uint16_t* X_bf16, uint8_t* A_fp8, float* a_scale, int 
     return after_launch();
 }
 
+int fq_cas_scales(const uint16_t* W_bf16, float target, float* lambda, int N, int K, void* stream) {
+    if (N <= 0 || K <= 0 || !(target > 0.f)) return FQ_ERR_SHAPE;
+    if (!W_bf16 || !lambda) return FQ_ERR_NULL;
+    fq_launch_cas_scales(W_bf16, target, lambda, N, K, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_pts_exponent(const uint16_t* W_bf16, const float* lambda, int* n_out, int N, int K, void* stream) {
+    if (N <= 0 || K <= 0 || (K % FQ_GROUP) != 0) return FQ_ERR_SHAPE;
+    if (!W_bf16 || !n_out) return FQ_ERR_NULL;
+    if (!aligned16(W_bf16) || !aligned16(n_out)) return FQ_ERR_ALIGN;
+    fq_launch_pts_exponent(W_bf16, lambda, n_out, N, K, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_quantize_weights(const uint16_t* W_bf16, const float* lambda, int n_pts, int sigma_nearest,
+                        int8_t* q, uint8_t* w_gscale, int N, int K, void* stream) {
+    if (N < 0 || K <= 0 || (K % FQ_GROUP) != 0 || n_pts < 0 || n_pts > 126) return FQ_ERR_SHAPE;
+    if (N == 0) return FQ_OK;
+    if (!W_bf16 || !q || !w_gscale) return FQ_ERR_NULL;
+    if (!aligned16(W_bf16) || !aligned16(q)) return FQ_ERR_ALIGN;
+    fq_launch_quantize_weights(W_bf16, lambda, n_pts, sigma_nearest != 0, q, w_gscale, N, K,
+                               static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
 size_t fq_w4a8_gemm_workspace_bytes(int M, int N, int K) {
     if (M <= 0 || N <= 0 || K <= 0 || (K % FQ_GROUP) != 0) return 0;
     return choose_kernel(M) == GemmKernel::Large ? fq_gemm_large_workspace_bytes(M, K) : 0;

@@ -34,3 +34,11 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
 bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, const uint16_t* R,
                            hipStream_t stream);
+
+// Offline weight quantisation (fq_wquant.hip).  W is [N,K] bf16; lambda (may be NULL) is [K] FP32.
+void fq_launch_cas_scales(const uint16_t* W, float target, float* lambda, int N, int K, hipStream_t stream);
+// n_out: 64 bytes of device memory; int 0 receives n, ints 8..12 are scratch for the statistics.
+void fq_launch_pts_exponent(const uint16_t* W, const float* lambda, int* n_out, int N, int K, hipStream_t stream);
+void fq_launch_quantize_weights(const uint16_t* W, const float* lambda, int n_pts, bool sigma_rne, int8_t* q,
+                                uint8_t* gs, int N, int K, hipStream_t stream);
+

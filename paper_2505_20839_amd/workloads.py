@@ -120,6 +120,19 @@ def draw_residual(M: int, N: int, *, scale: float, seed: int) -> np.ndarray:
     return f32_to_bf16_bits(rng.standard_normal((M, N), dtype=np.float32) * np.float32(scale))
 
 
+def draw_weights(N: int, K: int, *, seed: int, std: float = 0.02, channel_spread: float = 0.5,
+                 zero_frac: float = 0.0) -> np.ndarray:
+    """uint16 [N,K] bf16 bit patterns of a synthetic weight matrix for the offline quantiser: N(0, std^2)
+    entries, input channel k scaled by a log-normal factor exp(channel_spread * N(0,1)) (the uneven
+    channel magnitudes that channel-wise scaling evens out), a fraction `zero_frac` of entries set to zero."""
+    rng = np.random.default_rng([seed, 0xBEEF])
+    W = rng.standard_normal((N, K), dtype=np.float32) * np.float32(std)
+    W *= np.exp(channel_spread * rng.standard_normal((1, K))).astype(np.float32)
+    if zero_frac > 0:
+        W[rng.random((N, K)) < zero_frac] = 0.0
+    return f32_to_bf16_bits(W)
+
+
 def draw_workload(name: str, rows: Optional[int] = None):
     w = WORKLOADS[name]
     return draw(w.M, w.N, w.K, seed=w.seed, act=w.act, outlier_frac=w.outlier_frac,

@@ -21,7 +21,8 @@ def test_library_exports_every_declared_symbol():
     L = binding.lib()
     names = _declared_functions()
     assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_swiglu_ws", "fq_w4a8_gemm_add_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_quantize_act_ws", "fq_packed_weight_bytes", "fq_pack_weights",
-                            "fq_unpack_weights", "fq_layout_version", "fq_status_string"])
+                            "fq_unpack_weights", "fq_layout_version", "fq_status_string",
+                            "fq_cas_scales", "fq_pts_exponent", "fq_quantize_weights"])
     for name in names:
         assert hasattr(L, name), name
     assert os.path.samefile(L._name, build.LIB_PATH)
@@ -97,6 +98,19 @@ def test_bad_arguments_are_rejected_without_a_launch():
     assert L.fq_quantize_act(p, p, p, 0, 128, null) == 0
     assert L.fq_quantize_act(null, p, p, 4, 128, null) == -1
     assert L.fq_quantize_act(p, odd, p, 4, 128, null) == -3
+    # offline weight quantiser
+    assert L.fq_cas_scales(p, f1, p, 0, 128, null) == -2
+    assert L.fq_cas_scales(p, ctypes.c_float(0.0), p, 4, 128, null) == -2
+    assert L.fq_cas_scales(null, f1, p, 4, 128, null) == -1
+    assert L.fq_pts_exponent(p, null, p, 4, 100, null) == -2
+    assert L.fq_pts_exponent(p, null, null, 4, 128, null) == -1
+    assert L.fq_pts_exponent(p, null, odd, 4, 128, null) == -3
+    assert L.fq_quantize_weights(p, null, 0, 0, p, p, 4, 100, null) == -2
+    assert L.fq_quantize_weights(p, null, 127, 0, p, p, 4, 128, null) == -2
+    assert L.fq_quantize_weights(p, null, -1, 0, p, p, 4, 128, null) == -2
+    assert L.fq_quantize_weights(p, null, 0, 0, null, p, 4, 128, null) == -1
+    assert L.fq_quantize_weights(p, null, 0, 0, odd, p, 4, 128, null) == -3
+    assert L.fq_quantize_weights(null, null, 0, 0, null, null, 0, 128, null) == 0
     assert L.fq_pack_weights(p, p, 8, 100, null) == -2
     assert L.fq_pack_weights(null, p, 8, 128, null) == -1
     assert L.fq_pack_weights(p, odd, 8, 128, null) == -3

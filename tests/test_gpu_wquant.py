@@ -1,0 +1,143 @@
+"""GPU parity of the offline weight quantiser (fq_cas_scales, fq_pts_exponent, fq_quantize_weights)
+against the CPU oracle: channel scales to the last FP32 bit, the per-tensor exponent exactly, INT4 codes
+and FP8 group scales bit for bit."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_20839_amd import workloads
+from parity_util import bf16_bits_from_gpu, check_gemm, to_gpu_bf16
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+T = 7 * 2.0 ** -9
+
+
+@pytest.fixture(scope="module")
+def fq():
+    from paper_2505_20839_amd import binding
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    binding.lib()
+    return binding
+
+
+def _bits(x):
+    return workloads.f32_to_bf16_bits(np.asarray(x, np.float32))
+
+
+@pytest.mark.parametrize("N,K,seed", [(40, 128, 0), (300, 1000, 1), (7, 64, 2), (1024, 512, 3)])
+def test_cas_scales_match_oracle(fq, N, K, seed):
+    Wb = workloads.draw_weights(N, K, seed=seed, channel_spread=1.0)
+    Wb[:, K // 3] = 0                                          # an all-zero channel keeps lambda = 1
+    target = float(np.float32(0.03))                            # the entry point takes the target as FP32
+    lam = fq.fq_cas_scales(to_gpu_bf16(Wb), target).cpu().numpy()
+    want = oracle.cas_scales(Wb, target)
+    assert lam.dtype == np.float32 and lam[K // 3] == 1.0
+    w32 = want.astype(np.float32)
+    ulp = np.abs(np.nextafter(w32, np.float32(np.inf)) - w32)
+    assert np.all(np.abs(lam.astype(np.float64) - want) <= ulp), "more than one FP32 ulp from the FP64 value"
+    assert np.mean(lam == w32) > 0.999
+
+
+PTS_CASES = {
+    "typical": dict(std=0.02, zero_frac=0.0),                  # the overflow band stops the search
+    "tiny": dict(std=2e-5, zero_frac=0.0),
+    "with_zeros": dict(std=0.02, zero_frac=0.3),
+    "wide": dict(std=0.5, channel_spread=2.0),
+}
+
+
+@pytest.mark.parametrize("case", sorted(PTS_CASES))
+@pytest.mark.parametrize("with_lambda", [False, True])
+def test_pts_exponent_matches_oracle(fq, case, with_lambda):
+    Wb = workloads.draw_weights(48, 512, seed=len(case), **PTS_CASES[case])
+    W = to_gpu_bf16(Wb)
+    lam = fq.fq_cas_scales(W, 0.05) if with_lambda else None
+    n = int(fq.fq_pts_exponent(W, lam)[0])
+    assert n == oracle.pts_exponent(Wb, None if lam is None else lam.cpu().numpy())
+
+
+def test_pts_exponent_hand_matrices(fq):
+    """The cases that pin the two conditions of the definition and their edges, through the GPU."""
+    def n_of(values):
+        v = np.zeros((1, 128), np.float32)
+        v[0, :len(values)] = values
+        n = int(fq.fq_pts_exponent(to_gpu_bf16(_bits(v)))[0])
+        assert n == oracle.pts_exponent(_bits(v))
+        return n
+    assert n_of([1.0, -0.5, T]) == 0                           # zeros of the padding never matter
+    assert n_of([]) == 0
+    assert n_of([1.0, T / 8]) == 3
+    assert n_of([0.5, 2.0 ** -40]) == 9
+    assert n_of([224.0, 2.0 ** -40]) == 0
+    assert n_of([223.0, 2.0 ** -40]) == 1
+    assert n_of([448.0, T / 4]) == 2
+    assert n_of([2.0 ** -100]) == 94
+    assert n_of([2.0 ** -130]) == 124
+
+
+@pytest.mark.parametrize("N,K,n_pts,with_lambda,rne", [(33, 256, 0, False, False), (64, 512, 9, True, False),
+                                                       (64, 512, 9, True, True), (5, 128, 3, False, True),
+                                                       (257, 1408, 11, True, False)])
+def test_quantize_weights_matches_oracle_bit_for_bit(fq, N, K, n_pts, with_lambda, rne):
+    Wb = workloads.draw_weights(N, K, seed=N + K, std=0.02 * 2.0 ** (9 - n_pts), zero_frac=0.05)
+    Wb[0, :128] = 0                                            # an all-zero group
+    Wb[N - 1, K - 128:] = _bits(np.full(128, T / 2 ** n_pts * 0.9))   # a group under Lemma B.1's threshold
+    W = to_gpu_bf16(Wb)
+    lam = fq.fq_cas_scales(W, 0.02 * 2.0 ** (9 - n_pts)) if with_lambda else None
+    lam_np = None if lam is None else lam.cpu().numpy()
+    q, gs = fq.fq_quantize_weights(W, lam, n_pts, sigma_nearest=rne)
+    torch.cuda.synchronize()
+    q_ref, gs_ref = oracle.quantize_weights(Wb, lam_np, n_pts, sigma_rne=rne)
+    assert np.array_equal(gs.cpu().numpy(), gs_ref)
+    assert np.array_equal(q.cpu().numpy(), q_ref)
+    assert gs_ref[0, 0] == 0 and (with_lambda or rne or gs_ref[N - 1, -1] == 0)
+    assert q_ref.min() == -8 or q_ref.max() == 7               # the range is used
+
+
+def test_chain_from_bf16_weights_to_the_gemm(fq):
+    """Channel scales, per-tensor exponent, quantiser, packing and the GEMM with w_tscale = 2^-n: the
+    result equals the oracle's GEMM on the oracle's own codes, and stays close to X W^T in FP64."""
+    M, N, K = 96, 160, 1024
+    Wb = workloads.draw_weights(N, K, seed=77)
+    W = to_gpu_bf16(Wb)
+    n = int(fq.fq_pts_exponent(W)[0])
+    q, gs = fq.fq_quantize_weights(W, None, n)
+    d = workloads.draw(M, N, K, seed=78)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    Y = fq.fq_w4a8_gemm(A, s, fq.fq_pack_weights(q), gs, 2.0 ** -n, N)
+    torch.cuda.synchronize()
+    assert n == oracle.pts_exponent(Wb)
+    q_ref, gs_ref = oracle.quantize_weights(Wb, None, n)
+    Yr, B = oracle.w4a8_gemm(A.cpu().numpy(), s.cpu().numpy(), q_ref, gs_ref, 2.0 ** -n, want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Y), Yr, B, "chain")
+    exact = oracle.bf16_bits_to_f64(d["X_bf16"]) @ oracle.bf16_bits_to_f64(Wb).T
+    rel = np.linalg.norm(oracle.bf16_bits_to_f64(bf16_bits_from_gpu(Y)) - exact) / np.linalg.norm(exact)
+    assert rel < 0.25, rel              # INT4 steps of max/7 on uneven channels: 10-20 % is the format's own error
+
+
+def test_full_size_gate_up_matrix(fq):
+    """Llama2-7B gate/up shape (11008 x 4096): sampled channels against the oracle; the exponent against the
+    two conditions of the definition evaluated with numpy on the whole matrix."""
+    N, K = 11008, 4096
+    Wb = workloads.draw_weights(N, K, seed=5)
+    W = to_gpu_bf16(Wb)
+    lam = fq.fq_cas_scales(W, 0.02)
+    n = int(fq.fq_pts_exponent(W, lam)[0])
+    q, gs = fq.fq_quantize_weights(W, lam, n)
+    torch.cuda.synchronize()
+    lam_np = lam.cpu().numpy()
+    rows = [0, 1, 31, 32, 5000, 11007]
+    q_ref, gs_ref = oracle.quantize_weights(Wb[rows], lam_np, n)
+    assert np.array_equal(q.cpu().numpy()[rows], q_ref) and np.array_equal(gs.cpu().numpy()[rows], gs_ref)
+    cols = [0, 1, 63, 64, 2047, 4095]
+    want = oracle.cas_scales(Wb, float(np.float32(0.02)))[cols].astype(np.float32)
+    assert np.allclose(lam_np[cols], want, rtol=2e-7, atol=0)
+    v = np.abs(oracle.scaled_weights(Wb, lam_np).astype(np.float64))
+
+    def stops(m):                                              # does the search stop at m?
+        nz = v[v > 0]
+        return bool(np.all(nz * 2.0 ** m >= T)) or bool(np.any((v * 2.0 ** m >= 224) & (v * 2.0 ** m < 448)))
+    assert stops(n) and not any(stops(m) for m in range(n))
