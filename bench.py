@@ -163,6 +163,41 @@ def main() -> int:
         n = reps * graph_steps
         return w, d, n, wall, gemm_all / n, quant_all / n
 
+    def offline_quantiser(N, K, reps=20):
+        """Mean duration of the three offline stages on a synthetic N x K bf16 matrix (graph replays of
+        `reps` calls each) and the HBM rate of their algorithmic bytes."""
+        W = torch.from_numpy(workloads.draw_weights(N, K, seed=5).view(np.int16)).cuda().view(torch.bfloat16)
+        lam = fq.fq_cas_scales(W, 0.02)
+        n_pts = int(fq.fq_pts_exponent(W, lam)[0])
+        stages = {"fq_cas_scales": (lambda: fq.fq_cas_scales(W, 0.02), 2 * N * K + 4 * K),
+                  "fq_pts_exponent": (lambda: fq.fq_pts_exponent(W, lam), 2 * N * K + 4 * K),
+                  "fq_quantize_weights": (lambda: fq.fq_quantize_weights(W, lam, n_pts), 3 * N * K + N * K // 128 + 4 * K)}
+        out = {"N": N, "K": K, "n_pts": n_pts}
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for key, (fn, nbytes) in stages.items():
+                fn()
+                side.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    for _ in range(reps):
+                        fn()
+                g.replay()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                side.synchronize()
+                e0.record(side)
+                g.replay()
+                e1.record(side)
+                side.synchronize()
+                us = e0.elapsed_time(e1) * 1e3 / reps
+                out[key] = {"us": us, "algorithmic_bytes": nbytes, "GBps": nbytes / us / 1e3,
+                            "frac_hbm": nbytes / us / 1e3 / PEAK_HBM_GBPS}
+                del g
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.empty_cache()
+        return out
+
     name = args.workload
     w0 = workloads.WORKLOADS[name]
     decode_like = w0.M <= 64
@@ -231,6 +266,8 @@ def main() -> int:
                              "frac_mfma_peak": fo / gemm_o / 1e12 / PEAK_FP8_TFLOPS}
             torch.cuda.empty_cache()
         out["other_configs"] = others
+        # the offline step that produces the weight operands, on the gate/up matrix of the same model
+        out["offline_quantiser"] = offline_quantiser(11008, 4096)
 
     if not args.no_cpu_baseline:
         import oracle

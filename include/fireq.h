@@ -173,7 +173,7 @@ int fq_unpack_weights(const uint8_t *Wq_packed, int8_t *q, int N, int K, void *s
  *              Lemma B.1, under which a group with max < 7 * 2^-9 gets sigma8 = 0 -- or to
  *              nearest-even when sigma_nearest != 0
  *     q      = clamp(round_half_even(v * 2^n / sigma8), -8, 7)  (FP32 division); 0 where sigma8 = 0
- *   q [N,K] int8 (the input format of fq_pack_weights, 16-byte aligned here),
+ *   q [N,K] int8 (the input format of fq_pack_weights; 16-byte aligned here, like lambda),
  *   w_gscale [N,K/128] E4M3 codes.  Weights are finite.
  */
 int fq_cas_scales(const uint16_t *W_bf16, float target, float *lambda, int N, int K, void *stream);

@@ -122,7 +122,7 @@ int fq_quantize_weights(const uint16_t* W_bf16, const float* lambda, int n_pts, 
     if (N < 0 || K <= 0 || (K % FQ_GROUP) != 0 || n_pts < 0 || n_pts > 126) return FQ_ERR_SHAPE;
     if (N == 0) return FQ_OK;
     if (!W_bf16 || !q || !w_gscale) return FQ_ERR_NULL;
-    if (!aligned16(W_bf16) || !aligned16(q)) return FQ_ERR_ALIGN;
+    if (!aligned16(W_bf16) || !aligned16(q) || (lambda && !aligned16(lambda))) return FQ_ERR_ALIGN;
     fq_launch_quantize_weights(W_bf16, lambda, n_pts, sigma_nearest != 0, q, w_gscale, N, K,
                                static_cast<hipStream_t>(stream));
     return after_launch();
