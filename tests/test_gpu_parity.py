@@ -2,6 +2,7 @@
 seeded inputs.  Integer/byte work (packing, E4M3 codes, row scales) must be bit-exact; the bf16
 GEMM output must satisfy  |Y - Y_ref| <= 1 bf16 ulp + 1e-3 * sum|terms|  per element and a relative
 Frobenius error of at most 2e-3 against the unrounded FP64 result."""
+import ctypes
 import os
 
 import numpy as np
@@ -464,3 +465,64 @@ def test_config5_full(fq, name):
 ])
 def test_large_configs_sampled_rows(fq, name, rows):
     _full_config(fq, name, rows)
+
+
+def test_ws_entry_points_replay_in_a_hip_graph(fq):
+    """The explicit-workspace entry points allocate nothing and keep no state, so a captured graph of
+    quantiser + GEMM (plain, with residual, fused gate/up) can be replayed: three replays on fresh inputs,
+    eager work and synchronisations between them, each replay equal to the eager result bit for bit."""
+    M, N, K = 300, 512, 1024
+    d = workloads.draw(M, N, K, seed=91, gs_lo=0.01, gs_hi=0.1, outlier_frac=0.01)
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    gs = _gpu(d["gscale"])
+    X = to_gpu_bf16(d["X_bf16"]).clone()
+    R = to_gpu_bf16(workloads.draw_residual(M, N, scale=4.0, seed=92))
+    ws = torch.empty((fq.fq_w4a8_gemm_workspace_bytes(M, N, K),), dtype=torch.uint8, device="cuda")
+    A = torch.empty((M, K), dtype=torch.uint8, device="cuda")
+    s = torch.empty((M,), dtype=torch.float32, device="cuda")
+    Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    Ya = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
+    H = torch.empty((M, N // 2), dtype=torch.bfloat16, device="cuda")
+    L = fq.lib()
+
+    def enqueue():
+        st = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        wsb = ws.numel()
+        assert L.fq_quantize_act_ws(X.data_ptr(), A.data_ptr(), s.data_ptr(), M, K, ws.data_ptr(), wsb, st) == 0
+        t = ctypes.c_float(d["w_tscale"])
+        assert L.fq_w4a8_gemm_ws(A.data_ptr(), s.data_ptr(), packed.data_ptr(), gs.data_ptr(), t, Y.data_ptr(),
+                                 M, N, K, ws.data_ptr(), wsb, 1, st) == 0
+        assert L.fq_w4a8_gemm_add_ws(A.data_ptr(), s.data_ptr(), packed.data_ptr(), gs.data_ptr(), t, R.data_ptr(),
+                                     Ya.data_ptr(), M, N, K, ws.data_ptr(), wsb, 1, st) == 0
+        assert L.fq_w4a8_gemm_swiglu_ws(A.data_ptr(), s.data_ptr(), packed.data_ptr(), gs.data_ptr(), t, H.data_ptr(),
+                                        M, N, K, ws.data_ptr(), wsb, 1, st) == 0
+
+    enqueue()                                                  # warm-up outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            enqueue()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        Xn = to_gpu_bf16(workloads.draw(M, N, K, seed=100 + rep, outlier_frac=0.01)["X_bf16"])
+        X.copy_(Xn)
+        for out in (Y, Ya, H, A):
+            out.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [bf16_bits_from_gpu(Y).copy(), bf16_bits_from_gpu(Ya).copy(), bf16_bits_from_gpu(H).copy()]
+        A2, s2 = fq.fq_quantize_act(Xn)                        # eager, library-owned paths
+        want = [bf16_bits_from_gpu(fq.fq_w4a8_gemm(A2, s2, packed, gs, d["w_tscale"], N)),
+                bf16_bits_from_gpu(fq.fq_w4a8_gemm_add(A2, s2, packed, gs, d["w_tscale"], N, R)),
+                bf16_bits_from_gpu(fq.fq_w4a8_gemm_swiglu(A2, s2, packed, gs, d["w_tscale"], N))]
+        torch.cuda.synchronize()
+        assert torch.equal(A, A2)
+        for g, w, what in zip(got, want, ("gemm", "add", "swiglu")):
+            assert np.array_equal(g, w), "replay %d: %s differs from the eager call" % (rep, what)
+    # and the last replay against the oracle
+    Yr, B = oracle.w4a8_gemm(A.cpu().numpy(), s.cpu().numpy(), d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(got[0], Yr, B, "graph replay")
