@@ -238,6 +238,57 @@ int fqo_w4a8_gemm(const uint8_t *A, const float *a_scale, const int8_t *q,
 }
 
 /* ---------------------------------------------------------------------------------------
+ * The GEMM as the paper's own kernel forms it (Sec. 3.1.1 steps 1 and 2): per group a table of
+ * 16 FP8 entries {-8 sigma, ..., 7 sigma} is built from the FP8 group scale, every INT4 weight
+ * is replaced by its table entry, and the matrix unit multiplies FP8 activations with these
+ * FP8 weights; no scale is applied afterwards except the two outer factors:
+ *
+ *   Y[m,n] = a_scale[m] * w_tscale * sum_k dec8(A[m,k]) * dec8( E4M3( q[n,k] * dec8(gscale[n,g(k)]) ) )
+ *
+ * NOT the parity target of the library (which applies the scale exactly, see fqo_w4a8_gemm):
+ * this variant exists to measure what the table's rounding costs in accuracy.
+ * Reading: the entry q * sigma (exact in FP64: 4 x 4 significant bits) is rounded to E4M3
+ * nearest-even, saturating at 448; sums in FP64 (the paper accumulates in FP32).
+ * ------------------------------------------------------------------------------------- */
+int fqo_w4a8_gemm_lut(const uint8_t *A, const float *a_scale, const int8_t *q,
+                      const uint8_t *gscale, float w_tscale, double *Y, int M, int N, int K)
+{
+    if (M < 0 || N < 0 || K < 0 || (K % FQO_GROUP) != 0)
+        return -1;
+    if (M == 0 || N == 0)
+        return 0;
+    const int G = K / FQO_GROUP;
+    double *Wd = (double *)malloc((size_t)N * K * sizeof(double));   /* table entries, decoded */
+    if (!Wd)
+        return -2;
+    for (size_t n = 0; n < (size_t)N; ++n) {
+        for (int g = 0; g < G; ++g) {
+            double table[16];                                       /* index = INT4 code + 8 */
+            const double sigma = fqo_e4m3_decode(gscale[n * (size_t)G + (size_t)g]);
+            for (int c = -8; c <= 7; ++c)
+                table[c + 8] = fqo_e4m3_decode(fqo_e4m3_encode_rne((double)c * sigma));
+            for (int k = 0; k < FQO_GROUP; ++k) {
+                const size_t idx = n * (size_t)K + (size_t)(g * FQO_GROUP + k);
+                Wd[idx] = table[q[idx] + 8];
+            }
+        }
+    }
+    long m;
+#pragma omp parallel for schedule(static)
+    for (m = 0; m < M; ++m) {
+        const double outer = (double)a_scale[m] * (double)w_tscale;
+        for (int n = 0; n < N; ++n) {
+            double y = 0.0;
+            for (int k = 0; k < K; ++k)
+                y += fqo_e4m3_decode(A[(size_t)m * K + k]) * Wd[(size_t)n * K + k];
+            Y[(size_t)m * N + n] = outer * y;
+        }
+    }
+    free(Wd);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------------------
  * The gate/up pair of a feed-forward block with the epilogue fused (Sec. 3.1.1 step 3: the
  * kernel's epilogue applies the nonlinear activation, SiLU, and the element-wise
  * multiplication):
