@@ -406,10 +406,13 @@ __device__ __forceinline__ void fql_item(
     // the other stage.  Units 2c and 2c + 1 of a plane are the two lane halves of MFMA chunk c.
     {
         constexpr int RT = 32 * NMT;                      // rows of the item
+        // (range rounded up to whole words: the array's last word may hold fewer than four scales, and a
+        // word that crosses the end of the range would read as zero; the array is 16-byte aligned, so that
+        // word lies in the same cache line as its valid bytes, and the surplus bytes are cleared below)
         const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint8_t*>(gs), 0, (int)((unsigned)N * (unsigned)G), 0x00020000);
+            const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
         const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : 0xFFFFFF00u;   // channels past N read zeros
-        const bool words = ((G & 3) == 0) && ((reinterpret_cast<uintptr_t>(gs) & 3) == 0);
+        const bool unaligned_rows = (G & 3) != 0;         // (the array itself is 16-byte aligned)
         const int hl = lane >> 5;                         // which half of a chunk's 16 groups this lane holds
         const int rounds = (ZU + 7) >> 3;
         for (int r = 0; r < rounds; ++r) {
@@ -426,17 +429,20 @@ __device__ __forceinline__ void fql_item(
                 const int g0 = 16 * c + 8 * hl;
                 unsigned w[2] = {0u, 0u};
                 if (2 * ci < nu) {
-                    if (words) {
-#pragma unroll
-                        for (int x = 0; x < 2; ++x)
-                            w[x] = __builtin_amdgcn_raw_buffer_load_b32(rsS, g0 + 4 * x < G ? srow : 0xFFFFFF00u, g0 + 4 * x, 0);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) {
-                            const unsigned b = __builtin_amdgcn_raw_buffer_load_b8(rsS, g0 + e < G ? srow : 0xFFFFFF00u, g0 + e, 0);
-                            w[e >> 2] |= (b & 0xFFu) << (8 * (e & 3));
-                        }
-                    }
+                    // The 8 scale bytes of groups g0 .. g0 + 7 start at byte n * G + g0 of the array,
+                    // which is a multiple of 4 only when G is: fetch the aligned words around them
+                    // (out-of-range words read zero) and shift them into place.
+                    const unsigned o = srow + (unsigned)g0;
+                    const unsigned ob = (n_ok && g0 < G) ? (o & ~3u) : 0xFFFFFF00u;
+                    const unsigned d0 = __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 0, 0);
+                    const unsigned d1 = __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 4, 0);
+                    const unsigned d2 = unaligned_rows ? __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 8, 0) : 0u;
+                    w[0] = __builtin_amdgcn_alignbyte(d1, d0, o & 3u);
+                    w[1] = __builtin_amdgcn_alignbyte(d2, d1, o & 3u);
+                    // bytes of groups >= G belong to the next channel: cleared
+                    const int nv = G - g0;                // valid groups from g0 on
+                    if (nv < 4) w[0] &= nv <= 0 ? 0u : (1u << (8 * nv)) - 1u;
+                    if (nv < 8) w[1] &= nv <= 4 ? 0u : (1u << (8 * (nv - 4))) - 1u;
                 }
                 fq_v4i pk;                                // E4M3 -> fp16 is exact, whatever the rounding mode
 #pragma unroll
