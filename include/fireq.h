@@ -8,9 +8,9 @@
  *
  * Conventions for every entry point
  *   - All pointers are DEVICE pointers into memory owned by the caller.  The library
- *     allocates nothing, keeps no state between calls and never synchronises: work is
- *     enqueued on `stream` (a hipStream_t passed as void*; NULL is the default stream) and
- *     the call returns at once.
+ *     allocates nothing, keeps no state between calls and never synchronises (one exception:
+ *     fq_w4a8_gemm, which owns a workspace; see there): work is enqueued on `stream` (a
+ *     hipStream_t passed as void*; NULL is the default stream) and the call returns at once.
  *   - Inputs are never written.  After a non-zero status the outputs are undefined.
  *   - No exception crosses this boundary; every function that can fail returns a status.
  *   - M = 0 (or N = 0 where it is an output width) is a successful no-op.
