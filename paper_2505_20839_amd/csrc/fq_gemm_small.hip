@@ -49,33 +49,38 @@ __device__ __forceinline__ float fq_e4m3_byte_to_float(unsigned w, int i) {
 }
 #define FQ_MFMA16(a, b, c) __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4((a), (b), (c), 0, 0, 0, 0, 0, 0)
 
-// WORDS: every wave's slice starts at a multiple of 4 groups and the scale rows are word-aligned,
-// so four consecutive scale bytes of a channel are one aligned word.
-// A wave keeps a ring of BATCH groups in flight (NSUB * BATCH = 16, 12 or 8 weight chunks per lane):
-// it requests the first BATCH groups of its slice at once and re-requests each slot, for the group
-// BATCH further on, as soon as it has used it.  Loads return in order, so the ring is consumed in
-// the order it was requested.
-template <int NSUB, bool WORDS>
+// The four scale bytes of a channel that go with four consecutive slots are fetched as words.
+// WORDS: every wave's slice starts at a multiple of 4 groups and the scale rows are word-aligned, so
+// they are one aligned word; otherwise the two aligned words around them are fetched and shifted
+// into place when they are used.
+// A wave keeps a ring of BATCH groups in flight (4, 8 or 12: the shortest that holds a wave's slice,
+// at most 48 bytes of packed weights per lane): it requests the first BATCH groups of its slice at
+// once and re-requests each slot, for the group BATCH further on, as soon as it has used it.  Loads
+// return in order, so the ring is consumed in the order it was requested.
+template <int NSUB, bool WORDS, int BATCH_>
 struct fqs16_ring {
-    static constexpr int BATCH = NSUB <= 2 ? 8 : 4;
+    static constexpr int BATCH = BATCH_;
+    static_assert(BATCH % 4 == 0, "scale words cover four slots");
     fq_v4i bq[BATCH][NSUB];
     fq_v4i aq[BATCH][2];
-    unsigned sq[WORDS ? BATCH / 4 : BATCH][NSUB];         // scale bytes, or words of four
+    unsigned sq[BATCH / 4][NSUB][WORDS ? 1 : 2];          // scale words of four slots
 
     // request group g into slot i; groups at or past g_end request nothing and read as zeros
     __device__ __forceinline__ void issue(int i, __amdgpu_buffer_rsrc_t rsA, __amdgpu_buffer_rsrc_t rsW,
                                           __amdgpu_buffer_rsrc_t rsG, unsigned aoff, const unsigned (&woff)[NSUB],
                                           const unsigned (&goff)[NSUB], int g, int g_end) {
         const unsigned dead = g < g_end ? 0u : FQS16_OOB;
-        if (WORDS) {
-            if (i % 4 == 0) {
+        if (i % 4 == 0) {
 #pragma unroll
-                for (int j = 0; j < NSUB; ++j)
-                    sq[i / 4][j] = __builtin_amdgcn_raw_buffer_load_b32(rsG, goff[j] | dead, g, 0);
+            for (int j = 0; j < NSUB; ++j) {
+                if (WORDS) {
+                    sq[i / 4][j][0] = __builtin_amdgcn_raw_buffer_load_b32(rsG, goff[j] | dead, g, 0);
+                } else {
+                    const unsigned base = ((goff[j] + (unsigned)g) & ~3u) | dead;
+                    sq[i / 4][j][0] = __builtin_amdgcn_raw_buffer_load_b32(rsG, base, 0, 0);
+                    sq[i / 4][j][WORDS ? 0 : 1] = __builtin_amdgcn_raw_buffer_load_b32(rsG, base, 4, 0);
+                }
             }
-        } else {
-#pragma unroll
-            for (int j = 0; j < NSUB; ++j) sq[i][j] = __builtin_amdgcn_raw_buffer_load_b8(rsG, goff[j] | dead, g, 0);
         }
         aq[i][0] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, aoff | dead, g * FQ_GROUP, 0));
         aq[i][1] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, (aoff + 16u) | dead, g * FQ_GROUP, 0));
@@ -84,9 +89,16 @@ struct fqs16_ring {
             bq[i][j] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsW, woff[j] | dead, g * 2048, 2));
     }
 
-    // slot i -> accumulators (a dead group is all zeros and adds nothing); `sw` is the slot's scale
-    // word, read before the slot group's first slot may be re-requested
-    __device__ __forceinline__ void compute(int i, fq_v4f (&acc)[NSUB], const unsigned (&sw)[NSUB]) const {
+    // the scale word of slots i .. i + 3 (i a multiple of 4) of sub-tile j, whose first slot holds group g
+    __device__ __forceinline__ unsigned scale_word(int i, int j, unsigned goff_j, int g) const {
+        if (WORDS) return sq[i / 4][j][0];
+        return __builtin_amdgcn_alignbyte(sq[i / 4][j][WORDS ? 0 : 1], sq[i / 4][j][0], (goff_j + (unsigned)g) & 3u);
+    }
+
+    // slot i -> accumulators (a dead group is all zeros and adds nothing: `live` also keeps whatever
+    // byte sits where its scale would be out of the sum); `sw` is the slot's scale word, read before
+    // the slot group's first slot may be re-requested
+    __device__ __forceinline__ void compute(int i, fq_v4f (&acc)[NSUB], const unsigned (&sw)[NSUB], bool live) const {
         const fq_v4f zero4 = {0.f, 0.f, 0.f, 0.f};
         const fq_v8i a = fqs_join(aq[i][0], aq[i][1]);
         fq_v8i zp;
@@ -96,7 +108,8 @@ struct fqs16_ring {
 #pragma unroll
         for (int j = 0; j < NSUB; ++j) {
             const fq_v8i b = fq_unpack_chunk(bq[i][j]);
-            const float s = WORDS ? fq_e4m3_byte_to_float(sw[j], i % 4) : __builtin_amdgcn_cvt_f32_fp8((int)sq[i][j], 0);
+            // (WORDS: a dead slot's word was not fetched at all and reads as zero)
+            const float s = (WORDS || live) ? fq_e4m3_byte_to_float(sw[j], i % 4) : 0.f;
             const fq_v4f p = FQ_MFMA16(a, b, c0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) acc[j][r] = fmaf(s, p[r], acc[j][r]);
@@ -104,13 +117,13 @@ struct fqs16_ring {
     }
 };
 
-template <int NSUB, bool WORDS, bool ROUNDS>
+template <int NSUB, bool WORDS, bool ROUNDS, int BATCH_>
 __global__ __launch_bounds__(FQS16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void fq_gemm_small16_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K, int cols,
     int swiglu, const uint16_t* R) {
-    typedef fqs16_ring<NSUB, WORDS> ring_t;
+    typedef fqs16_ring<NSUB, WORDS, BATCH_> ring_t;
     constexpr int BATCH = ring_t::BATCH;
     __shared__ float red[FQS16_WAVES][NSUB][4][64];
     const int G = K / FQ_GROUP;
@@ -125,8 +138,10 @@ void fq_gemm_small16_kernel(
         const_cast<uint8_t*>(A), 0, (int)((unsigned)M * (unsigned)K), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(wp), 0, (int)((unsigned)((N + 31) >> 5) * (unsigned)G * 2048u), 0x00020000);
+    // (range rounded up to whole words, so that the array's last word is readable when it holds fewer
+    // than four scales; the array is 16-byte aligned and the surplus bytes never enter a sum)
     const __amdgpu_buffer_rsrc_t rsG = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(gs), 0, (int)((unsigned)N * (unsigned)G), 0x00020000);
+        const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
     // per sub-tile: byte offset of this lane's chunk in group 0 of its packed block, and of its scale row
     unsigned woff[NSUB], goff[NSUB];
 #pragma unroll
@@ -163,11 +178,11 @@ void fq_gemm_small16_kernel(
         unsigned sw[NSUB];
 #pragma unroll
         for (int i = 0; i < BATCH; ++i) {
-            if (WORDS && i % 4 == 0) {                    // keep the word: its slot may be re-requested below
+            if (i % 4 == 0) {                             // keep the word: its slot may be re-requested below
 #pragma unroll
-                for (int j = 0; j < NSUB; ++j) sw[j] = ring.sq[i / 4][j];
+                for (int j = 0; j < NSUB; ++j) sw[j] = ring.scale_word(i, j, goff[j], gb + i);
             }
-            ring.compute(i, acc, sw);
+            ring.compute(i, acc, sw, gb + i < g_end);
             __builtin_amdgcn_sched_barrier(0);            // slot by slot, as the data lands
             if (ROUNDS) {
                 ring.issue(i, rsA, rsW, rsG, aoff, woff, goff, gb + BATCH + i, g_end);
@@ -217,23 +232,36 @@ void fq_gemm_small16_kernel(
 
 namespace {
 
-template <int NSUB, bool WORDS>
-void fq_launch_small16w(bool rounds, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
+template <int NSUB, bool WORDS, int BATCH>
+void fq_launch_small16b(bool rounds, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
                         const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
     if (rounds)
-        hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, true>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
+        hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, true, BATCH>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
                            A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
     else
-        hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, false>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
+        hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, false, BATCH>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
                            A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+}
+
+// Ring depth: the shortest of 4, 8, 12 that holds a wave's slice of `per` groups, at most 12 / 8 / 4
+// groups for 1 / 2 / 3-4 sub-tiles (registers); longer slices go round the ring (ROUNDS).
+template <int NSUB, bool WORDS>
+void fq_launch_small16w(int per, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
+                        const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
+    constexpr int CAP = NSUB == 1 ? 12 : (NSUB == 2 ? 8 : 4);
+    if (CAP >= 12 && per > 8)
+        fq_launch_small16b<NSUB, WORDS, CAP >= 12 ? 12 : CAP>(per > 12, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+    else if (CAP >= 8 && per > 4)
+        fq_launch_small16b<NSUB, WORDS, CAP >= 8 ? 8 : CAP>(per > 8, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+    else
+        fq_launch_small16b<NSUB, WORDS, 4>(per > 4, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
 }
 
 template <int NSUB>
 void fq_launch_small16(bool words, int per, unsigned grid, hipStream_t stream, const uint8_t* A, const float* a_scale,
                        const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
-    const bool rounds = per > fqs16_ring<NSUB, true>::BATCH;      // some slice needs the ring more than once
-    if (words) fq_launch_small16w<NSUB, true>(rounds, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
-    else       fq_launch_small16w<NSUB, false>(rounds, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+    if (words) fq_launch_small16w<NSUB, true>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+    else       fq_launch_small16w<NSUB, false>(per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
 }
 
 }  // namespace

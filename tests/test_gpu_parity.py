@@ -140,7 +140,9 @@ def test_quantize_all_finite_bf16_values_and_zero_row(fq):
 # small: besides the basics, the M <= 16 kernel's variants -- byte-wise scales (K/128 = 11), a slice
 # longer than the ring (K = 14336), 2 and 3 sub-tiles of channels per workgroup, a masked last sub-tile
 SMALL_SHAPES = [(16, 256, 512), (1, 32, 128), (33, 100, 384), (64, 96, 1408), (7, 31, 256),
-                (8, 100, 1408), (16, 64, 14336), (16, 4120, 512), (3, 9000, 256), (12, 14336, 384)]
+                (8, 100, 1408), (16, 64, 14336), (16, 4120, 512), (3, 9000, 256), (12, 14336, 384),
+                # ring depths 12 and 8 with and without a second round, scale rows that are not word-aligned
+                (5, 200, 11008), (8, 8192, 5120), (4, 8192, 11008), (16, 300, 1664)]
 # large: ragged M and N, one group only, a second half tile without rows, several zero-point rounds
 LARGE_SHAPES = [(16, 256, 512), (300, 200, 640), (257, 513, 384), (512, 256, 1408), (65, 33, 128),
                 (129, 136, 256), (130, 64, 16384), (700, 1100, 256)]
