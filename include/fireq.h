@@ -148,6 +148,22 @@ int fq_pack_weights(const int8_t *q, uint8_t *Wq_packed, int N, int K, void *str
 int fq_unpack_weights(const uint8_t *Wq_packed, int8_t *q, int N, int K, void *stream);
 
 /*
+ * A whole linear layer from bfloat16 activations: the quantiser of Sec. 2.1 eq. 2 followed by the
+ * GEMM of Sec. 2.2 eq. 3, with the result fq_quantize_act + fq_w4a8_gemm_ws give, bit for bit.
+ * For M <= 6 and K <= 4096 (decode) it is ONE kernel: every workgroup quantises the few rows of
+ * X itself while its weights are on their way, no codes or scales go through memory, and no
+ * workspace is needed.  Otherwise the call runs the quantiser and the GEMM one after the other
+ * and keeps the codes, the row scales and the GEMM's own scratch in `workspace`
+ * (fq_w4a8_linear_workspace_bytes(M,N,K) bytes, 16-byte aligned; FQ_ERR_MEMORY if it is missing
+ * or too small).  X_bf16 [M,K] row-major, finite, 16-byte aligned; the other operands as for
+ * fq_w4a8_gemm_ws.  Allocates nothing, keeps no state, never synchronises.
+ */
+size_t fq_w4a8_linear_workspace_bytes(int M, int N, int K);
+int fq_w4a8_linear_ws(const uint16_t *X_bf16, const uint8_t *Wq_packed, const uint8_t *w_gscale,
+                      float w_tscale, uint16_t *Y_bf16, int M, int N, int K,
+                      void *workspace, size_t workspace_bytes, void *stream);
+
+/*
  * Offline weight quantisation: from a bfloat16 weight matrix W [N,K] (row n = output channel,
  * column k = input channel; Y = X W^T) to the operands of the GEMM.  Typical order:
  * fq_cas_scales, fq_pts_exponent, fq_quantize_weights, fq_pack_weights; the GEMM then takes

@@ -228,6 +228,13 @@ def w4a8_gemm_add(A, a_scale, q, gscale, w_tscale, R_bf16_bits, want_bound: bool
     return (Y, B) if want_bound else Y
 
 
+def w4a8_linear(X_bf16_bits, q, gscale, w_tscale, want_bound: bool = False):
+    """A whole linear layer from bf16 activations: the quantiser of Sec. 2.1 eq. 2 (quantize_act) followed by
+    the GEMM of Sec. 2.2 eq. 3 (w4a8_gemm) -- their composition and nothing else."""
+    A, s = quantize_act(X_bf16_bits)
+    return w4a8_gemm(A, s, q, gscale, w_tscale, want_bound=want_bound)
+
+
 def quantize_act(X_bf16_bits):
     """uint16 [M,K] bf16 bit patterns -> (uint8 [M,K] E4M3 codes, float32 [M] scales)."""
     X = _c(X_bf16_bits, np.uint16)

@@ -54,6 +54,10 @@ def lib() -> ctypes.CDLL:
     L.fq_pack_weights.argtypes = [vp, vp, ci, ci, vp]
     L.fq_unpack_weights.restype = ci
     L.fq_unpack_weights.argtypes = [vp, vp, ci, ci, vp]
+    L.fq_w4a8_linear_workspace_bytes.restype = ctypes.c_size_t
+    L.fq_w4a8_linear_workspace_bytes.argtypes = [ci, ci, ci]
+    L.fq_w4a8_linear_ws.restype = ci
+    L.fq_w4a8_linear_ws.argtypes = [vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, vp]
     L.fq_cas_scales.restype = ci
     L.fq_cas_scales.argtypes = [vp, cf, vp, ci, ci, vp]
     L.fq_pts_exponent.restype = ci
@@ -287,6 +291,37 @@ def fq_w4a8_gemm_add(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Te
                                    1 if (workspace_prepared and workspace is not None) else 0, _stream())
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_add_ws")
+    return out
+
+
+def fq_w4a8_linear_workspace_bytes(M: int, N: int, K: int) -> int:
+    return int(lib().fq_w4a8_linear_workspace_bytes(M, N, K))
+
+
+def fq_w4a8_linear(X: torch.Tensor, Wq_packed: torch.Tensor, w_gscale: torch.Tensor, w_tscale: float, N: int,
+                   out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[M,N] (bf16) of a whole linear layer from bf16 activations X[M,K] (quantiser + GEMM; one kernel
+    for M <= 6 and K <= 4096).  Calls fq_w4a8_linear_ws; the workspace is allocated here when not given."""
+    X = _dev(X, torch.bfloat16, "X")
+    Wq_packed = _dev(Wq_packed, torch.uint8, "Wq_packed")
+    w_gscale = _dev(w_gscale, torch.uint8, "w_gscale")
+    M, K = X.shape
+    if K % GROUP or w_gscale.numel() != N * (K // GROUP) or Wq_packed.numel() < fq_packed_weight_bytes(N, K):
+        raise FireqError(-2, "fq_w4a8_linear")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=X.device)
+    else:
+        out = _dev(out, torch.bfloat16, "out")
+        if tuple(out.shape) != (M, N):
+            raise FireqError(-2, "fq_w4a8_linear")
+    need = fq_w4a8_linear_workspace_bytes(M, N, K)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=X.device)
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (0, 0)
+    rc = lib().fq_w4a8_linear_ws(X.data_ptr(), Wq_packed.data_ptr(), w_gscale.data_ptr(), ctypes.c_float(float(w_tscale)),
+                                 out.data_ptr(), M, N, K, ws_ptr, ws_bytes, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_w4a8_linear_ws")
     return out
 
 

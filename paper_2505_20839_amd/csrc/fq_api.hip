@@ -217,6 +217,50 @@ int fq_w4a8_gemm_swiglu_ws(const uint8_t* A_fp8, const float* a_scale, const uin
                    workspace_prepared, true, nullptr, false, stream);
 }
 
+namespace {
+
+inline size_t round16(size_t v) { return (v + 15u) & ~(size_t)15u; }
+
+// one kernel for the whole layer: small M, short K, and no kernel forced from outside
+bool linear_is_fused(int M, int K) {
+    const GemmKernel k = forced_kernel();
+    return (k == GemmKernel::Auto || k == GemmKernel::Small) && fq_linear_small_serves(M, K);
+}
+
+}  // namespace
+
+size_t fq_w4a8_linear_workspace_bytes(int M, int N, int K) {
+    if (M <= 0 || N <= 0 || K <= 0 || (K % FQ_GROUP) != 0) return 0;
+    if (linear_is_fused(M, K)) return 0;
+    return round16((size_t)M * (size_t)K) + round16((size_t)M * sizeof(float)) + fq_w4a8_gemm_workspace_bytes(M, N, K);
+}
+
+int fq_w4a8_linear_ws(const uint16_t* X_bf16, const uint8_t* Wq_packed, const uint8_t* w_gscale, float w_tscale,
+                      uint16_t* Y_bf16, int M, int N, int K, void* workspace, size_t workspace_bytes, void* stream) {
+    // the GEMM's checks, with X in the place of the codes (same alignment rule, twice the bytes)
+    const int rc = check_gemm_args(X_bf16, X_bf16, Wq_packed, w_gscale, Y_bf16, M, N, K);
+    if (rc != FQ_OK || M == 0) return rc;
+    if ((unsigned long long)M * (unsigned long long)K * 2ull >= 0xFFFFFF00ull) return FQ_ERR_SHAPE;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (linear_is_fused(M, K)) {
+        if (fq_launch_linear_small(X_bf16, nullptr, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, s)) return after_launch();
+        return FQ_ERR_LAUNCH;                             // (the predicate and the launcher agree; not reached)
+    }
+    const size_t need = fq_w4a8_linear_workspace_bytes(M, N, K);
+    if (!workspace || workspace_bytes < need) return FQ_ERR_MEMORY;
+    if (!aligned16(workspace)) return FQ_ERR_ALIGN;
+    uint8_t* A = static_cast<uint8_t*>(workspace);
+    float* a_scale = reinterpret_cast<float*>(A + round16((size_t)M * (size_t)K));
+    uint8_t* gemm_ws = reinterpret_cast<uint8_t*>(a_scale) + round16((size_t)M * sizeof(float));
+    const size_t gemm_ws_bytes = fq_w4a8_gemm_workspace_bytes(M, N, K);
+    int q;
+    if (gemm_ws_bytes > 0) q = fq_quantize_act_ws(X_bf16, A, a_scale, M, K, gemm_ws, gemm_ws_bytes, stream);
+    else                   q = fq_quantize_act(X_bf16, A, a_scale, M, K, stream);
+    if (q != FQ_OK) return q;
+    return fq_w4a8_gemm_ws(A, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, gemm_ws, gemm_ws_bytes,
+                           gemm_ws_bytes > 0 ? 1 : 0, stream);
+}
+
 int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
                  const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
                  int M, int N, int K, void* stream) {

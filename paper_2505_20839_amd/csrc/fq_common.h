@@ -88,6 +88,47 @@ __device__ __forceinline__ float fq_silu_mul(float g, float u) {
     return g * __builtin_amdgcn_rcpf(1.0f + __expf(-g)) * u;
 }
 
+// ---- activation quantisation (Sec. 2.1 eq. 2), shared by the quantiser kernel and the fused linear ----
+// The two bf16 halves of a word as floats.
+__device__ __forceinline__ float fq_bf16_hi(unsigned w) { return __uint_as_float(w & 0xFFFF0000u); }
+__device__ __forceinline__ float fq_bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
+
+// x / s.  FAST: from rcp = 1 / s with one exact residual step; the E4M3 code of the result equals that
+// of the IEEE quotient for every finite bf16 x with |x| <= 448 * s and s in [2^-60, 2^60] (checked
+// exhaustively by a host program); otherwise the full division.  FAST is a template argument so that
+// the choice is made once per row (fq_scale_is_fast), not per element.
+template <bool FAST>
+__device__ __forceinline__ float fq_quotient(float x, float s, float rcp) {
+    if (!FAST) return x / s;
+    const float q = x * rcp;
+    const float e = fmaf(-q, s, x);
+    return copysignf(fmaf(e, rcp, q), x);
+}
+
+__device__ __forceinline__ bool fq_scale_is_fast(float s) { return s >= 0x1p-60f && s <= 0x1p60f; }
+
+// Four quotients -> four E4M3 codes (nearest even, saturating at +-448 instead of becoming NaN).
+template <bool FAST>
+__device__ __forceinline__ unsigned fq_quant4(float a, float b, float c, float d, float s, float rcp) {
+    a = fminf(fmaxf(fq_quotient<FAST>(a, s, rcp), -448.f), 448.f);
+    b = fminf(fmaxf(fq_quotient<FAST>(b, s, rcp), -448.f), 448.f);
+    c = fminf(fmaxf(fq_quotient<FAST>(c, s, rcp), -448.f), 448.f);
+    d = fminf(fmaxf(fq_quotient<FAST>(d, s, rcp), -448.f), 448.f);
+    int r = 0;
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, r, false);
+    r = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, r, true);
+    return (unsigned)r;
+}
+
+// The eight bf16 of a 16-byte chunk -> eight E4M3 codes.
+template <bool FAST>
+__device__ __forceinline__ fq_v2i fq_quant8(fq_v4i v, float s, float rcp) {
+    fq_v2i o;
+    o[0] = (int)fq_quant4<FAST>(fq_bf16_lo(v[0]), fq_bf16_hi(v[0]), fq_bf16_lo(v[1]), fq_bf16_hi(v[1]), s, rcp);
+    o[1] = (int)fq_quant4<FAST>(fq_bf16_lo(v[2]), fq_bf16_hi(v[2]), fq_bf16_lo(v[3]), fq_bf16_hi(v[3]), s, rcp);
+    return o;
+}
+
 // float -> bf16 bits, round to nearest even (finite or infinite input; NaN not expected).
 __device__ __forceinline__ unsigned fq_float_to_bf16(float f) {
     unsigned u = __float_as_uint(f);

@@ -10,6 +10,7 @@
 // overall and every activation byte once per workgroup; the partial sums of the waves are added
 // through LDS.  Activations are tiny (M x K bytes) and come straight from L2 in MFMA operand order.
 #include <cstdlib>
+#include <type_traits>
 #include "fq_common.h"
 #include "fq_kernels.h"
 
@@ -41,6 +42,7 @@ __device__ __forceinline__ fq_v8i fqs_join(fq_v4i lo, fq_v4i hi) {
 // ---------------------------------------------------------------------------------------------
 #define FQS16_THREADS 512
 #define FQS16_WAVES 8
+#define FQS16_FUSED_MAX_M 6                               // rows up to which quantising inside the GEMM kernel pays (<= waves)
 #define FQS16_OOB 0xFFFFFF00u                             // beyond any 32-bit buffer size
 // byte `i` (0..3, compile-time) of a word of E4M3 codes -> float
 __device__ __forceinline__ float fq_e4m3_byte_to_float(unsigned w, int i) {
@@ -66,6 +68,8 @@ struct fqs16_ring {
     unsigned sq[BATCH / 4][NSUB][WORDS ? 1 : 2];          // scale words of four slots
 
     // request group g into slot i; groups at or past g_end request nothing and read as zeros
+    // (LOAD_A = false: the activations of the slot come from elsewhere)
+    template <bool LOAD_A = true>
     __device__ __forceinline__ void issue(int i, __amdgpu_buffer_rsrc_t rsA, __amdgpu_buffer_rsrc_t rsW,
                                           __amdgpu_buffer_rsrc_t rsG, unsigned aoff, const unsigned (&woff)[NSUB],
                                           const unsigned (&goff)[NSUB], int g, int g_end) {
@@ -82,8 +86,10 @@ struct fqs16_ring {
                 }
             }
         }
-        aq[i][0] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, aoff | dead, g * FQ_GROUP, 0));
-        aq[i][1] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, (aoff + 16u) | dead, g * FQ_GROUP, 0));
+        if (LOAD_A) {
+            aq[i][0] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, aoff | dead, g * FQ_GROUP, 0));
+            aq[i][1] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, (aoff + 16u) | dead, g * FQ_GROUP, 0));
+        }
 #pragma unroll
         for (int j = 0; j < NSUB; ++j)                    // streamed once: non-temporal
             bq[i][j] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsW, woff[j] | dead, g * 2048, 2));
@@ -117,12 +123,23 @@ struct fqs16_ring {
     }
 };
 
-template <int NSUB, bool WORDS, bool ROUNDS, int BATCH_>
+// FUSEDQ (M <= 6, K <= 4096): `A` holds the bf16 activations X [M,K] instead of E4M3 codes, and the
+// kernel quantises them itself (Sec. 2.1 eq. 2, the arithmetic of the quantiser kernel): wave w reads
+// row w of X whole (coalesced 16-byte loads into registers), takes its maximum, converts it and
+// leaves the codes in LDS ([M rows][K + 16 bytes]: the pad spreads the rows over the banks); after one
+// barrier every wave fetches the operands of its K slice from there.  All of that happens while the
+// weights are on their way.  Every workgroup repeats it for all of X, which for a few rows costs
+// less than a second kernel (measured at N = 14336, K = 4096: 8.4 against 10.0 us at M = 1, 8.8 against
+// 10.1 at M = 4, 10.5 against 10.3 at M = 8: the conversion is some ten instructions per element, on
+// every compute unit).  `a_scale` is not read;
+// `a_scale_out` (may be NULL) receives the row scales.  Dynamic LDS: 8 * (K + 16) bytes.
+template <int NSUB, bool WORDS, bool ROUNDS, int BATCH_, bool FUSEDQ = false>
 __global__ __launch_bounds__(FQS16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void fq_gemm_small16_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K, int cols,
-    int swiglu, const uint16_t* R) {
+    int swiglu, const uint16_t* R, float* __restrict__ a_scale_out) {
+    static_assert(!(FUSEDQ && ROUNDS), "the fused form serves K <= 4096: a slice is at most four groups");
     typedef fqs16_ring<NSUB, WORDS, BATCH_> ring_t;
     constexpr int BATCH = ring_t::BATCH;
     __shared__ float red[FQS16_WAVES][NSUB][4][64];
@@ -135,7 +152,7 @@ void fq_gemm_small16_kernel(
     const int g_end = (g_begin + per < G) ? g_begin + per : G;
 
     const __amdgpu_buffer_rsrc_t rsA = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint8_t*>(A), 0, (int)((unsigned)M * (unsigned)K), 0x00020000);
+        const_cast<uint8_t*>(A), 0, (int)((unsigned)M * (unsigned)K * (FUSEDQ ? 2u : 1u)), 0x00020000);
     const __amdgpu_buffer_rsrc_t rsW = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(wp), 0, (int)((unsigned)((N + 31) >> 5) * (unsigned)G * 2048u), 0x00020000);
     // (range rounded up to whole words, so that the array's last word is readable when it holds fewer
@@ -158,11 +175,13 @@ void fq_gemm_small16_kernel(
     // output factor of the (at most two) elements this thread writes at the end, fetched up front
     constexpr int NOUT = (NSUB * 256 + FQS16_THREADS - 1) / FQS16_THREADS;
     float osc[NOUT];
+    if (!FUSEDQ) {
 #pragma unroll
-    for (int i = 0; i < NOUT; ++i) {
-        const int idx = threadIdx.x + i * FQS16_THREADS;
-        const int m = 4 * ((idx & 63) >> 4) + ((idx >> 6) & 3);
-        osc[i] = a_scale[m < M ? m : M - 1];
+        for (int i = 0; i < NOUT; ++i) {
+            const int idx = threadIdx.x + i * FQS16_THREADS;
+            const int m = 4 * ((idx & 63) >> 4) + ((idx >> 6) & 3);
+            osc[i] = a_scale[m < M ? m : M - 1];
+        }
     }
 
     fq_v4f acc[NSUB];
@@ -170,9 +189,75 @@ void fq_gemm_small16_kernel(
     for (int j = 0; j < NSUB; ++j) acc[j] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
 
     ring_t ring;
+    extern __shared__ __attribute__((aligned(16))) uint8_t codes[];   // FUSEDQ: [8][K + 16] E4M3 codes
+    __shared__ float srow[FQS16_WAVES];                   // FUSEDQ: row scales
+    constexpr int XCH = 8;                                // 16-byte chunks of a row per lane: K <= 4096
+    fq_v4i xr[FUSEDQ ? XCH : 1];
+    const bool my_row = FUSEDQ && wave < M;               // wave w quantises row w (M <= 6 < number of waves)
+    if (FUSEDQ) {                                         // first in the queue: they are needed first
 #pragma unroll
-    for (int i = 0; i < BATCH; ++i) ring.issue(i, rsA, rsW, rsG, aoff, woff, goff, g_begin + i, g_end);
+        for (int c = 0; c < XCH; ++c) {
+            const int chunk = lane + 64 * c;
+            const unsigned off = (my_row && chunk < (K >> 3)) ? ((unsigned)wave * (unsigned)K * 2u + (unsigned)chunk * 16u) : FQS16_OOB;
+            xr[c] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsA, off, 0, 0));
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < BATCH; ++i) ring.template issue<!FUSEDQ>(i, rsA, rsW, rsG, aoff, woff, goff, g_begin + i, g_end);
     __builtin_amdgcn_sched_barrier(0);                    // all requests go out before any arithmetic
+    if (FUSEDQ) {
+        const int stride = K + 16;
+        if (my_row) {
+            float amax = 0.f;
+#pragma unroll
+            for (int c = 0; c < XCH; ++c)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const unsigned w = (unsigned)xr[c][e];
+                    amax = fmaxf(amax, fmaxf(fabsf(fq_bf16_lo(w)), fabsf(fq_bf16_hi(w))));
+                }
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) amax = fmaxf(amax, __shfl_xor(amax, o, 64));
+            const float s = amax == 0.f ? 1.0f : amax / 448.0f;   // the quantiser's scale (an all-zero row: 1)
+            const float rcp = 1.0f / s;
+            if (lane == 0) {
+                srow[wave] = s;
+                if (a_scale_out != nullptr && blockIdx.x == 0) a_scale_out[wave] = s;
+            }
+            // one choice of quotient per row (s is the same in every lane), then straight-line code
+            auto convert = [&](auto fast_tag) __attribute__((always_inline)) {
+                constexpr bool FAST = decltype(fast_tag)::value;
+#pragma unroll
+                for (int c = 0; c < XCH; ++c) {
+                    const int chunk = lane + 64 * c;
+                    if (chunk < (K >> 3))
+                        *reinterpret_cast<fq_v2i*>(codes + wave * stride + chunk * 8) = fq_quant8<FAST>(xr[c], s, rcp);
+                }
+            };
+            if (__builtin_amdgcn_readfirstlane((int)fq_scale_is_fast(s))) convert(std::true_type());
+            else convert(std::false_type());
+        }
+        __syncthreads();
+        // operands of this wave's slice: row r16 (rows past M repeat the last one, as the unfused form does)
+        const uint8_t* arow = codes + (r16 < M ? r16 : M - 1) * stride + kq * 32;
+#pragma unroll
+        for (int i = 0; i < BATCH; ++i) {
+            const int g = g_begin + i;
+            if (g < g_end) {
+                ring.aq[i][0] = *reinterpret_cast<const fq_v4i*>(arow + g * FQ_GROUP);
+                ring.aq[i][1] = *reinterpret_cast<const fq_v4i*>(arow + g * FQ_GROUP + 16);
+            } else {
+                ring.aq[i][0] = ring.aq[i][1] = (fq_v4i){0, 0, 0, 0};
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < NOUT; ++i) {
+            const int idx = threadIdx.x + i * FQS16_THREADS;
+            const int m = 4 * ((idx & 63) >> 4) + ((idx >> 6) & 3);
+            osc[i] = srow[m < M ? m : M - 1];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
     // ROUNDS == false: no slice is longer than BATCH groups, the ring is used once and never refilled
     for (int gb = g_begin; gb < g_end; gb += BATCH) {
         unsigned sw[NSUB];
@@ -237,10 +322,29 @@ void fq_launch_small16b(bool rounds, unsigned grid, hipStream_t stream, const ui
                         const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols, int swiglu, const uint16_t* R) {
     if (rounds)
         hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, true, BATCH>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
-                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R, static_cast<float*>(nullptr));
     else
         hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, false, BATCH>), dim3(grid), dim3(FQS16_THREADS), 0, stream,
-                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R);
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R, static_cast<float*>(nullptr));
+}
+
+// The fused form (bf16 activations in, quantised by the kernel): slices of at most four groups per wave
+// (K <= 4096), for which a slice of X fits into registers beside the ring.
+template <int NSUB, bool WORDS>
+bool fq_launch_linear16w(int per, unsigned grid, hipStream_t stream, const uint16_t* X, float* a_scale_out,
+                         const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols) {
+    if (per > 4) return false;
+    const size_t lds = (size_t)8 * (size_t)(K + 16);      // the codes of X
+    static bool attr_set = false;
+    if (!attr_set) {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_small16_kernel<NSUB, WORDS, false, 4, true>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 8 * (4096 + 16));
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, false, 4, true>), dim3(grid), dim3(FQS16_THREADS), lds, stream,
+                       reinterpret_cast<const uint8_t*>(X), static_cast<const float*>(nullptr), wp, gs, tscale, Y, M, N, K, cols,
+                       0, static_cast<const uint16_t*>(nullptr), a_scale_out);
+    return true;
 }
 
 // Ring depth: the shortest of 4, 8, 12 that holds a wave's slice of `per` groups, at most 12 / 8 / 4
@@ -281,6 +385,8 @@ struct fqsm_ring {
     fq_v4i aq[BATCH][MT][2];
 
     // request group g into slot i; groups at or past g_end request nothing and read as zeros
+    // (LOAD_A = false: the activations of the slot come from elsewhere)
+    template <bool LOAD_A = true>
     __device__ __forceinline__ void issue(int i, __amdgpu_buffer_rsrc_t rsA, __amdgpu_buffer_rsrc_t rsW,
                                           const unsigned (&aoff)[MT], const unsigned (&woff)[NSUB], int g, int g_end) {
         const unsigned dead = g < g_end ? 0u : FQS16_OOB;
@@ -504,10 +610,19 @@ bool fq_launch_smallm_mt(int nsub, int per, unsigned grid, hipStream_t stream, c
 
 }  // namespace
 
-bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
-                          float tscale, uint16_t* Y, int M, int N, int K, bool swiglu_epilogue, const uint16_t* R, hipStream_t stream) {
-    const int swiglu = swiglu_epilogue ? 1 : 0;
-    // channels per workgroup: an even share of N over the compute units, a multiple of 8, at most 64
+namespace {
+
+// How a small-M problem is cut up: channels per workgroup (an even share of N over the compute units,
+// a multiple of 8, at most 64), workgroups, groups per wave, sub-tiles of 16 channels, and whether the
+// scale bytes of four consecutive groups are one aligned word.
+struct fqs_shape {
+    int cols;
+    unsigned grid;
+    int per, nsub;
+    bool words;
+};
+
+fqs_shape fqs_shape_of(int N, int K, const uint8_t* gs) {
     static int cus = 0;
     if (cus == 0) {
         int dev = 0, v = 0;
@@ -515,12 +630,47 @@ bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t*
             hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
         else cus = 256;
     }
-    int cols = ((N + cus - 1) / cus + 7) & ~7;
-    cols = cols < 8 ? 8 : (cols > 64 ? 64 : cols);
-    const unsigned grid = (unsigned)((N + cols - 1) / cols);
-    const int G = K / FQ_GROUP, per = (G + FQS16_WAVES - 1) / FQS16_WAVES, nsub = (cols + 15) / 16;
+    fqs_shape sh;
+    sh.cols = ((N + cus - 1) / cus + 7) & ~7;
+    sh.cols = sh.cols < 8 ? 8 : (sh.cols > 64 ? 64 : sh.cols);
+    sh.grid = (unsigned)((N + sh.cols - 1) / sh.cols);
+    const int G = K / FQ_GROUP;
+    sh.per = (G + FQS16_WAVES - 1) / FQS16_WAVES;
+    sh.nsub = (sh.cols + 15) / 16;
+    sh.words = (sh.per % 4 == 0) && (G % 4 == 0) && ((reinterpret_cast<uintptr_t>(gs) & 3) == 0);
+    return sh;
+}
+
+}  // namespace
+
+bool fq_linear_small_serves(int M, int K) {
+    return M >= 1 && M <= FQS16_FUSED_MAX_M && (K / FQ_GROUP + FQS16_WAVES - 1) / FQS16_WAVES <= 4;
+}
+
+bool fq_launch_linear_small(const uint16_t* X, float* a_scale_out, const uint8_t* wp, const uint8_t* gs, float tscale,
+                            uint16_t* Y, int M, int N, int K, hipStream_t stream) {
+    if (!fq_linear_small_serves(M, K)) return false;
+    const fqs_shape sh = fqs_shape_of(N, K, gs);
+    switch (2 * sh.nsub + (sh.words ? 1 : 0)) {
+        case 2: return fq_launch_linear16w<1, false>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+        case 3: return fq_launch_linear16w<1, true>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+        case 4: return fq_launch_linear16w<2, false>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+        case 5: return fq_launch_linear16w<2, true>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+        case 6: return fq_launch_linear16w<3, false>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+        case 7: return fq_launch_linear16w<3, true>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+        case 8: return fq_launch_linear16w<4, false>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+        default: return fq_launch_linear16w<4, true>(sh.per, sh.grid, stream, X, a_scale_out, wp, gs, tscale, Y, M, N, K, sh.cols);
+    }
+}
+
+bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                          float tscale, uint16_t* Y, int M, int N, int K, bool swiglu_epilogue, const uint16_t* R, hipStream_t stream) {
+    const int swiglu = swiglu_epilogue ? 1 : 0;
+    const fqs_shape sh = fqs_shape_of(N, K, gs);
+    const int cols = sh.cols, per = sh.per, nsub = sh.nsub;
+    const unsigned grid = sh.grid;
     if (M <= 16) {
-        const bool words = (per % 4 == 0) && (G % 4 == 0) && ((reinterpret_cast<uintptr_t>(gs) & 3) == 0);
+        const bool words = sh.words;
         switch (nsub) {
             case 1: fq_launch_small16<1>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R); break;
             case 2: fq_launch_small16<2>(words, per, grid, stream, A, a_scale, wp, gs, tscale, Y, M, N, K, cols, swiglu, R); break;

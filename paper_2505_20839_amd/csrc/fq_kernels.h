@@ -34,6 +34,11 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
 bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, const uint16_t* R,
                            hipStream_t stream);
+// M <= 16: quantiser and GEMM in one kernel, from bf16 activations X [M,K]; a_scale_out (may be NULL) receives
+// the row scales.  Serves M <= 6 with K <= 4096 (fq_linear_small_serves); returns false (nothing enqueued) otherwise.
+bool fq_linear_small_serves(int M, int K);
+bool fq_launch_linear_small(const uint16_t* X, float* a_scale_out, const uint8_t* wp, const uint8_t* gs, float tscale,
+                            uint16_t* Y, int M, int N, int K, hipStream_t stream);
 
 // Offline weight quantisation (fq_wquant.hip).  W is [N,K] bf16; lambda (may be NULL) is [K] FP32.
 void fq_launch_cas_scales(const uint16_t* W, float target, float* lambda, int N, int K, hipStream_t stream);

@@ -9,14 +9,12 @@
 // [2^-60, 2^60]: checked exhaustively on the host (5.3e8 pairs; the few quotients that differ in
 // their last bit all come from subnormal x and round to zero).  Rows with beta outside that range
 // take the full division.
+#include <type_traits>
 #include "fq_common.h"
 #include "fq_kernels.h"
 
 #define FQ_Q_THREADS 256
 #define FQ_Q_MAXCHUNK 8        // 16-byte chunks (8 bf16) a thread keeps in registers: K <= 16384
-
-__device__ __forceinline__ float fq_bf16_hi(unsigned w) { return __uint_as_float(w & 0xFFFF0000u); }
-__device__ __forceinline__ float fq_bf16_lo(unsigned w) { return __uint_as_float(w << 16); }
 
 __device__ __forceinline__ float fq_block_max(float v, float* red) {
 #pragma unroll
@@ -28,24 +26,6 @@ __device__ __forceinline__ float fq_block_max(float v, float* red) {
 #pragma unroll
     for (int i = 1; i < FQ_Q_THREADS / 64; ++i) r = fmaxf(r, red[i]);
     return r;
-}
-
-__device__ __forceinline__ float fq_quotient(float x, float s, float rcp, bool fast) {
-    if (!fast) return x / s;
-    const float q = x * rcp;
-    const float e = fmaf(-q, s, x);
-    return copysignf(fmaf(e, rcp, q), x);
-}
-
-__device__ __forceinline__ unsigned fq_quant4(float a, float b, float c, float d, float s, float rcp, bool fast) {
-    a = fminf(fmaxf(fq_quotient(a, s, rcp, fast), -448.f), 448.f);
-    b = fminf(fmaxf(fq_quotient(b, s, rcp, fast), -448.f), 448.f);
-    c = fminf(fmaxf(fq_quotient(c, s, rcp, fast), -448.f), 448.f);
-    d = fminf(fmaxf(fq_quotient(d, s, rcp, fast), -448.f), 448.f);
-    int r = 0;
-    r = __builtin_amdgcn_cvt_pk_fp8_f32(a, b, r, false);
-    r = __builtin_amdgcn_cvt_pk_fp8_f32(c, d, r, true);
-    return (unsigned)r;
 }
 
 // Sum of the eight E4M3 values of two words of codes.
@@ -102,17 +82,17 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
     amax = fq_block_max(amax, red);
     const float s = (amax == 0.f) ? 1.0f : amax / 448.0f;
     if (threadIdx.x == 0) a_scale[m] = s;
-    const bool fast = s >= 0x1p-60f && s <= 0x1p60f;      // the range the short quotient was checked on
     const float rcp = 1.0f / s;
+    // One choice of quotient per row (s is the same in every thread of the workgroup): the range the
+    // short quotient was checked on, else the full division; straight-line code either way.
+    auto convert = [&](auto fast_tag) __attribute__((always_inline)) {
+    constexpr bool FAST = decltype(fast_tag)::value;
     if (in_regs) {
 #pragma unroll
         for (int i = 0; i < FQ_Q_MAXCHUNK; ++i) {
             int c = threadIdx.x + i * FQ_Q_THREADS;
             if (c < nchunk) {
-                fq_v4i v = keep[i];
-                fq_v2i o;
-                o[0] = (int)fq_quant4(fq_bf16_lo(v[0]), fq_bf16_hi(v[0]), fq_bf16_lo(v[1]), fq_bf16_hi(v[1]), s, rcp, fast);
-                o[1] = (int)fq_quant4(fq_bf16_lo(v[2]), fq_bf16_hi(v[2]), fq_bf16_lo(v[3]), fq_bf16_hi(v[3]), s, rcp, fast);
+                const fq_v2i o = fq_quant8<FAST>(keep[i], s, rcp);
                 a[c] = o;
                 if (ZP) {
                     // a group is 16 consecutive chunks = 16 consecutive lanes (nchunk is a multiple of 16,
@@ -144,14 +124,11 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
             }
         }
     } else {
-        for (int c = threadIdx.x; c < nchunk; c += FQ_Q_THREADS) {
-            fq_v4i v = x[c];
-            fq_v2i o;
-            o[0] = (int)fq_quant4(fq_bf16_lo(v[0]), fq_bf16_hi(v[0]), fq_bf16_lo(v[1]), fq_bf16_hi(v[1]), s, rcp, fast);
-            o[1] = (int)fq_quant4(fq_bf16_lo(v[2]), fq_bf16_hi(v[2]), fq_bf16_lo(v[3]), fq_bf16_hi(v[3]), s, rcp, fast);
-            a[c] = o;
-        }
+        for (int c = threadIdx.x; c < nchunk; c += FQ_Q_THREADS) a[c] = fq_quant8<FAST>(x[c], s, rcp);
     }
+    };
+    if (__builtin_amdgcn_readfirstlane((int)fq_scale_is_fast(s))) convert(std::true_type());
+    else convert(std::false_type());
 }
 
 void fq_launch_quantize(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, hipStream_t stream) {

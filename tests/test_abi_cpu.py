@@ -22,7 +22,8 @@ def test_library_exports_every_declared_symbol():
     names = _declared_functions()
     assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_swiglu_ws", "fq_w4a8_gemm_add_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_quantize_act_ws", "fq_packed_weight_bytes", "fq_pack_weights",
                             "fq_unpack_weights", "fq_layout_version", "fq_status_string",
-                            "fq_cas_scales", "fq_pts_exponent", "fq_quantize_weights"])
+                            "fq_cas_scales", "fq_pts_exponent", "fq_quantize_weights",
+                            "fq_w4a8_linear_ws", "fq_w4a8_linear_workspace_bytes"])
     for name in names:
         assert hasattr(L, name), name
     assert os.path.samefile(L._name, build.LIB_PATH)
@@ -98,6 +99,19 @@ def test_bad_arguments_are_rejected_without_a_launch():
     assert L.fq_quantize_act(p, p, p, 0, 128, null) == 0
     assert L.fq_quantize_act(null, p, p, 4, 128, null) == -1
     assert L.fq_quantize_act(p, odd, p, 4, 128, null) == -3
+    # the whole layer from bf16 activations: no workspace for the one-kernel case, else codes + scales + GEMM scratch
+    assert L.fq_w4a8_linear_workspace_bytes(6, 256, 4096) == 0
+    assert L.fq_w4a8_linear_workspace_bytes(7, 256, 4096) == 7 * 4096 + 32
+    assert L.fq_w4a8_linear_workspace_bytes(16, 256, 8192) == 16 * 8192 + 64
+    assert L.fq_w4a8_linear_workspace_bytes(17, 256, 512) == 17 * 512 + 80
+    assert L.fq_w4a8_linear_workspace_bytes(100, 256, 512) == 100 * 512 + 400 + L.fq_w4a8_gemm_workspace_bytes(100, 256, 512)
+    lin = (ctypes.c_size_t(1 << 30), null)
+    assert L.fq_w4a8_linear_ws(p, p, p, f1, p, 4, 32, 100, p, *lin) == -2
+    assert L.fq_w4a8_linear_ws(null, p, p, f1, p, 4, 32, 128, p, *lin) == -1
+    assert L.fq_w4a8_linear_ws(odd, p, p, f1, p, 4, 32, 128, p, *lin) == -3
+    assert L.fq_w4a8_linear_ws(p, p, p, f1, p, 100, 32, 128, null, ctypes.c_size_t(0), null) == -5
+    assert L.fq_w4a8_linear_ws(p, p, p, f1, p, 100, 32, 128, p, ctypes.c_size_t(64), null) == -5
+    assert L.fq_w4a8_linear_ws(null, null, null, f1, null, 0, 32, 128, null, ctypes.c_size_t(0), null) == 0
     # offline weight quantiser
     assert L.fq_cas_scales(p, f1, p, 0, 128, null) == -2
     assert L.fq_cas_scales(p, ctypes.c_float(0.0), p, 4, 128, null) == -2

@@ -528,3 +528,53 @@ def test_ws_entry_points_replay_in_a_hip_graph(fq):
     # and the last replay against the oracle
     Yr, B = oracle.w4a8_gemm(A.cpu().numpy(), s.cpu().numpy(), d["q"], d["gscale"], d["w_tscale"], want_bound=True)
     check_gemm(got[0], Yr, B, "graph replay")
+
+
+# ---- the whole layer from bf16 activations (one kernel for M <= 6, K <= 4096) -------------------
+
+LINEAR_SHAPES = [(6, 256, 512), (1, 32, 128), (5, 100, 384), (6, 4120, 512), (6, 8192, 4096), (4, 4096, 4096),
+                 (3, 9000, 256), (6, 14336, 4096), (1, 14336, 4096), (5, 300, 1408), (2, 6144, 3072), (7, 100, 384),
+                 # not served by the one-kernel form: long K, more rows, the large-M kernel
+                 (16, 200, 8192), (40, 96, 1408), (300, 256, 1024)]
+
+
+@pytest.mark.parametrize("shape", LINEAR_SHAPES)
+def test_linear_matches_oracle_and_the_two_step_path(fq, shape):
+    """fq_w4a8_linear against the oracle (quantiser then GEMM), and bit for bit against fq_quantize_act +
+    fq_w4a8_gemm on the GPU: the fused kernel must quantise exactly as the quantiser kernel does."""
+    M, N, K = shape
+    d = workloads.draw(M, N, K, seed=7 * M + N + K, outlier_frac=0.01)
+    if M > 2:
+        d["X_bf16"][1, :] = 0                                  # an all-zero row takes scale 1
+    X = to_gpu_bf16(d["X_bf16"])
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    gs = _gpu(d["gscale"])
+    need = fq.fq_w4a8_linear_workspace_bytes(M, N, K)
+    assert (need == 0) == (M <= 6 and K <= 4096)
+    Yl = fq.fq_w4a8_linear(X, packed, gs, d["w_tscale"], N)
+    A, s = fq.fq_quantize_act(X)
+    Y2 = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits_from_gpu(Yl), bf16_bits_from_gpu(Y2)), "differs from quantiser + GEMM"
+    Yr, B = oracle.w4a8_linear(d["X_bf16"], d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Yl), Yr, B, "linear %s" % (shape,))
+
+
+def test_linear_on_every_bf16_magnitude(fq):
+    """Rows whose maxima span the whole bf16 range (tiny, huge, subnormal neighbours): the fused kernel's
+    codes decide the output, so any difference from the quantiser kernel would show in the comparison."""
+    M, N, K = 6, 64, 512
+    rng = np.random.default_rng(3)
+    X = rng.standard_normal((M, K)).astype(np.float32)
+    X *= (2.0 ** np.array([-126, -70, -10, 0, 60, 126]))[:, None].astype(np.float32)
+    Xb = workloads.f32_to_bf16_bits(X)
+    d = workloads.draw(M, N, K, seed=5)
+    packed = fq.fq_pack_weights(_gpu(d["q"]))
+    gs = _gpu(d["gscale"])
+    Yl = fq.fq_w4a8_linear(to_gpu_bf16(Xb), packed, gs, 1.0, N)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(Xb))
+    Y2 = fq.fq_w4a8_gemm(A, s, packed, gs, 1.0, N)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits_from_gpu(Yl), bf16_bits_from_gpu(Y2))
+    An, sn = oracle.quantize_act(Xb)
+    assert np.array_equal(A.cpu().numpy() & 0x7F, An & 0x7F) and np.array_equal(s.cpu().numpy(), sn)

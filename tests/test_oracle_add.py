@@ -85,3 +85,19 @@ def test_shape_errors():
         oracle.w4a8_gemm_add(A, a, q, gs, 1.0, np.zeros((4, 2), np.uint16))
     with pytest.raises(TypeError):
         oracle.w4a8_gemm_add(A, a, q, gs, 1.0, np.zeros((2, 4), np.float32))
+
+
+def test_linear_is_the_quantiser_followed_by_the_gemm():
+    """oracle.w4a8_linear: hand value (row [2, -1]: beta = 2/448, codes 448 and -224, both weights 1 and the
+    group scale 1 give beta * 224 = 1) and equality with the two pinned functions it chains."""
+    X = np.zeros((1, 128), np.float32); X[0, 0] = 2.0; X[0, 1] = -1.0
+    q = np.zeros((1, 128), np.int8); q[0, 0] = 1; q[0, 1] = 1
+    gs = np.array([[ONE]], np.uint8)
+    Y = oracle.w4a8_linear(_bf16_bits(X), q, gs, 1.0)
+    assert Y.shape == (1, 1) and abs(Y[0, 0] - 1.0) < 1e-7
+    rng = np.random.default_rng(12)
+    Xb = (rng.standard_normal((5, 256)).astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    q = rng.integers(-8, 8, (9, 256), dtype=np.int8)
+    gs = rng.integers(0x10, 0x30, (9, 2)).astype(np.uint8)
+    A, s = oracle.quantize_act(Xb)
+    assert np.array_equal(oracle.w4a8_linear(Xb, q, gs, 0.5), oracle.w4a8_gemm(A, s, q, gs, 0.5))
