@@ -97,8 +97,9 @@ int fq_w4a8_gemm_swiglu_ws(const uint8_t *A_fp8, const float *a_scale, const uin
                            int workspace_prepared, void *stream);
 
 /*
- * The GEMM with the residual stream added in its epilogue (Sec. 3.1.1 step 3, "activation
- * addition"; Fig. 1: after the attention-output and the down projections):
+ * The GEMM with the residual stream added in its epilogue (Sec. 3.1.1 step 3 lists the
+ * addition of activations among the epilogue operations; Fig. 1: after the attention-output and the
+ * down projections):
  *
  *   Y[m,n] = bf16( GEMM[m,n] + R[m,n] ),
  *

@@ -341,8 +341,8 @@ int fqo_w4a8_gemm_swiglu(const uint8_t *A, const float *a_scale, const int8_t *q
 }
 
 /* ---------------------------------------------------------------------------------------
- * The GEMM with the activation addition of the epilogue (Sec. 3.1.1 step 3: "activation
- * addition" is the residual stream added to the output of the attention-output and the
+ * The GEMM with the activation addition of the epilogue (Sec. 3.1.1 step 3 lists the addition
+ * of activations: the residual stream added to the output of the attention-output and the
  * down projections, Fig. 1):
  *
  *   Y[m,n] = GEMM[m,n] + R[m,n],   R [M,N] bf16 bit patterns, row-major.
