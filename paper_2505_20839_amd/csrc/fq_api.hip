@@ -6,6 +6,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 
 namespace {
 
@@ -267,9 +268,13 @@ int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_p
     const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, Y_bf16, M, N, K);
     if (rc != FQ_OK || M == 0) return rc;
     // the library's own workspace: one grow-only device buffer, shared by every call of the process
+    // (the mutex keeps the bookkeeping whole when several host threads call; the kernels of overlapping
+    // calls still share the buffer, as the header says)
+    static std::mutex ws_mutex;
     static void* ws = nullptr;
     static size_t ws_bytes = 0;
     const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
+    std::lock_guard<std::mutex> lock(ws_mutex);
     if (need > ws_bytes) {
         if (ws) (void)hipFree(ws);
         ws = nullptr;
