@@ -8,18 +8,20 @@
 // wave w owns 32 channels and all rows of the tile (NMT = 8 or 4 MFMA tiles of 32x32), so every
 // weight is unpacked exactly once per workgroup and each unpacked operand is reused by all row tiles.
 // Two workgroups share a compute unit (80 KiB of LDS and one wave per SIMD each): the two waves of
-// a SIMD belong to different workgroups, so no barrier couples them, and one workgroup's prologue,
-// epilogue and load stalls are covered by the other's MFMAs.
+// a SIMD belong to different workgroups, so no barrier couples them, and each fills the other's
+// stalls inside the loop (the workgroups of a launch run in step, so their prologues and epilogues
+// mostly coincide).
 // Per 128-wide group g:
 //     P   = A[:, g, first 64] * Wq[g, first 64]            v_mfma_f32_32x32x64_f8f6f4, C = 0
 //     P  += A[:, g, last 64]  * Wq[g, last 64]             same, C = P
 //     acc += e4m3(gscale[n, g]) * P                        16 v_fma_f32 per 32x32 tile
 // The packed codes carry a zero point of 8 (byte c reads as the E4M3 number c * 2^-9), so unpacking
 // is a mask and a shift, and the sum above comes out too large by 2^-6 * gscale[n, g] * sum_k A[m, k]
-// per group.  That excess is a product of a per-(row, group) and a per-(channel, group) factor: a
-// small kernel first writes Z[m, g] = -2^-6 * sum_k A[m, k] (FP32, split into two fp16 terms: 22
-// significant bits), and each tile ends with  acc += Z * gscale^T  as fp16 MFMAs of depth K / 128;
-// the first 16 groups' worth of Z is fetched into the idle A stage during the tile's last group.
+// per group.  That excess is a product of a per-(row, group) and a per-(channel, group) factor: the
+// activation quantiser (or else a small kernel launched first) writes Z[m, g] = -2^-6 * sum_k A[m, k]
+// (FP32, split into two fp16 terms: 22 significant bits), and each tile ends with  acc += Z * gscale^T
+// as fp16 MFMAs of depth K / 128; the first round of Z is fetched into the idle A stage during the
+// tile's last group.
 // A tiles go global -> LDS directly (buffer_load_dwordx4 ... lds, two stages of 32 KiB, one group
 // per barrier); packed weights go global -> LDS the same way (2 x 2 KiB private to each wave) and
 // are unpacked one group ahead, a slice under each MFMA.
@@ -27,9 +29,9 @@
 // Tile order.  Workgroup b runs on XCD b % 8 (round-robin dispatch); each XCD gets a contiguous
 // range of tiles in an order that walks panels of 4 row tiles, row tile fastest, so the workgroups
 // an XCD runs at one time cover a few row tiles x a few channel tiles and share them in its L2.
-// The tiles an XCD cannot fill a whole round of its slots with are cut into two 128-row halves and
-// run by a second launch of the NMT = 4 variant, so that the last round keeps all units busy for
-// half the time.
+// The tiles an XCD cannot fill a whole round of its slots with are cut into two 128-row halves (the
+// NMT = 4 variant, later workgroups of the same launch), so that the last round keeps all units busy
+// for half the time.
 #include <type_traits>
 #include "fq_common.h"
 #include "fq_kernels.h"

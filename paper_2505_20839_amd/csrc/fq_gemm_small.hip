@@ -32,7 +32,7 @@ __device__ __forceinline__ fq_v8i fqs_join(fq_v4i lo, fq_v4i hi) {
 // bytes and the whole matrix is requested at once.  A workgroup of 8 waves covers its channels with
 // NSUB <= 4 sub-tiles of 16 channels (the last one may be partly masked); the waves split K into
 // eight contiguous slices, so each activation byte is read once per workgroup and each weight byte
-// once overall.  A wave requests all packed weights of a batch of four groups before it computes
+// once overall.  A wave requests the packed weights of its first 4, 8 or 12 groups before it computes
 // anything; with K = 4096 that is its whole share.
 // Every load is a raw buffer load: masked lanes carry an out-of-range offset (they fetch nothing
 // and read zero), group steps travel in the scalar offset, and the code has no branches between
