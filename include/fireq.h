@@ -128,8 +128,9 @@ int fq_quantize_act(const uint16_t *X_bf16, uint8_t *A_fp8, float *a_scale,
 /*
  * fq_quantize_act that also prepares the workspace of the GEMM that consumes A_fp8 (see
  * fq_w4a8_gemm_ws: pass workspace_prepared = 1 there).  K must be a multiple of 128 here;
- * `workspace` must hold at least fq_w4a8_gemm_workspace_bytes(M, N, K) bytes for an M > 64
- * (the size does not depend on N), 16-byte aligned; FQ_ERR_MEMORY otherwise.
+ * `workspace` must hold at least fq_w4a8_gemm_workspace_bytes(M, N, K) bytes (the size does not
+ * depend on N), 16-byte aligned; FQ_ERR_MEMORY otherwise.  Where that size is 0 (M <= 64) the call
+ * is fq_quantize_act and `workspace` may be NULL.
  */
 int fq_quantize_act_ws(const uint16_t *X_bf16, uint8_t *A_fp8, float *a_scale, int M, int K,
                        void *workspace, size_t workspace_bytes, void *stream);
@@ -198,6 +199,25 @@ int fq_pts_exponent(const uint16_t *W_bf16, const float *lambda, int *n_out, int
                     void *stream);
 int fq_quantize_weights(const uint16_t *W_bf16, const float *lambda, int n_pts, int sigma_nearest,
                         int8_t *q, uint8_t *w_gscale, int N, int K, void *stream);
+
+/*
+ * Diagnostics (used by the tests; no kernel is launched).
+ *
+ * fq_w4a8_gemm_plan: how fq_w4a8_gemm_ws would run an M x N x K problem on a device with `cus`
+ *   compute units (0 = the current device).  `plan` is HOST memory of 8 ints:
+ *     plan[0]  kernel: 0 one-thread-per-output cross-check kernel, 1 the M <= 16 kernel, 2 the
+ *              M <= 64 kernel, 3 the large-M kernel
+ *     plan[1]  large-M kernel: whole tiles (256 rows x 128 channels) written with whole-row stores
+ *     plan[2]  whole tiles written element by element (a ragged edge, or N not a multiple of 8)
+ *     plan[3], plan[4]  the same two counts for the 128-row half tiles of the last round
+ *     plan[5..7]  0
+ * fq_test_force_kernel: "simple", "small" or "large" makes every GEMM entry point use that kernel
+ *   where it serves the shape; "" or NULL restores the choice by M.  The environment variable
+ *   FQ_FORCE_KERNEL, read once when the library is loaded, sets the initial value.  Process-wide;
+ *   meant for cross-checking the kernels against each other.
+ */
+int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int *plan);
+int fq_test_force_kernel(const char *name);
 
 /* Changes whenever the byte order written by fq_pack_weights changes. */
 int fq_layout_version(void);

@@ -64,6 +64,10 @@ def lib() -> ctypes.CDLL:
     L.fq_pts_exponent.argtypes = [vp, vp, vp, ci, ci, vp]
     L.fq_quantize_weights.restype = ci
     L.fq_quantize_weights.argtypes = [vp, vp, ci, ci, vp, vp, ci, ci, vp]
+    L.fq_w4a8_gemm_plan.restype = ci
+    L.fq_w4a8_gemm_plan.argtypes = [ci, ci, ci, ci, ctypes.POINTER(ctypes.c_int)]
+    L.fq_test_force_kernel.restype = ci
+    L.fq_test_force_kernel.argtypes = [ctypes.c_char_p]
     L.fq_layout_version.restype = ci
     L.fq_layout_version.argtypes = []
     L.fq_status_string.restype = ctypes.c_char_p
@@ -327,3 +331,18 @@ def fq_w4a8_linear(X: torch.Tensor, Wq_packed: torch.Tensor, w_gscale: torch.Ten
 
 def fq_w4a8_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
     return int(lib().fq_w4a8_gemm_workspace_bytes(M, N, K))
+
+
+def fq_w4a8_gemm_plan(M: int, N: int, K: int, cus: int = 0) -> dict:
+    """How the GEMM entry points would run this shape (see fireq.h); cus = 0 asks the current device."""
+    buf = (ctypes.c_int * 8)()
+    rc = lib().fq_w4a8_gemm_plan(int(M), int(N), int(K), int(cus), buf)
+    if rc != 0:
+        raise FireqError(rc, "fq_w4a8_gemm_plan")
+    return {"kernel": ("simple", "small16", "smallm", "large")[buf[0]], "whole": buf[1], "whole_ragged": buf[2],
+            "half": buf[3], "half_ragged": buf[4]}
+
+
+def fq_test_force_kernel(name: Optional[str]) -> None:
+    """Cross-check hook: "simple" | "small" | "large" forces that GEMM kernel, None or "auto" restores the choice by M."""
+    lib().fq_test_force_kernel((name or "").encode() if name != "auto" else b"")

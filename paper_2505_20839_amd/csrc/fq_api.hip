@@ -6,6 +6,7 @@
 
 #include <cstdlib>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 
 namespace {
@@ -17,14 +18,18 @@ inline int after_launch() { return hipGetLastError() == hipSuccess ? FQ_OK : FQ_
 enum class GemmKernel { Auto, Simple, Large, Small };
 
 // FQ_FORCE_KERNEL=simple|large|small overrides the choice (tests use it to cross-check kernels).
-GemmKernel forced_kernel() {
-    const char* e = std::getenv("FQ_FORCE_KERNEL");
+GemmKernel parse_kernel(const char* e) {
     if (!e || !*e) return GemmKernel::Auto;
     if (!std::strcmp(e, "simple")) return GemmKernel::Simple;
     if (!std::strcmp(e, "large")) return GemmKernel::Large;
     if (!std::strcmp(e, "small")) return GemmKernel::Small;
     return GemmKernel::Auto;
 }
+
+// The environment is read when the library is loaded; fq_test_force_kernel changes the choice later.
+std::atomic<int> g_forced{static_cast<int>(parse_kernel(std::getenv("FQ_FORCE_KERNEL")))};
+
+GemmKernel forced_kernel() { return static_cast<GemmKernel>(g_forced.load(std::memory_order_relaxed)); }
 
 // The GEMM kernels address every operand through 32-bit buffer offsets: each of A, the packed
 // weights, the group scales and the workspace must stay below 4 GiB, and a band of 256 output rows too.
@@ -129,6 +134,21 @@ int fq_quantize_weights(const uint16_t* W_bf16, const float* lambda, int n_pts, 
     return after_launch();
 }
 
+int fq_test_force_kernel(const char* name) {
+    g_forced.store(static_cast<int>(parse_kernel(name)), std::memory_order_relaxed);
+    return FQ_OK;
+}
+
+int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int* plan) {
+    if (M <= 0 || N <= 0 || K <= 0 || (K % FQ_GROUP) != 0 || cus < 0) return FQ_ERR_SHAPE;
+    if (!plan) return FQ_ERR_NULL;
+    for (int i = 0; i < 8; ++i) plan[i] = 0;
+    const GemmKernel k = choose_kernel(M);
+    plan[0] = k == GemmKernel::Simple ? 0 : k == GemmKernel::Small ? (M <= 16 ? 1 : 2) : 3;
+    if (k == GemmKernel::Large) fq_gemm_large_plan(M, N, cus > 0 ? cus : fq_device_cus(), plan + 1);
+    return FQ_OK;
+}
+
 size_t fq_w4a8_gemm_workspace_bytes(int M, int N, int K) {
     if (M <= 0 || N <= 0 || K <= 0 || (K % FQ_GROUP) != 0) return 0;
     return choose_kernel(M) == GemmKernel::Large ? fq_gemm_large_workspace_bytes(M, K) : 0;
@@ -140,9 +160,13 @@ int fq_quantize_act_ws(const uint16_t* X_bf16, uint8_t* A_fp8, float* a_scale, i
     if (M == 0) return FQ_OK;
     if (!X_bf16 || !A_fp8 || !a_scale) return FQ_ERR_NULL;
     if (!aligned16(X_bf16) || !aligned16(A_fp8)) return FQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (choose_kernel(M) != GemmKernel::Large) {          // that GEMM takes no workspace: the plain quantiser
+        fq_launch_quantize(X_bf16, A_fp8, a_scale, M, K, s);
+        return after_launch();
+    }
     if (!workspace || workspace_bytes < fq_gemm_large_workspace_bytes(M, K)) return FQ_ERR_MEMORY;
     if (!aligned16(workspace)) return FQ_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     if (fq_quantize_can_write_zero_point(K)) {
         fq_launch_quantize_zp(X_bf16, A_fp8, a_scale, M, K, workspace, s);
     } else {                                              // very long rows: two kernels

@@ -110,7 +110,10 @@ __device__ __forceinline__ void fql_issue_z(__amdgpu_buffer_rsrc_t rsZ, fq_v4i* 
     for (int t = 0; t < NMT; ++t) {
         const int q = wave + FQL_WAVES * t;
         const int slot = q / SUBS, sub = q - slot * SUBS;
-        const unsigned v = slot < nu ? (unsigned)(m0 + 64 * sub + lane) * 16u : 0xFFFFFF00u;
+        // rows past M are masked like slots past the last unit: the range check sees the per-lane
+        // offset only, and the last unit's scalar offset would carry such a row past the workspace
+        const int row = m0 + 64 * sub + lane;
+        const unsigned v = (slot < nu && row < M) ? (unsigned)row * 16u : 0xFFFFFF00u;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsZ, (fql_lds_ptr)(lds_stage + slot * RT + 64 * sub), 16, v,
                                                  (int)((unsigned)(u0 + slot) * (unsigned)M * 16u), 0, 0);
     }
@@ -142,6 +145,33 @@ __host__ __device__ inline fql_split fql_xcd_split(int x, int ntiles, int slots)
     if (r > 0 && 2 * r <= slots) { sp.nfull = count - r; sp.nhalf = 2 * r; }
     else                         { sp.nfull = count;     sp.nhalf = 0; }
     return sp;
+}
+
+// Which item workgroup `bid` of its kind (NMT = 8: whole tiles, NMT = 4: 128-row halves) runs: XCD
+// x = bid % 8 (both kinds start at a multiple of 8 workgroups), j-th item of that XCD's list.  Tile
+// order: panels of `pm` row tiles; inside a panel row tile fastest, then channel tile.  False: no item
+// (past the end of the XCD's list, or a second half without rows).
+template <int NMT>
+__host__ __device__ inline bool fql_locate(unsigned bid, int M, int tiles_m, int tiles_n, int slots, int pm,
+                                           int* m0, int* n0) {
+    const int x = bid % FQL_XCDS, j = bid / FQL_XCDS;
+    const fql_split sp = fql_xcd_split(x, tiles_m * tiles_n, slots);
+    int t, half = 0;
+    if (NMT == 8) {
+        if (j >= sp.nfull) return false;
+        t = sp.lo + j;
+    } else {
+        if (j >= sp.nhalf) return false;
+        t = sp.lo + sp.nfull + (j >> 1);
+        half = j & 1;
+    }
+    const int per_panel = pm * tiles_n;
+    const int panel = t / per_panel, rem = t - panel * per_panel;
+    const int ph = tiles_m - panel * pm < pm ? tiles_m - panel * pm : pm;   // row tiles of this panel
+    const int tn = rem / ph, tm = panel * pm + (rem - tn * ph);
+    *m0 = tm * FQL_BM + half * 128;
+    *n0 = tn * FQL_BN;
+    return *m0 < M;
 }
 
 }  // namespace
@@ -204,29 +234,8 @@ __device__ __forceinline__ void fql_item(
     constexpr int NT = NMT;                               // A transfers per wave and stage
     const int G = K / FQ_GROUP;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
-    // which item: XCD x = bid % 8 (both kinds start at a multiple of 8 workgroups), j-th item of that XCD's list
     int m0, n0;
-    {
-        const int x = bid % FQL_XCDS, j = bid / FQL_XCDS;
-        const fql_split sp = fql_xcd_split(x, tiles_m * tiles_n, slots);
-        int t, half = 0;
-        if (NMT == 8) {
-            if (j >= sp.nfull) return;
-            t = sp.lo + j;
-        } else {
-            if (j >= sp.nhalf) return;
-            t = sp.lo + sp.nfull + (j >> 1);
-            half = j & 1;
-        }
-        // tile order: panels of `pm` row tiles; inside a panel row tile fastest, then channel tile
-        const int per_panel = pm * tiles_n;
-        const int panel = t / per_panel, rem = t - panel * per_panel;
-        const int ph = tiles_m - panel * pm < pm ? tiles_m - panel * pm : pm;   // row tiles of this panel
-        const int tn = rem / ph, tm = panel * pm + (rem - tn * ph);
-        m0 = tm * FQL_BM + half * 128;
-        n0 = tn * FQL_BN;
-        if (m0 >= M) return;                              // a second half without rows
-    }
+    if (!fql_locate<NMT>(bid, M, tiles_m, tiles_n, slots, pm, &m0, &n0)) return;
     const int nw0 = n0 + wave * 32;                       // first output channel of this wave
     const bool wave_on = nw0 < N;                         // waves past N compute a duplicate tile and store nothing
     const int n = nw0 + (lane & 31);                      // this lane's output channel
@@ -641,6 +650,24 @@ size_t fq_gemm_large_workspace_bytes(int M, int K) {
     return (size_t)FQL_ZPLANES * fql_c2(K / FQ_GROUP) * (size_t)M * 16;
 }
 
+void fq_gemm_large_plan(int M, int N, int cus, int out[4]) {
+    const int tiles_m = (M + FQL_BM - 1) / FQL_BM, tiles_n = (N + FQL_BN - 1) / FQL_BN;
+    int slots = 2 * cus / FQL_XCDS;
+    if (slots < 1) slots = 1;
+    const int pm = tiles_m < 4 ? tiles_m : 4;
+    out[0] = out[1] = out[2] = out[3] = 0;
+    for (int x = 0; x < FQL_XCDS; ++x) {
+        const fql_split sp = fql_xcd_split(x, tiles_m * tiles_n, slots);
+        int m0, n0;
+        for (int j = 0; j < sp.nfull; ++j)
+            if (fql_locate<8>((unsigned)(j * FQL_XCDS + x), M, tiles_m, tiles_n, slots, pm, &m0, &n0))
+                ++out[(m0 + 256 <= M && n0 + FQL_BN <= N && (N & 7) == 0) ? 0 : 1];
+        for (int j = 0; j < sp.nhalf; ++j)
+            if (fql_locate<4>((unsigned)(j * FQL_XCDS + x), M, tiles_m, tiles_n, slots, pm, &m0, &n0))
+                ++out[(m0 + 128 <= M && n0 + FQL_BN <= N && (N & 7) == 0) ? 2 : 3];
+    }
+}
+
 void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipStream_t stream) {
     hipLaunchKernelGGL(fq_zero_point_kernel, dim3((unsigned)M), dim3(256), 0, stream, A,
                        static_cast<uint16_t*>(workspace), M, K);
@@ -649,16 +676,12 @@ void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipSt
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
                           bool swiglu, const uint16_t* R, hipStream_t stream) {
-    static bool attr_set = false;
-    static int cus = 256;
-    if (!attr_set) {
+    static fq_device_once attr_once;
+    fq_once_per_device(attr_once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
-        int dev = 0;
-        if (hipGetDevice(&dev) == hipSuccess)
-            (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-        attr_set = true;
-    }
+    });
+    const int cus = fq_device_cus();
     uint16_t* planes = static_cast<uint16_t*>(workspace); // zero-point planes
     if (!prepared) fq_launch_zero_point(A, workspace, M, K, stream);
     const int tiles_m = (M + FQL_BM - 1) / FQL_BM, tiles_n = (N + FQL_BN - 1) / FQL_BN;

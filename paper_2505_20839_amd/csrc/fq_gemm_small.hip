@@ -335,12 +335,11 @@ bool fq_launch_linear16w(int per, unsigned grid, hipStream_t stream, const uint1
                          const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y, int M, int N, int K, int cols) {
     if (per > 4) return false;
     const size_t lds = (size_t)8 * (size_t)(K + 16);      // the codes of X
-    static bool attr_set = false;
-    if (!attr_set) {
+    static fq_device_once attr_once;                       // (one per template instance)
+    fq_once_per_device(attr_once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_small16_kernel<NSUB, WORDS, false, 4, true>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 8 * (4096 + 16));
-        attr_set = true;
-    }
+    });
     hipLaunchKernelGGL((fq_gemm_small16_kernel<NSUB, WORDS, false, 4, true>), dim3(grid), dim3(FQS16_THREADS), lds, stream,
                        reinterpret_cast<const uint8_t*>(X), static_cast<const float*>(nullptr), wp, gs, tscale, Y, M, N, K, cols,
                        0, static_cast<const uint16_t*>(nullptr), a_scale_out);
@@ -623,13 +622,7 @@ struct fqs_shape {
 };
 
 fqs_shape fqs_shape_of(int N, int K, const uint8_t* gs) {
-    static int cus = 0;
-    if (cus == 0) {
-        int dev = 0, v = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0) cus = v;
-        else cus = 256;
-    }
+    const int cus = fq_device_cus();
     fqs_shape sh;
     sh.cols = ((N + cus - 1) / cus + 7) & ~7;
     sh.cols = sh.cols < 8 ? 8 : (sh.cols > 64 ? 64 : sh.cols);

@@ -2,6 +2,26 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <atomic>
+
+// ---- per-device host state (fq_device.hip) ----
+// Compute units of the current device, read once per device (256 if the runtime cannot say).
+int fq_device_cus();
+// One-time set-up that has to happen on every device the library is used on (kernel attributes): `f`
+// has run on the current device when fq_once_per_device returns.  Threads that race on a device's
+// first call may both run `f`, so it must be idempotent (hipFuncSetAttribute is).
+#define FQ_MAX_DEVICES 64
+struct fq_device_once {
+    std::atomic<unsigned char> done[FQ_MAX_DEVICES];
+};
+int fq_current_device_slot();                             // current device id, 0 if out of range or unknown
+template <class F>
+inline void fq_once_per_device(fq_device_once& st, F&& f) {
+    const int d = fq_current_device_slot();
+    if (st.done[d].load(std::memory_order_acquire)) return;
+    f();
+    st.done[d].store(1, std::memory_order_release);
+}
 
 // Each launcher validates nothing: arguments were checked by the C entry point.  They enqueue on
 // `stream` and return; the caller reads hipGetLastError().
@@ -26,6 +46,11 @@ void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t
 // holding the zero-point term of every (row, group) of A: fq_launch_zero_point writes it, and
 // fq_launch_gemm_large calls that first unless `prepared` says the workspace already holds it.
 size_t fq_gemm_large_workspace_bytes(int M, int K);
+// How the large-M kernel cuts an M x N problem on `cus` compute units: out[0] whole tiles (256 rows x
+// 128 channels) stored with whole-row vector stores, out[1] whole tiles stored element by element (rows
+// past M, channels past N, or N not a multiple of 8), out[2] / out[3] the same for the 128-row halves of
+// the tail round.
+void fq_gemm_large_plan(int M, int N, int cus, int out[4]);
 void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipStream_t stream);
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,

@@ -5,6 +5,7 @@ import oracle
 
 REL_FROBENIUS_TOL = 2e-3       # against the unrounded FP64 result (bf16 rounding alone costs ~1.7e-3)
 BOUND_TOL = 1e-3               # per element: 1 bf16 ulp + 1e-3 * sum of |terms|
+FLIP_FRACTION_TOL = 0.15       # share of outputs allowed to land one bf16 step from the once-rounded reference
 
 
 def to_gpu_bf16(bits: np.ndarray):
@@ -30,7 +31,13 @@ def check_gemm(Y_bits: np.ndarray, Y_ref: np.ndarray, bound: np.ndarray, what: s
     if denom > 0:
         rel = np.linalg.norm(Yg - Y_ref) / denom
         assert rel <= REL_FROBENIUS_TOL, "%s: relative Frobenius error %g" % (what, rel)
-    # against the once-rounded reference the disagreement must be tiny (at most rare 1-ulp flips)
+    # Against the once-rounded reference: an output differs only where the FP32 result and the exact one
+    # lie on opposite sides of a rounding boundary, which FP32 accumulation noise makes happen for a few
+    # per cent of the outputs (more where terms cancel); an epilogue that truncated, or rounded twice,
+    # would move a quarter to a half of them.  Every difference is a single bf16 step.
     Yb = oracle.bf16_bits_to_f64(oracle.bf16_round_array(Y_ref))
-    flips = np.mean(Yg != Yb)
+    differs = Yg != Yb
+    flips = np.mean(differs)
+    assert flips <= FLIP_FRACTION_TOL, "%s: %.1f %% of the outputs differ from the once-rounded reference" % (
+        what, 100 * flips)
     return {"flips_vs_rounded_ref": float(flips), "max_err_over_tol": float(np.max(err / tol))}

@@ -23,7 +23,8 @@ def test_library_exports_every_declared_symbol():
     assert names == sorted(["fq_w4a8_gemm", "fq_w4a8_gemm_ws", "fq_w4a8_gemm_swiglu_ws", "fq_w4a8_gemm_add_ws", "fq_w4a8_gemm_workspace_bytes", "fq_quantize_act", "fq_quantize_act_ws", "fq_packed_weight_bytes", "fq_pack_weights",
                             "fq_unpack_weights", "fq_layout_version", "fq_status_string",
                             "fq_cas_scales", "fq_pts_exponent", "fq_quantize_weights",
-                            "fq_w4a8_linear_ws", "fq_w4a8_linear_workspace_bytes"])
+                            "fq_w4a8_linear_ws", "fq_w4a8_linear_workspace_bytes",
+                            "fq_w4a8_gemm_plan", "fq_test_force_kernel"])
     for name in names:
         assert hasattr(L, name), name
     assert os.path.samefile(L._name, build.LIB_PATH)
@@ -92,9 +93,9 @@ def test_bad_arguments_are_rejected_without_a_launch():
     assert L.fq_quantize_act_ws(p, p, p, 4, 100, p, ctypes.c_size_t(1 << 30), null) == -2      # K % 128
     assert L.fq_quantize_act_ws(p, p, p, 0, 128, null, ctypes.c_size_t(0), null) == 0
     assert L.fq_quantize_act_ws(null, p, p, 4, 128, p, ctypes.c_size_t(1 << 30), null) == -1
-    assert L.fq_quantize_act_ws(p, p, p, 4, 128, null, ctypes.c_size_t(0), null) == -5
-    assert L.fq_quantize_act_ws(p, p, p, 4, 128, p, ctypes.c_size_t(8), null) == -5
-    assert L.fq_quantize_act_ws(p, p, p, 4, 128, odd, ctypes.c_size_t(1 << 30), null) == -3
+    assert L.fq_quantize_act_ws(p, p, p, 128, 128, null, ctypes.c_size_t(0), null) == -5
+    assert L.fq_quantize_act_ws(p, p, p, 128, 128, p, ctypes.c_size_t(8), null) == -5
+    assert L.fq_quantize_act_ws(p, p, p, 128, 128, odd, ctypes.c_size_t(1 << 30), null) == -3
     assert L.fq_quantize_act(p, p, p, 4, 12, null) == -2
     assert L.fq_quantize_act(p, p, p, 0, 128, null) == 0
     assert L.fq_quantize_act(null, p, p, 4, 128, null) == -1

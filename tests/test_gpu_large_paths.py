@@ -1,0 +1,151 @@
+"""GPU parity of every path of the large-M kernel: whole tiles (256 rows x 128 channels) and half tiles,
+with whole-row stores and with element-wise stores at ragged edges, each as the plain GEMM, with the
+residual added (out of place and in place) and with the fused gate/up epilogue -- every output element
+against the CPU oracle.  Which path a shape takes depends on the device's compute-unit count, so each
+test first asks the library (fq_w4a8_gemm_plan) and asserts that the shape reaches the path it is meant for."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_20839_amd import workloads
+from parity_util import bf16_bits_from_gpu, check_gemm, to_gpu_bf16
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def fq():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU: torch.cuda.is_available() is False")
+    from paper_2505_20839_amd import binding
+    binding.lib()
+    binding.fq_test_force_kernel(None)
+    return binding
+
+
+def _gpu(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+# shape -> the kinds of work item it must contain on this device
+WHOLE_EVEN = (2048, 8192, 256)       # 512 whole tiles, nothing ragged
+WHOLE_RAGGED = (2100, 4112, 384)     # whole tiles; last row tile has 52 rows, last channel tile 16 channels
+MIXED = (2048, 8200, 256)            # whole tiles, half tiles, and a ragged last channel tile of 8 channels
+
+
+def _plan(fq, shape):
+    return fq.fq_w4a8_gemm_plan(*shape)
+
+
+def test_shapes_reach_the_paths_they_are_meant_for(fq):
+    p = _plan(fq, WHOLE_EVEN)
+    assert p["kernel"] == "large" and p["whole"] > 0 and p["whole_ragged"] == p["half"] == p["half_ragged"] == 0
+    p = _plan(fq, WHOLE_RAGGED)
+    assert p["whole"] > 0 and p["whole_ragged"] > 0
+    p = _plan(fq, MIXED)
+    assert p["whole"] > 0 and p["half"] > 0 and p["whole_ragged"] + p["half_ragged"] > 0
+    # the benchmark workloads: c2 mixes whole and half tiles, c4a / c4b are whole tiles throughout
+    assert _plan(fq, (2048, 11008, 4096))["whole"] > 0
+    assert _plan(fq, (8192, 14336, 4096))["whole"] == 32 * 112
+    assert _plan(fq, (8192, 4096, 4096))["whole"] > 0          # attention output projection at prefill, with residual
+
+
+def _problem(shape, seed, **kw):
+    M, N, K = shape
+    return workloads.draw(M, N, K, seed=seed, outlier_frac=0.01, **kw)
+
+
+@pytest.mark.parametrize("shape", [WHOLE_EVEN, WHOLE_RAGGED, MIXED])
+def test_plain_gemm_every_element(fq, shape):
+    M, N, K = shape
+    d = _problem(shape, seed=M + N)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    Yg = fq.fq_w4a8_gemm(A, s, fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"]), d["w_tscale"], N)
+    torch.cuda.synchronize()
+    Y, B = oracle.w4a8_gemm(A.cpu().numpy(), s.cpu().numpy(), d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Yg), Y, B, "plain %s" % (shape,))
+
+
+@pytest.mark.parametrize("shape", [WHOLE_EVEN, WHOLE_RAGGED, MIXED])
+def test_residual_every_element_and_in_place(fq, shape):
+    M, N, K = shape
+    d = _problem(shape, seed=2 * M + N)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    packed, gs = fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"])
+    An, sn = A.cpu().numpy(), s.cpu().numpy()
+    Rb = workloads.draw_residual(M, N, scale=4.0, seed=M + N)
+    R = to_gpu_bf16(Rb)
+    Yg = fq.fq_w4a8_gemm_add(A, s, packed, gs, d["w_tscale"], N, R)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits_from_gpu(R), Rb)           # the residual itself is not written
+    Y, B = oracle.w4a8_gemm_add(An, sn, d["q"], d["gscale"], d["w_tscale"], Rb, want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Yg), Y, B, "add %s" % (shape,))
+    Yi = fq.fq_w4a8_gemm_add(A, s, packed, gs, d["w_tscale"], N, R, out=R)
+    torch.cuda.synchronize()
+    assert np.array_equal(bf16_bits_from_gpu(Yi), bf16_bits_from_gpu(Yg)), "in place differs"
+
+
+@pytest.mark.parametrize("shape", [WHOLE_EVEN, WHOLE_RAGGED, MIXED])
+def test_swiglu_every_element(fq, shape):
+    M, N, K = shape
+    d = _problem(shape, seed=3 * M + N, gs_lo=0.01, gs_hi=0.1, w_tscale=0.25)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    Hg = fq.fq_w4a8_gemm_swiglu(A, s, fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"]), d["w_tscale"], N)
+    torch.cuda.synchronize()
+    H, B = oracle.w4a8_gemm_swiglu(A.cpu().numpy(), s.cpu().numpy(), d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Hg), H, B, "swiglu %s" % (shape,))
+
+
+@pytest.mark.parametrize("shape", [WHOLE_EVEN, WHOLE_RAGGED, MIXED])
+def test_zero_activations_return_the_residual_bit_for_bit(fq, shape):
+    """All-zero activations: every output is bf16(0 + R[m,n]) = R[m,n], so each element of the residual has to
+    arrive at its own place in every kind of tile."""
+    M, N, K = shape
+    q = np.random.default_rng(M).integers(-8, 8, (N, K), dtype=np.int8)
+    gs = np.full((N, K // 128), 0x38, np.uint8)
+    Rb = np.random.default_rng(N).integers(0, 0x7F80, (M, N)).astype(np.uint16)
+    Rb |= np.random.default_rng(N + 1).integers(0, 2, (M, N)).astype(np.uint16) << 15
+    Rb[Rb == 0x8000] = 0                                       # 0 + (-0) is +0
+    Yg = fq.fq_w4a8_gemm_add(_gpu(np.zeros((M, K), np.uint8)), _gpu(np.ones(M, np.float32)),
+                             fq.fq_pack_weights(_gpu(q)), _gpu(gs), 1.0, N, to_gpu_bf16(Rb))
+    torch.cuda.synchronize()
+    bad = np.argwhere(bf16_bits_from_gpu(Yg) != Rb)
+    assert bad.size == 0, "%s: first wrong element %s" % (shape, bad[:1])
+
+
+def test_exactly_sized_workspace_with_ragged_rows(fq):
+    """A workspace of exactly fq_w4a8_gemm_workspace_bytes, placed at the very end of an allocation whose next
+    bytes hold a pattern: the result is the oracle's, and the bytes behind the workspace are never written."""
+    M, N, K = 300, 256, 1024
+    d = workloads.draw(M, N, K, seed=17, outlier_frac=0.01)
+    need = fq.fq_w4a8_gemm_workspace_bytes(M, N, K)
+    arena = torch.full((need + 4096,), 0xA5, dtype=torch.uint8, device="cuda")
+    ws = arena[:need]
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]), workspace=ws)
+    Yg = fq.fq_w4a8_gemm(A, s, fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"]), d["w_tscale"], N, workspace=ws,
+                         workspace_prepared=True)
+    torch.cuda.synchronize()
+    assert bool((arena[need:] == 0xA5).all())
+    Y, B = oracle.w4a8_gemm(A.cpu().numpy(), s.cpu().numpy(), d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Yg), Y, B, "exact workspace")
+
+
+def test_attention_output_projection_with_residual_at_prefill_size(fq):
+    """M = 8192, N = K = 4096 (Llama3-8B attention output projection at prefill) with the residual stream updated
+    in place: whole tiles + residual at a real size, one row of every eight against the oracle."""
+    M, N, K = 8192, 4096, 4096
+    d = workloads.draw(M, N, K, seed=41, act="laplace", outlier_frac=0.01)
+    need = fq.fq_w4a8_gemm_workspace_bytes(M, N, K)
+    ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]), workspace=ws)
+    rows = np.array([8 * i + (5 * i) % 8 for i in range(M // 8)])
+    Rb = workloads.draw_residual(M, N, scale=workloads.RESIDUAL_SCALE, seed=42)
+    R = to_gpu_bf16(Rb)
+    fq.fq_w4a8_gemm_add(A, s, fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"]), d["w_tscale"], N, R, out=R,
+                        workspace=ws, workspace_prepared=True)
+    torch.cuda.synchronize()
+    Y, B = oracle.w4a8_gemm_add(A.cpu().numpy()[rows], s.cpu().numpy()[rows], d["q"], d["gscale"], d["w_tscale"],
+                                Rb[rows], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(R)[rows], Y, B, "o_proj + residual")
