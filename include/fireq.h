@@ -80,6 +80,26 @@ int fq_w4a8_gemm(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_p
                  int M, int N, int K, void *stream);
 
 /*
+ * fq_w4a8_gemm for callers that cannot allocate device memory and have none to pass: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operands, result
+ * and status codes as fq_w4a8_gemm_ws with workspace_prepared = 0, bit for bit; the scratch is a
+ * fixed array inside the library's code object (fq_w4a8_gemm_static_max_workspace() bytes, 4 MiB,
+ * one copy on every GPU the library is loaded on, held until the process ends).  The call
+ * allocates nothing (no hipMalloc, hipFree or allocating library routine) and never synchronises.
+ * A problem whose fq_w4a8_gemm_workspace_bytes(M,N,K) exceeds that size is refused with
+ * FQ_ERR_MEMORY before anything is enqueued (M = 8192 with K = 16384 still fits).  All calls on
+ * one GPU share that GPU's array: calls that overlap in time on one GPU (different streams) race
+ * on it and give wrong results; calls on one stream, or ordered by events, are fine.  Nothing in
+ * the array has to survive or be cleared between calls: each call writes every byte it reads.
+ * The first call on a device looks the array's address up (hipGetSymbolAddress); make that call
+ * outside stream capture.
+ */
+size_t fq_w4a8_gemm_static_max_workspace(void);
+int fq_w4a8_gemm_static(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
+                        const uint8_t *w_gscale, float w_tscale, uint16_t *Y_bf16,
+                        int M, int N, int K, void *stream);
+
+/*
  * The gate and up projections of a feed-forward block in one call, with the epilogue fused
  * (Sec. 3.1.1 step 3: nonlinear activation and element-wise multiplication in the kernel's
  * epilogue).  The weight matrix holds the two projections with their rows interleaved: row 2j

@@ -36,6 +36,10 @@ def lib() -> ctypes.CDLL:
     vp, ci, cf = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
     L.fq_w4a8_gemm.restype = ci
     L.fq_w4a8_gemm.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
+    L.fq_w4a8_gemm_static.restype = ci
+    L.fq_w4a8_gemm_static.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
+    L.fq_w4a8_gemm_static_max_workspace.restype = ctypes.c_size_t
+    L.fq_w4a8_gemm_static_max_workspace.argtypes = []
     L.fq_w4a8_gemm_ws.restype = ci
     L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
     L.fq_w4a8_gemm_add_ws.restype = ci

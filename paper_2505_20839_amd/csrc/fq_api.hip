@@ -9,6 +9,11 @@
 #include <atomic>
 #include <mutex>
 
+// Scratch of fq_w4a8_gemm_static: one array per GPU the library runs on, part of the code object, held
+// until the process ends.  In host code the name is only a handle for hipGetSymbolAddress.
+#define FQ_STATIC_SCRATCH_BYTES (4u << 20)
+static __device__ __align__(256) unsigned char scratch[FQ_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -70,7 +75,8 @@ const char* fq_status_string(int status) {
         case FQ_ERR_SHAPE: return "invalid shape (sizes must be non-negative, K a positive multiple of 128)";
         case FQ_ERR_ALIGN: return "a base pointer is not 16-byte aligned";
         case FQ_ERR_LAUNCH: return "the HIP runtime rejected the kernel launch";
-        case FQ_ERR_MEMORY: return "workspace missing or too small, or the library could not allocate its own";
+        case FQ_ERR_MEMORY: return "workspace missing or too small (fq_w4a8_gemm_static: the problem needs more than the "
+                                   "built-in scratch holds), or the library could not allocate its own";
         default: return "unknown status";
     }
 }
@@ -284,6 +290,42 @@ int fq_w4a8_linear_ws(const uint16_t* X_bf16, const uint8_t* Wq_packed, const ui
     if (q != FQ_OK) return q;
     return fq_w4a8_gemm_ws(A, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, gemm_ws, gemm_ws_bytes,
                            gemm_ws_bytes > 0 ? 1 : 0, stream);
+}
+
+size_t fq_w4a8_gemm_static_max_workspace(void) { return FQ_STATIC_SCRATCH_BYTES; }
+
+int fq_w4a8_gemm_static(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                        const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
+                        int M, int N, int K, void* stream) {
+    const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, Y_bf16, M, N, K);
+    if (rc != FQ_OK || M == 0) return rc;
+    const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
+    if (need > FQ_STATIC_SCRATCH_BYTES) return FQ_ERR_MEMORY;
+    // the device address of this GPU's copy of the array, looked up once per device
+    static std::mutex m;
+    static void* ptr[FQ_MAX_DEVICES];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= FQ_MAX_DEVICES) {
+        (void)hipGetLastError();
+        return FQ_ERR_LAUNCH;
+    }
+    void* ws;
+    {
+        std::lock_guard<std::mutex> lock(m);
+        if (!ptr[dev]) {
+            void* p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+                (void)hipGetLastError();
+                return FQ_ERR_MEMORY;
+            }
+            ptr[dev] = p;
+        }
+        ws = ptr[dev];
+    }
+    // every byte of the scratch this call reads is written by this call first (the zero-point pre-pass
+    // fills all units of all M rows), so nothing needs clearing between calls
+    return fq_w4a8_gemm_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, ws, FQ_STATIC_SCRATCH_BYTES, 0,
+                           stream);
 }
 
 int fq_w4a8_gemm(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
