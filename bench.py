@@ -7,9 +7,12 @@ All inputs are synthetic (seeded) and resident in HBM before the timed region st
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 
-Prints one JSON line: whole-step throughput (`value`), the roofline figure of the GEMM call
-measured with HIP events around replays of a graph that holds only the GEMM calls of the timed
-steps, and the CPU oracle timed on a bounded sample of the same workload.
+Prints one JSON line: whole-step throughput (`value`: median over REPS timed regions of K steps
+each), the roofline figure of the GEMM call measured with HIP events around replays of a graph
+that holds only the GEMM calls (REPS repetitions of at least MIN_LAUNCHES launches after a
+warm-up of WARM_MS of replays; `frac` from the median, the best beside it), the small-M figures
+for M = 1, 4, 16, 64 with a plain streaming read of the same weights beside them, and the CPU
+oracle timed on a bounded sample of the same workload.
 """
 from __future__ import annotations
 
@@ -30,6 +33,10 @@ PEAK_HBM_GBPS = 8000.0
 DEFAULT_WORKLOAD = "c2_l2_7b_gateup"
 DECODE_COPIES = 12            # rotating weight copies so that small-M launches read HBM, not cache
 LARGE_GRAPH_STEPS = 10        # steps per captured graph at large M (one copy of the weights: they do not fit a cache)
+REPS = 5                      # timed repetitions; median and best are reported
+MIN_LAUNCHES = 50             # GEMM launches per repetition of the kernel timing (500 at small M), whatever --steps says
+MIN_LAUNCHES_SMALL = 500
+WARM_MS = 100.0               # warm-up: this many milliseconds of graph replays before every timed series
 
 
 def _traffic_from_profiles(workload: str):
@@ -88,9 +95,31 @@ def main() -> int:
         gs = torch.from_numpy(d["gscale"]).cuda()
         return w, d, X, packed, gs
 
-    def run(name, steps, warmup, copies, graph_steps):
-        """Times `steps` steps; returns (workload, inputs, steps timed, seconds for all of them,
-        mean GEMM seconds, mean quantiser seconds).
+    def timed_series(side, graph, replays):
+        """WARM_MS of replays, then REPS timed regions of `replays` replays each, every region bracketed by a
+        stream synchronisation; returns (wall seconds per region, HIP-event seconds per region) as lists."""
+        t_end = time.perf_counter() + WARM_MS * 1e-3
+        while time.perf_counter() < t_end:
+            for _ in range(4):
+                graph.replay()
+            side.synchronize()
+        walls, evs = [], []
+        for _ in range(REPS):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            side.synchronize()
+            t0 = time.perf_counter()
+            e0.record(side)
+            for _ in range(replays):
+                graph.replay()
+            e1.record(side)
+            side.synchronize()
+            walls.append(time.perf_counter() - t0)
+            evs.append(e0.elapsed_time(e1) * 1e-3)
+        return walls, evs
+
+    def run(name, steps, warmup, copies, graph_steps, with_read_floor=False):
+        """Times `steps` steps, REPS times over; returns the workload, its inputs, and per-repetition
+        seconds per step / per GEMM call / per quantiser call (lists of REPS values).
 
         A step is two or three short kernels, faster than Python can launch them one by one, so
         `graph_steps` steps are captured into a HIP graph and the graph is replayed (small M: each step
@@ -148,26 +177,25 @@ def main() -> int:
                 for i in range(graph_steps):
                     fq.fq_quantize_act(X, workspace=ws if need > 0 else None)
             reps = max(1, (steps + graph_steps - 1) // graph_steps)
+            min_launches = MIN_LAUNCHES_SMALL if w.M <= 64 else MIN_LAUNCHES
+            kreps = max(reps, (min_launches + graph_steps - 1) // graph_steps)
 
-            def timed(graph):
-                graph.replay()
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                side.synchronize()
-                t0 = time.perf_counter()
-                e0.record(side)
-                for _ in range(reps):
-                    graph.replay()
-                e1.record(side)
-                side.synchronize()
-                t1 = time.perf_counter()
-                return t1 - t0, e0.elapsed_time(e1) * 1e-3
-
-            wall, _ = timed(g_steps)
-            _, gemm_all = timed(g_gemm)
-            _, quant_all = timed(g_quant)
+            wall, _ = timed_series(side, g_steps, reps)
+            _, gemm_all = timed_series(side, g_gemm, kreps)
+            _, quant_all = timed_series(side, g_quant, kreps)
+            read_all = None
+            if with_read_floor:                            # a kernel that only reads the same weights, same rotation
+                sink = fq.fq_diag_stream_read(packs[0])
+                g_read = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g_read, stream=side):
+                    for i in range(graph_steps):
+                        fq.fq_diag_stream_read(packs[i % copies], sink)   # (98.5 % of the bytes: the scale bytes are left out)
+                _, read_all = timed_series(side, g_read, kreps)
         torch.cuda.current_stream().wait_stream(side)
-        n = reps * graph_steps
-        return w, d, n, wall, gemm_all / n, quant_all / n
+        n, nk = reps * graph_steps, kreps * graph_steps
+        per = lambda series, cnt: None if series is None else [t / cnt for t in series]   # noqa: E731
+        return {"w": w, "d": d, "steps": n, "step_s": per(wall, n), "gemm_s": per(gemm_all, nk),
+                "quant_s": per(quant_all, nk), "read_s": per(read_all, nk), "kernel_launches": nk}
 
     def offline_quantiser(N, K, reps=20):
         """Mean duration of the three offline stages on a synthetic N x K bf16 matrix (graph replays of
@@ -204,13 +232,20 @@ def main() -> int:
         torch.cuda.empty_cache()
         return out
 
+    import statistics
+
+    def med(xs):
+        return statistics.median(xs)
+
     name = args.workload
     w0 = workloads.WORKLOADS[name]
     decode_like = w0.M <= 64
     steps = args.steps if args.steps is not None else (2000 if decode_like else 200)
     warmup = args.warmup if args.warmup is not None else (50 if decode_like else 20)
-    w, d, steps, total_s, gemm_s, quant_s = run(name, steps, warmup, DECODE_COPIES if decode_like else 1,
-                                                DECODE_COPIES if decode_like else LARGE_GRAPH_STEPS)
+    r = run(name, steps, warmup, DECODE_COPIES if decode_like else 1,
+            DECODE_COPIES if decode_like else LARGE_GRAPH_STEPS, with_read_floor=decode_like)
+    w, d, steps = r["w"], r["d"], r["steps"]
+    step_s, gemm_s, quant_s = med(r["step_s"]), med(r["gemm_s"]), med(r["quant_s"])
 
     flop = 2.0 * w.M * w.N * w.K
     G = w.K // 128
@@ -220,29 +255,46 @@ def main() -> int:
         + (2 * w.M * w.N if w.epilogue == "add" else 0)
     if decode_like:
         metric, unit = "W4A8 GEMM packed-weight GB/s at small M", "GB/s"
-        value = wbytes * steps / total_s / 1e9
-        roof = {"bound": "hbm", "achieved": wbytes / gemm_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s"}
+        value = wbytes / step_s / 1e9
+        value_best = wbytes / min(r["step_s"]) / 1e9
+        roof = {"bound": "hbm", "achieved": wbytes / gemm_s / 1e9, "peak": PEAK_HBM_GBPS, "unit": "GB/s",
+                "achieved_best": wbytes / min(r["gemm_s"]) / 1e9}
     else:
         metric = ("W4A8 GEMM TFLOPS (% FP8 MFMA peak) at M=2048; GB/s (% HBM) at M=16" if name == DEFAULT_WORKLOAD
                   else ("W4A8 gate/up GEMM with fused SiLU(gate)*up, TFLOPS at M=%d" if swiglu
                         else "W4A8 GEMM with the residual added in the epilogue, TFLOPS at M=%d" if w.epilogue == "add"
                         else "W4A8 GEMM TFLOPS at M=%d") % w.M)
         unit = "TFLOP/s"
-        value = flop * steps / total_s / 1e12
-        roof = {"bound": "mfma", "achieved": flop / gemm_s / 1e12, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s"}
+        value = flop / step_s / 1e12
+        value_best = flop / min(r["step_s"]) / 1e12
+        roof = {"bound": "mfma", "achieved": flop / gemm_s / 1e12, "peak": PEAK_FP8_TFLOPS, "unit": "TFLOP/s",
+                "achieved_best": flop / min(r["gemm_s"]) / 1e12}
     roof["frac"] = roof["achieved"] / roof["peak"]
+    roof["frac_best"] = roof["achieved_best"] / roof["peak"]
     roof["traffic"] = _traffic_from_profiles(name)
-    # what one fq_w4a8_gemm call launches: kernel_us is the mean duration of the whole call
-    roof["kernel"] = ("fq_gemm_small16_kernel" if w.M <= 16 else "fq_gemm_small_kernel") if decode_like \
+    # what one fq_w4a8_gemm call launches: kernel_us is the median duration of the whole call over REPS
+    # repetitions of `kernel_launches` launches each
+    roof["kernel"] = ("fq_gemm_small16_kernel" if w.M <= 16 else "fq_gemm_smallm_kernel") if decode_like \
         else "fq_gemm_large_kernel"
     roof["kernel_us"] = gemm_s * 1e6
+    roof["kernel_us_best"] = min(r["gemm_s"]) * 1e6
+    roof["kernel_us_all"] = [round(t * 1e6, 3) for t in r["gemm_s"]]
+    roof["kernel_launches_per_repetition"] = r["kernel_launches"]
+    roof["repetitions"] = REPS
     roof["quantize_us"] = quant_s * 1e6
     roof["algorithmic_bytes"] = gemm_bytes
+    if r["read_s"] is not None:
+        read_s = med(r["read_s"])
+        roof["stream_read_us"] = read_s * 1e6
+        roof["frac_of_measured_read"] = read_s / gemm_s
 
     out = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": steps, "warmup": warmup,
-        "ms_per_step": total_s * 1e3 / steps, "higher_is_better": True, "scaling": "weak",
+        "ms_per_step": step_s * 1e3, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "fp8_e4m3 x int4 -> f32", "data": "synthetic",
+        "value_best": value_best, "value_all": [(wbytes / t / 1e9) if decode_like else (flop / t / 1e12) for t in r["step_s"]],
+        "protocol": "%.0f ms of graph replays as warm-up, then %d timed regions (each bracketed by a stream synchronisation) "
+                    "of %d steps; value = median region" % (WARM_MS, REPS, steps),
         "config": {"workload": name, "M": w.M, "N": w.N, "K": w.K, "group": 128,
                    "step": (("fq_w4a8_linear_ws (quantiser and GEMM in one kernel)" if fq.fq_w4a8_linear_workspace_bytes(w.M, w.N, w.K) == 0
                              else "fq_quantize_act + fq_w4a8_gemm") if decode_like else
@@ -252,13 +304,26 @@ def main() -> int:
         "roofline": roof,
     }
 
-    if not decode_like and not args.no_decode:
-        # second half of the metric: packed-weight GB/s at M = 16 against the HBM roofline
-        wd, dd, n_d, tot_d, gemm_d, _ = run("c5_decode_m16", 1500, 50, DECODE_COPIES, DECODE_COPIES)
+    def decode_entry(wl):
+        """Packed-weight GB/s of the GEMM call at small M over rotating weight copies, and the same bytes read by
+        a kernel that does nothing else (the ceiling one launch per GEMM can show at this size)."""
+        rd = run(wl, 600, 50, DECODE_COPIES, DECODE_COPIES, with_read_floor=True)
+        wd = rd["w"]
         wb = wd.N * wd.K / 2 + wd.N * (wd.K // 128)
-        out["decode_m16"] = {"workload": "c5_decode_m16", "kernel_us": gemm_d * 1e6, "step_us": tot_d / n_d * 1e6,
-                             "weight_GBps": wb / gemm_d / 1e9, "frac_hbm": wb / gemm_d / 1e9 / PEAK_HBM_GBPS,
-                             "weight_copies_rotated": DECODE_COPIES}
+        g, g_best, rs = med(rd["gemm_s"]), min(rd["gemm_s"]), med(rd["read_s"])
+        torch.cuda.empty_cache()
+        return {"workload": wl, "M": wd.M, "kernel_us": g * 1e6, "kernel_us_best": g_best * 1e6,
+                "step_us": med(rd["step_s"]) * 1e6, "weight_GBps": wb / g / 1e9, "frac_hbm": wb / g / 1e9 / PEAK_HBM_GBPS,
+                "frac_hbm_best": wb / g_best / 1e9 / PEAK_HBM_GBPS, "stream_read_us": rs * 1e6,
+                "stream_read_GBps": wb / rs / 1e9, "frac_of_measured_read": rs / g,
+                "launches_per_repetition": rd["kernel_launches"], "repetitions": REPS,
+                "weight_copies_rotated": DECODE_COPIES}
+
+    if not decode_like and not args.no_decode:
+        # second half of the metric: packed-weight GB/s at M = 16 against the HBM roofline (and M = 1, 4, 64 beside it)
+        out["decode_m16"] = decode_entry("c5_decode_m16")
+        if not args.no_other_configs:
+            out["decode_sweep"] = {wl: decode_entry(wl) for wl in ("c5_decode_m1", "c5_decode_m4", "c5_decode_m64")}
 
     if not args.no_other_configs and not decode_like and name == DEFAULT_WORKLOAD:
         others = {}
@@ -266,11 +331,13 @@ def main() -> int:
                       "ffn_l2_7b_down_residual"):
             if other == name:
                 continue
-            wo, _, n_o, tot_o, gemm_o, quant_o = run(other, 50, 5, 1, LARGE_GRAPH_STEPS)
+            ro = run(other, 50, 5, 1, LARGE_GRAPH_STEPS)
+            wo = ro["w"]
             fo = 2.0 * wo.M * wo.N * wo.K
-            others[other] = {"M": wo.M, "N": wo.N, "K": wo.K, "kernel_us": gemm_o * 1e6, "quantize_us": quant_o * 1e6,
-                             "step_us": tot_o / n_o * 1e6, "gemm_TFLOPs": fo / gemm_o / 1e12,
-                             "frac_mfma_peak": fo / gemm_o / 1e12 / PEAK_FP8_TFLOPS}
+            go = med(ro["gemm_s"])
+            others[other] = {"M": wo.M, "N": wo.N, "K": wo.K, "kernel_us": go * 1e6, "kernel_us_best": min(ro["gemm_s"]) * 1e6,
+                             "quantize_us": med(ro["quant_s"]) * 1e6, "step_us": med(ro["step_s"]) * 1e6,
+                             "gemm_TFLOPs": fo / go / 1e12, "frac_mfma_peak": fo / go / 1e12 / PEAK_FP8_TFLOPS}
             torch.cuda.empty_cache()
         out["other_configs"] = others
         # the offline step that produces the weight operands, on the gate/up matrix of the same model

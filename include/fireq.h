@@ -235,8 +235,14 @@ int fq_quantize_weights(const uint16_t *W_bf16, const float *lambda, int n_pts, 
  *   where it serves the shape; "" or NULL restores the choice by M.  The environment variable
  *   FQ_FORCE_KERNEL, read once when the library is loaded, sets the initial value.  Process-wide;
  *   meant for cross-checking the kernels against each other.
+ * fq_diag_stream_read: a kernel that only reads `bytes` bytes (a multiple of 16) of device memory at
+ *   `src` (16-byte aligned) and leaves fq_diag_stream_read_sink_bytes() bytes of checksums in the
+ *   device buffer `sink`.  The benchmark times it on the packed weights to put the small-M GEMM's
+ *   rate beside that of a plain streaming read of the same bytes.
  */
 int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int *plan);
+size_t fq_diag_stream_read_sink_bytes(void);
+int fq_diag_stream_read(const void *src, size_t bytes, void *sink, void *stream);
 int fq_test_force_kernel(const char *name);
 
 /* Changes whenever the byte order written by fq_pack_weights changes. */

@@ -70,6 +70,10 @@ def lib() -> ctypes.CDLL:
     L.fq_quantize_weights.argtypes = [vp, vp, ci, ci, vp, vp, ci, ci, vp]
     L.fq_w4a8_gemm_plan.restype = ci
     L.fq_w4a8_gemm_plan.argtypes = [ci, ci, ci, ci, ctypes.POINTER(ctypes.c_int)]
+    L.fq_diag_stream_read.restype = ci
+    L.fq_diag_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    L.fq_diag_stream_read_sink_bytes.restype = ctypes.c_size_t
+    L.fq_diag_stream_read_sink_bytes.argtypes = []
     L.fq_test_force_kernel.restype = ci
     L.fq_test_force_kernel.argtypes = [ctypes.c_char_p]
     L.fq_layout_version.restype = ci
@@ -350,3 +354,14 @@ def fq_w4a8_gemm_plan(M: int, N: int, K: int, cus: int = 0) -> dict:
 def fq_test_force_kernel(name: Optional[str]) -> None:
     """Cross-check hook: "simple" | "small" | "large" forces that GEMM kernel, None or "auto" restores the choice by M."""
     lib().fq_test_force_kernel((name or "").encode() if name != "auto" else b"")
+
+
+def fq_diag_stream_read(src: torch.Tensor, sink: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Measurement aid: enqueue a kernel that only reads `src` (its bytes must be a multiple of 16)."""
+    nbytes = src.numel() * src.element_size()
+    if sink is None:
+        sink = torch.empty((lib().fq_diag_stream_read_sink_bytes(),), dtype=torch.uint8, device=src.device)
+    rc = lib().fq_diag_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_diag_stream_read")
+    return sink

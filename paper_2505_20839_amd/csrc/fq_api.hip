@@ -145,6 +145,16 @@ int fq_test_force_kernel(const char* name) {
     return FQ_OK;
 }
 
+size_t fq_diag_stream_read_sink_bytes(void) { return (size_t)fq_stream_read_blocks() * sizeof(unsigned); }
+
+int fq_diag_stream_read(const void* src, size_t bytes, void* sink, void* stream) {
+    if (bytes == 0) return FQ_OK;
+    if (!src || !sink) return FQ_ERR_NULL;
+    if (!aligned16(src) || (bytes & 15u) != 0) return FQ_ERR_ALIGN;
+    fq_launch_stream_read(src, bytes, static_cast<unsigned*>(sink), static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
 int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int* plan) {
     if (M <= 0 || N <= 0 || K <= 0 || (K % FQ_GROUP) != 0 || cus < 0) return FQ_ERR_SHAPE;
     if (!plan) return FQ_ERR_NULL;

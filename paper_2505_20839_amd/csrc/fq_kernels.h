@@ -72,3 +72,8 @@ void fq_launch_pts_exponent(const uint16_t* W, const float* lambda, int* n_out, 
 void fq_launch_quantize_weights(const uint16_t* W, const float* lambda, int n_pts, bool sigma_rne, int8_t* q,
                                 uint8_t* gs, int N, int K, hipStream_t stream);
 
+
+// Measurement aid (fq_diag.hip): reads `bytes` (a multiple of 16) from src and writes one word per workgroup
+// to sink (fq_stream_read_blocks() words).
+unsigned fq_stream_read_blocks();
+void fq_launch_stream_read(const void* src, size_t bytes, unsigned* sink, hipStream_t stream);
