@@ -197,6 +197,32 @@ def main() -> int:
         return {"w": w, "d": d, "steps": n, "step_s": per(wall, n), "gemm_s": per(gemm_all, nk),
                 "quant_s": per(quant_all, nk), "read_s": per(read_all, nk), "kernel_launches": nk}
 
+    def table_mode(wl):
+        """The paper's table mode (fq_w4a8_gemm_lut: weights rounded to E4M3(q * sigma), no per-group scaling) on
+        workload `wl`: GEMM-call duration measured like the exact mode's, and how far its result lies from the
+        exact mode's on the same operands (relative Frobenius distance of the two bf16 outputs)."""
+        w, d, X, packed, gs = upload(wl)
+        A, a_s = fq.fq_quantize_act(X)
+        Yl = fq.fq_w4a8_gemm_lut(A, a_s, packed, gs, d["w_tscale"], w.N)
+        Ye = fq.fq_w4a8_gemm(A, a_s, packed, gs, d["w_tscale"], w.N)
+        torch.cuda.synchronize()
+        rel = float((Yl.float() - Ye.float()).norm() / Ye.float().norm())
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                for _ in range(LARGE_GRAPH_STEPS):
+                    fq.fq_w4a8_gemm_lut(A, a_s, packed, gs, d["w_tscale"], w.N, out=Yl)
+            _, ev = timed_series(side, g, MIN_LAUNCHES // LARGE_GRAPH_STEPS)
+        torch.cuda.current_stream().wait_stream(side)
+        per = sorted(t / MIN_LAUNCHES for t in ev)
+        flop = 2.0 * w.M * w.N * w.K
+        return {"workload": wl, "kernel": "fq_gemm_large_lut_kernel", "kernel_us": per[len(per) // 2] * 1e6,
+                "kernel_us_best": per[0] * 1e6, "gemm_TFLOPs": flop / per[len(per) // 2] / 1e12,
+                "frac_mfma_peak": flop / per[len(per) // 2] / 1e12 / PEAK_FP8_TFLOPS,
+                "rel_frobenius_distance_from_exact_mode": rel}
+
     def offline_quantiser(N, K, reps=20):
         """Mean duration of the three offline stages on a synthetic N x K bf16 matrix (graph replays of
         `reps` calls each) and the HBM rate of their algorithmic bytes."""
@@ -340,6 +366,7 @@ def main() -> int:
                              "gemm_TFLOPs": fo / go / 1e12, "frac_mfma_peak": fo / go / 1e12 / PEAK_FP8_TFLOPS}
             torch.cuda.empty_cache()
         out["other_configs"] = others
+        out["table_mode"] = table_mode(name)
         # the offline step that produces the weight operands, on the gate/up matrix of the same model
         out["offline_quantiser"] = offline_quantiser(11008, 4096)
 

@@ -100,6 +100,23 @@ int fq_w4a8_gemm_static(const uint8_t *A_fp8, const float *a_scale, const uint8_
                         int M, int N, int K, void *stream);
 
 /*
+ * The same GEMM in the paper's own table mode (Sec. 3.1.1 steps 1-2; App. B.1 compares it with exact
+ * scales): per group and channel a 16-entry FP8 table T[q] = E4M3(q * sigma), q = -8..7 (nearest
+ * even, saturating at +-448), the INT4 codes looked up in registers, and
+ *
+ *   Y[m,n] = bf16( a_scale[m] * w_tscale * sum_k e4m3(A_fp8[m,k]) * T_{n, k/128}[ q[n,k] ] )
+ *
+ * accumulated in FP32 over all of K with no separate group scale.  It is an approximation of
+ * fq_w4a8_gemm (q * sigma keeps at most four significant bits: about 2 % relative error on
+ * workload-like operands) and exists to measure that trade-off; the library's linear layers use
+ * the exact form.  Operands, checks and status codes as for fq_w4a8_gemm; needs no workspace,
+ * allocates nothing, keeps no state; every M is served by the large-M kernel.
+ */
+int fq_w4a8_gemm_lut(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
+                     const uint8_t *w_gscale, float w_tscale, uint16_t *Y_bf16,
+                     int M, int N, int K, void *stream);
+
+/*
  * The gate and up projections of a feed-forward block in one call, with the epilogue fused
  * (Sec. 3.1.1 step 3: nonlinear activation and element-wise multiplication in the kernel's
  * epilogue).  The weight matrix holds the two projections with their rows interleaved: row 2j

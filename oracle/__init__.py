@@ -62,7 +62,7 @@ def _load():
     lib.fqo_w4a8_gemm.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
                                   ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.fqo_w4a8_gemm_lut.restype = ctypes.c_int
-    lib.fqo_w4a8_gemm_lut.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p,
+    lib.fqo_w4a8_gemm_lut.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.fqo_w4a8_gemm_swiglu.restype = ctypes.c_int
     lib.fqo_w4a8_gemm_swiglu.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
@@ -156,9 +156,10 @@ def w4a8_gemm(A, a_scale, q, gscale, w_tscale, want_bound: bool = False):
     return (Y, B) if want_bound else Y
 
 
-def w4a8_gemm_lut(A, a_scale, q, gscale, w_tscale):
+def w4a8_gemm_lut(A, a_scale, q, gscale, w_tscale, want_bound: bool = False):
     """FP64 ``Y[M,N]`` of the GEMM in the paper's table form (Sec. 3.1.1 step 1): every weight is the
-    E4M3 rounding of ``q * sigma``.  A measuring stick for that rounding, not the library's target."""
+    E4M3 rounding of ``q * sigma``.  A measuring stick for that rounding, not the library's target.
+    With ``want_bound`` also the same sum over absolute values (the forward-error scale)."""
     A = _c(A, np.uint8)
     a_scale = _c(a_scale, np.float32)
     q = _c(q, np.int8)
@@ -170,13 +171,15 @@ def w4a8_gemm_lut(A, a_scale, q, gscale, w_tscale):
     if q.size and (q.min() < -8 or q.max() > 7):
         raise ValueError("INT4 codes out of range")
     Y = np.zeros((M, N), dtype=np.float64)
+    B = np.zeros((M, N), dtype=np.float64) if want_bound else None
     rc = _load().fqo_w4a8_gemm_lut(
         _ptr(A, ctypes.c_uint8), _ptr(a_scale, ctypes.c_float), _ptr(q, ctypes.c_int8),
         _ptr(gscale, ctypes.c_uint8), ctypes.c_float(float(np.float32(w_tscale))),
-        _ptr(Y, ctypes.c_double), M, N, K)
+        _ptr(Y, ctypes.c_double),
+        _ptr(B, ctypes.c_double) if want_bound else ctypes.POINTER(ctypes.c_double)(), M, N, K)
     if rc != 0:
         raise ValueError("fqo_w4a8_gemm_lut failed with %d" % rc)
-    return Y
+    return (Y, B) if want_bound else Y
 
 
 def w4a8_gemm_swiglu(A, a_scale, q, gscale, w_tscale, want_bound: bool = False):

@@ -251,7 +251,7 @@ int fqo_w4a8_gemm(const uint8_t *A, const float *a_scale, const int8_t *q,
  * nearest-even, saturating at 448; sums in FP64 (the paper accumulates in FP32).
  * ------------------------------------------------------------------------------------- */
 int fqo_w4a8_gemm_lut(const uint8_t *A, const float *a_scale, const int8_t *q,
-                      const uint8_t *gscale, float w_tscale, double *Y, int M, int N, int K)
+                      const uint8_t *gscale, float w_tscale, double *Y, double *B, int M, int N, int K)
 {
     if (M < 0 || N < 0 || K < 0 || (K % FQO_GROUP) != 0)
         return -1;
@@ -278,10 +278,15 @@ int fqo_w4a8_gemm_lut(const uint8_t *A, const float *a_scale, const int8_t *q,
     for (m = 0; m < M; ++m) {
         const double outer = (double)a_scale[m] * (double)w_tscale;
         for (int n = 0; n < N; ++n) {
-            double y = 0.0;
-            for (int k = 0; k < K; ++k)
-                y += fqo_e4m3_decode(A[(size_t)m * K + k]) * Wd[(size_t)n * K + k];
+            double y = 0.0, b = 0.0;                                /* b: the same sum over absolute values */
+            for (int k = 0; k < K; ++k) {
+                const double t = fqo_e4m3_decode(A[(size_t)m * K + k]) * Wd[(size_t)n * K + k];
+                y += t;
+                b += fabs(t);
+            }
             Y[(size_t)m * N + n] = outer * y;
+            if (B)
+                B[(size_t)m * N + n] = fabs(outer) * b;
         }
     }
     free(Wd);

@@ -40,6 +40,8 @@ def lib() -> ctypes.CDLL:
     L.fq_w4a8_gemm_static.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
     L.fq_w4a8_gemm_static_max_workspace.restype = ctypes.c_size_t
     L.fq_w4a8_gemm_static_max_workspace.argtypes = []
+    L.fq_w4a8_gemm_lut.restype = ci
+    L.fq_w4a8_gemm_lut.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
     L.fq_w4a8_gemm_ws.restype = ci
     L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
     L.fq_w4a8_gemm_add_ws.restype = ci
@@ -365,3 +367,27 @@ def fq_diag_stream_read(src: torch.Tensor, sink: Optional[torch.Tensor] = None) 
     if rc != 0:
         raise FireqError(rc, "fq_diag_stream_read")
     return sink
+
+
+def fq_w4a8_gemm_lut(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor, w_gscale: torch.Tensor,
+                     w_tscale: float, N: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Y[M,N] (bf16) of the GEMM in the paper's table mode (weights rounded to E4M3(q * sigma)); calls fq_w4a8_gemm_lut."""
+    A = _dev(A, torch.uint8, "A")
+    a_scale = _dev(a_scale, torch.float32, "a_scale")
+    Wq_packed = _dev(Wq_packed, torch.uint8, "Wq_packed")
+    w_gscale = _dev(w_gscale, torch.uint8, "w_gscale")
+    M, K = A.shape
+    if a_scale.numel() != M or K % GROUP or w_gscale.numel() != N * (K // GROUP) \
+            or Wq_packed.numel() < fq_packed_weight_bytes(N, K):
+        raise FireqError(-2, "fq_w4a8_gemm_lut")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A.device)
+    else:
+        out = _dev(out, torch.bfloat16, "out")
+        if tuple(out.shape) != (M, N):
+            raise FireqError(-2, "fq_w4a8_gemm_lut")
+    rc = lib().fq_w4a8_gemm_lut(A.data_ptr(), a_scale.data_ptr(), Wq_packed.data_ptr(), w_gscale.data_ptr(),
+                                ctypes.c_float(float(w_tscale)), out.data_ptr(), M, N, K, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_w4a8_gemm_lut")
+    return out

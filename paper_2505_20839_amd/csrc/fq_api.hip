@@ -302,6 +302,20 @@ int fq_w4a8_linear_ws(const uint16_t* X_bf16, const uint8_t* Wq_packed, const ui
                            gemm_ws_bytes > 0 ? 1 : 0, stream);
 }
 
+int fq_w4a8_gemm_lut(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                     const uint8_t* w_gscale, float w_tscale, uint16_t* Y_bf16,
+                     int M, int N, int K, void* stream) {
+    const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, Y_bf16, M, N, K);
+    if (rc != FQ_OK || M == 0) return rc;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (forced_kernel() == GemmKernel::Simple)
+        fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, false, nullptr, s, true);
+    else
+        fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, Y_bf16, M, N, K, nullptr, true, false, nullptr, s,
+                             true);
+    return after_launch();
+}
+
 size_t fq_w4a8_gemm_static_max_workspace(void) { return FQ_STATIC_SCRATCH_BYTES; }
 
 int fq_w4a8_gemm_static(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,

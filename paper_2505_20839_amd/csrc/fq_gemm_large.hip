@@ -119,6 +119,46 @@ __device__ __forceinline__ void fql_issue_z(__amdgpu_buffer_rsrc_t rsZ, fq_v4i* 
     }
 }
 
+// ---- table mode (Sec. 3.1.1 step 1): the group scale folded into a 16-entry FP8 table ----
+// T[c] = E4M3(q * sigma), q = c - 8, rounded to nearest even and saturating at +-448: the paper's
+// in-register table {-8 sigma .. 7 sigma} of one group of one channel, 16 bytes in four registers.
+__device__ __forceinline__ fq_v4i fql_lut_table(float sigma) {
+    fq_v4i t;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float v[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) v[e] = fminf(fmaxf((float)(4 * i + e - 8) * sigma, -448.f), 448.f);   // q * sigma is exact in FP32
+        int r = 0;
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(v[0], v[1], r, false);
+        r = __builtin_amdgcn_cvt_pk_fp8_f32(v[2], v[3], r, true);
+        t[i] = r;
+    }
+    return t;
+}
+
+// Four codes (one per byte, 0..15) -> their four table entries: two 8-entry byte permutes and a select
+// on bit 3 of each code.
+__device__ __forceinline__ int fql_lut4(unsigned x, fq_v4i t) {
+    const unsigned lo = x & 0x07070707u;
+    const unsigned r0 = __builtin_amdgcn_perm((unsigned)t[1], (unsigned)t[0], lo);
+    const unsigned r1 = __builtin_amdgcn_perm((unsigned)t[3], (unsigned)t[2], lo);
+    const unsigned b3 = x & 0x08080808u;
+    const unsigned mask = (b3 << 5) - (b3 >> 3);          // 0xFF in every byte whose code is 8 or more
+    return (int)((r0 & ~mask) | (r1 & mask));
+}
+
+__device__ __forceinline__ fq_v8i fql_unpack_chunk_lut(fq_v4i w, fq_v4i t) {
+    fq_v8i r;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const unsigned u = (unsigned)w[i];
+        r[i]     = fql_lut4(u & 0x0F0F0F0Fu, t);
+        r[4 + i] = fql_lut4((u >> 4) & 0x0F0F0F0Fu, t);
+    }
+    return r;
+}
+
 // s_waitcnt immediate (gfx9 encoding) that waits until at most n vector-memory transfers are pending
 // and leaves the other counters alone.
 #define FQL_WAIT_VM(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
@@ -224,7 +264,12 @@ __global__ __launch_bounds__(256) void fq_zero_point_kernel(const uint8_t* __res
 
 // One item: NMT row tiles of 32 rows (8, or 4 for the half tiles) x 128 channels.  `bid` counts the
 // workgroups of the item's kind.
-template <int NMT>
+// LUT: the paper's table mode instead of the exact one.  The weights enter the matrix cores as
+// E4M3(q * sigma) (looked up in a per-group table that is built one group ahead), the products
+// accumulate straight into the tile (no per-group scaling, no zero point, `planes` unused), and
+// the output factor is a_scale * w_tscale alone.  Everything else (tile order, transfers, epilogues)
+// is shared with the exact mode.
+template <int NMT, bool LUT = false>
 __device__ __forceinline__ void fql_item(
     fq_v4i* lds, const unsigned bid,
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
@@ -281,9 +326,15 @@ __device__ __forceinline__ void fql_item(
     fq_v8i b0[2], b1[2];                                  // unpacked operands: [u] current, [u^1] next
     float sc[2];
     __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
-    b0[0] = fq_unpack_chunk(wbuf[lane]);
-    b1[0] = fq_unpack_chunk(wbuf[64 + lane]);
     sc[0] = __builtin_amdgcn_cvt_f32_fp8((int)psb[0], 0);
+    if (LUT) {
+        const fq_v4i t0 = fql_lut_table(sc[0]);
+        b0[0] = fql_unpack_chunk_lut(wbuf[lane], t0);
+        b1[0] = fql_unpack_chunk_lut(wbuf[64 + lane], t0);
+    } else {
+        b0[0] = fq_unpack_chunk(wbuf[lane]);
+        b1[0] = fq_unpack_chunk(wbuf[64 + lane]);
+    }
     b0[1] = b0[0]; b1[1] = b1[0]; sc[1] = 0.f;
     __syncthreads();
 
@@ -310,7 +361,7 @@ __device__ __forceinline__ void fql_item(
             {   // A tile of the next group -> the stage the previous group used (all waves are past
                 // the barrier that ended it)
                 const int g1 = g + 1 < G ? g + 1 : G - 1;
-                if (LAST && u == 1)
+                if (LAST && u == 1 && !LUT)
                     fql_issue_z<NMT>(rsZ, lds + (u ^ 1) * FQL_STAGE_CHUNKS, wave, lane, m0, M, 0, ZU < 8 ? ZU : 8);
                 else
                     fql_issue_a<NT>(rsA, abase, m0, K, lds + (u ^ 1) * FQL_STAGE_CHUNKS, wave, g1);
@@ -328,6 +379,8 @@ __device__ __forceinline__ void fql_item(
             __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(NT + 3));
             const fq_v4i* nxt = wbuf + (u ^ 1) * 128 + lane;
             const float s = sc[u];
+            fq_v4i tabn = {0, 0, 0, 0};                   // table of group g+1 (all zero for a ghost group)
+            if (LUT) tabn = fql_lut_table((g + 1 < G) ? __builtin_amdgcn_cvt_f32_fp8((int)qs, 0) : 0.f);
             fq_v4i q = nxt[0];                            // packed words 0..3; 4..7 are fetched half-way
             fq_v16f pt;
             __builtin_amdgcn_sched_barrier(0);
@@ -345,10 +398,14 @@ __device__ __forceinline__ void fql_item(
                     } else if (mt + 1 < NMT) {
                         an = fql_join(cur[(mt + 1) * 256 + o00], cur[(mt + 1) * 256 + o01]);
                     }
-                    if (h == 0) pt = FQ_MFMA(ac, b0[u], zero);
-                    else        pt = FQ_MFMA(ac, b1[u], pt);
+                    if (LUT) {
+                        acc[mt] = FQ_MFMA(ac, h == 0 ? b0[u] : b1[u], acc[mt]);
+                    } else {
+                        if (h == 0) pt = FQ_MFMA(ac, b0[u], zero);
+                        else        pt = FQ_MFMA(ac, b1[u], pt);
 #pragma unroll
-                    for (int r = 8 * h; r < 8 * h + 8; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
+                        for (int r = 8 * h; r < 8 * h + 8; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
+                    }
                     // a share of the next group's unpack: half a packed word per step with 8 row
                     // tiles, a whole word's half twice with 4
 #pragma unroll
@@ -356,7 +413,7 @@ __device__ __forceinline__ void fql_item(
                         const int slot = (8 / NMT) * mt + e;                    // packed word 0..7
                         const unsigned w = (unsigned)q[slot & 3];
                         const unsigned x = (h == 0 ? w : (w >> 4)) & 0x0F0F0F0Fu;
-                        const int ev = (int)x;                        // byte c = c * 2^-9 in E4M3
+                        const int ev = LUT ? fql_lut4(x, tabn) : (int)x;   // exact mode: byte c = c * 2^-9 in E4M3
                         if (slot < 4) b0[u ^ 1][4 * h + (slot & 3)] = ev;
                         else          b1[u ^ 1][4 * h + (slot & 3)] = ev;
                     }
@@ -366,7 +423,7 @@ __device__ __forceinline__ void fql_item(
                     __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);  // its shadow: VALU work
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                pprev = pt;
+                if (!LUT) pprev = pt;
             }
             sprev = s;
             {
@@ -386,8 +443,10 @@ __device__ __forceinline__ void fql_item(
     for (int p = 0; p < npairs - 1; ++p) pair_of_groups(p, std::false_type());
     pair_of_groups(npairs - 1, std::true_type());
     // last pending row tile of the last group
+    if (!LUT) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) acc[NMT - 1][r] = fmaf(sprev, pprev[r], acc[NMT - 1][r]);
+        for (int r = 0; r < 16; ++r) acc[NMT - 1][r] = fmaf(sprev, pprev[r], acc[NMT - 1][r]);
+    }
 
     // ---- residual tile (activation addition, Sec. 3.1.1 step 3): requested now, used in the epilogue ----
     // Step `it` of the epilogue handles rows 8 * it + 4 * (lane / 32) + 0..3 of this lane's channel.
@@ -415,7 +474,10 @@ __device__ __forceinline__ void fql_item(
     // Rounds of up to 8 units of Z (32 * NMT rows x 8 groups, 16 bytes per row); round r sits in A
     // stage r & 1 (round 0 arrived during the last group) while the next round is on its way to
     // the other stage.  Units 2c and 2c + 1 of a plane are the two lane halves of MFMA chunk c.
-    {
+    if (LUT) {                                            // no zero point; the stages are reused below
+        __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
+        __syncthreads();
+    } else {
         constexpr int RT = 32 * NMT;                      // rows of the item
         // (range rounded up to whole words: the array's last word may hold fewer than four scales, and a
         // word that crosses the end of the range would read as zero; the array is 16-byte aligned, so that
@@ -488,7 +550,7 @@ __device__ __forceinline__ void fql_item(
     float* osc = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + FQL_BM * FQL_OUT_STRIDE);
     for (int i = threadIdx.x; i < 32 * NMT; i += FQL_THREADS) {   // x 2^9: the weights were fed in units of 2^-9
         int m = m0 + i;
-        osc[i] = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);
+        osc[i] = a_scale[m < M ? m : M - 1] * (LUT ? tscale : tscale * 512.0f);
     }
     __syncthreads();
     if (swiglu) {
@@ -646,6 +708,20 @@ void fq_gemm_large_kernel(
                     swiglu, R);
 }
 
+// The table mode of the same items (no zero-point planes).
+__global__ __launch_bounds__(FQL_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void fq_gemm_large_lut_kernel(
+    const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
+    const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K,
+    int tiles_m, int tiles_n, int slots, int pm, unsigned full_wgs, int swiglu, const uint16_t* R) {
+    extern __shared__ fq_v4i lds[];
+    if (blockIdx.x < full_wgs)
+        fql_item<8, true>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, nullptr, swiglu, R);
+    else
+        fql_item<4, true>(lds, blockIdx.x - full_wgs, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, nullptr,
+                          swiglu, R);
+}
+
 size_t fq_gemm_large_workspace_bytes(int M, int K) {
     return (size_t)FQL_ZPLANES * fql_c2(K / FQ_GROUP) * (size_t)M * 16;
 }
@@ -675,15 +751,17 @@ void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipSt
 
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
-                          bool swiglu, const uint16_t* R, hipStream_t stream) {
+                          bool swiglu, const uint16_t* R, hipStream_t stream, bool lut) {
     static fq_device_once attr_once;
     fq_once_per_device(attr_once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_lut_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, FQL_LDS_BYTES);
     });
     const int cus = fq_device_cus();
     uint16_t* planes = static_cast<uint16_t*>(workspace); // zero-point planes
-    if (!prepared) fq_launch_zero_point(A, workspace, M, K, stream);
+    if (!prepared && !lut) fq_launch_zero_point(A, workspace, M, K, stream);
     const int tiles_m = (M + FQL_BM - 1) / FQL_BM, tiles_n = (N + FQL_BN - 1) / FQL_BN;
     int slots = 2 * cus / FQL_XCDS;                       // resident workgroups per XCD: two per compute unit
     if (slots < 1) slots = 1;
@@ -696,6 +774,11 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
         max_half = sp.nhalf > max_half ? sp.nhalf : max_half;
     }
     const unsigned full_wgs = (unsigned)(max_full * FQL_XCDS), half_wgs = (unsigned)(max_half * FQL_XCDS);
+    if (lut) {
+        hipLaunchKernelGGL(fq_gemm_large_lut_kernel, dim3(full_wgs + half_wgs), dim3(FQL_THREADS), FQL_LDS_BYTES, stream,
+                           A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, full_wgs, swiglu ? 1 : 0, R);
+        return;
+    }
     hipLaunchKernelGGL(fq_gemm_large_kernel, dim3(full_wgs + half_wgs), dim3(FQL_THREADS), FQL_LDS_BYTES, stream,
                        A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, full_wgs,
                        swiglu ? 1 : 0, R);

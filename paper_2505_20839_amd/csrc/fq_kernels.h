@@ -37,11 +37,13 @@ void fq_launch_quantize_zp(const uint16_t* X, uint8_t* A, float* a_scale, int M,
 // GEMM kernels.  `which` selects the kernel: see fq_api.hip.
 // `swiglu` (all three launchers): channels 2j / 2j+1 are the gate / up rows of a feed-forward block and
 // the output is H[M, N/2] = bf16(SiLU(gate) * up) instead of Y[M, N] (N even).
+// `lut` (the simple and the large-M launcher): the paper's table mode, weights rounded to E4M3(q * sigma)
+// before the products (Sec. 3.1.1 step 1); workspace and `prepared` are ignored then.
 // `R` (all three; NULL = none; not together with swiglu): residual [M, N] in bf16 added to the result
 // before its one rounding; may be the output array itself.
 void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                            float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, const uint16_t* R,
-                           hipStream_t stream);
+                           hipStream_t stream, bool lut = false);
 // The large-M kernel needs fq_gemm_large_workspace_bytes(M, K) bytes of device scratch (16-byte aligned)
 // holding the zero-point term of every (row, group) of A: fq_launch_zero_point writes it, and
 // fq_launch_gemm_large calls that first unless `prepared` says the workspace already holds it.
@@ -54,7 +56,7 @@ void fq_gemm_large_plan(int M, int N, int cus, int out[4]);
 void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipStream_t stream);
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
-                          bool swiglu, const uint16_t* R, hipStream_t stream);
+                          bool swiglu, const uint16_t* R, hipStream_t stream, bool lut = false);
 // M <= 64 only; returns false (nothing enqueued) for a shape it does not serve.
 bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, const uint16_t* R,

@@ -18,8 +18,11 @@ def bf16_bits_from_gpu(t) -> np.ndarray:
     return t.view(torch.int16).cpu().numpy().view(np.uint16)
 
 
-def check_gemm(Y_bits: np.ndarray, Y_ref: np.ndarray, bound: np.ndarray, what: str = ""):
-    """Y_bits: uint16 bf16 patterns from the GPU; Y_ref, bound: FP64 from the oracle."""
+def check_gemm(Y_bits: np.ndarray, Y_ref: np.ndarray, bound: np.ndarray, what: str = "", frobenius: bool = True):
+    """Y_bits: uint16 bf16 patterns from the GPU; Y_ref, bound: FP64 from the oracle.
+    frobenius=False leaves out the norm-wise criterion (for inputs built so that a handful of outputs carry the
+    whole norm: their bf16 rounding alone, up to 2^-9 each, can then exceed the 2e-3 meant for a matrix of like-sized
+    outputs); the element-wise criterion, which is the sharper one, always applies."""
     Yg = oracle.bf16_bits_to_f64(Y_bits)
     assert np.all(np.isfinite(Yg)), what + ": non-finite output"
     err = np.abs(Yg - Y_ref)
@@ -28,7 +31,7 @@ def check_gemm(Y_bits: np.ndarray, Y_ref: np.ndarray, bound: np.ndarray, what: s
     assert np.all(err <= tol), "%s: element %s off by %g (tol %g, ref %g)" % (
         what, np.unravel_index(worst, err.shape), err.flat[worst], tol.flat[worst], Y_ref.flat[worst])
     denom = np.linalg.norm(Y_ref)
-    if denom > 0:
+    if denom > 0 and frobenius:
         rel = np.linalg.norm(Yg - Y_ref) / denom
         assert rel <= REL_FROBENIUS_TOL, "%s: relative Frobenius error %g" % (what, rel)
     # Against the once-rounded reference: an output differs only where the FP32 result and the exact one

@@ -576,3 +576,65 @@ def test_linear_on_every_bf16_magnitude(fq):
     assert np.array_equal(bf16_bits_from_gpu(Yl), bf16_bits_from_gpu(Y2))
     An, sn = oracle.quantize_act(Xb)
     assert np.array_equal(A.cpu().numpy() & 0x7F, An & 0x7F) and np.array_equal(s.cpu().numpy(), sn)
+
+
+# ---- the paper's table mode (Sec. 3.1.1 step 1) ----------------------------------------------------
+
+LUT_SHAPES = [("simple", (5, 64, 256)), ("simple", (33, 100, 384)),
+              ("large", (16, 256, 512)), ("large", (65, 33, 128)), ("large", (300, 200, 640)), ("large", (257, 513, 384)),
+              ("large", (512, 256, 1408)), ("large", (2048, 8192, 256)), ("large", (2100, 4112, 384))]
+
+
+@pytest.mark.parametrize("kernel,shape", LUT_SHAPES)
+def test_gemm_table_mode_matches_its_oracle(fq, kernel_choice, kernel, shape):
+    """fq_w4a8_gemm_lut against the oracle's table-form GEMM (every weight E4M3(q * sigma)), element by element at
+    the tolerance of the exact mode (one bf16 step + 1e-3 of the sum of |terms|); the scales span subnormals,
+    normals and a few that saturate the table."""
+    M, N, K = shape
+    A, a, q, gs, t = _rand_codes(M, N, K, seed=2 * M + N + K)
+    gs[0, :] = 0x7E                                            # 448: every entry but 0 and +-1 saturates
+    gs[N // 2, :] = 0x00                                       # zero scale: an all-zero table (App. B, Lemma B.1)
+    kernel_choice(kernel if kernel == "simple" else "auto")
+    Yg = fq.fq_w4a8_gemm_lut(_gpu(A), _gpu(a), fq.fq_pack_weights(_gpu(q)), _gpu(gs), t, N)
+    torch.cuda.synchronize()
+    Y, B = oracle.w4a8_gemm_lut(A, a, q, gs, t, want_bound=True)
+    # (channel 0 saturates and carries the whole norm: element-wise criterion only)
+    check_gemm(bf16_bits_from_gpu(Yg), Y, B, "table mode %s %s" % (kernel, shape), frobenius=False)
+
+
+def test_table_mode_equals_exact_mode_for_power_of_two_scales(fq):
+    """Power-of-two scales: q * sigma keeps q's four bits, the table rounds nothing, and the two modes compute
+    the same sums (each to its own FP32 summation order: equal within a few FP32 steps of the bound)."""
+    M, N, K = 300, 256, 1024
+    A, a, q, gs, t = _rand_codes(M, N, K, seed=77)
+    gs = (np.random.default_rng(3).integers(2, 12, gs.shape).astype(np.uint8) << 3)
+    Ad, ad, pk, gd = _gpu(A), _gpu(a), fq.fq_pack_weights(_gpu(q)), _gpu(gs)
+    Yl = bf16_bits_from_gpu(fq.fq_w4a8_gemm_lut(Ad, ad, pk, gd, t, N))
+    Ye = bf16_bits_from_gpu(fq.fq_w4a8_gemm(Ad, ad, pk, gd, t, N))
+    torch.cuda.synchronize()
+    Y, B = oracle.w4a8_gemm(A, a, q, gs, t, want_bound=True)
+    d = np.abs(oracle.bf16_bits_to_f64(Yl) - oracle.bf16_bits_to_f64(Ye))
+    assert np.all(d <= oracle.bf16_ulp_array(Y) + 1e-4 * B)
+    check_gemm(Yl, Y, B, "table mode, power-of-two scales, against the exact oracle")
+
+
+def test_table_mode_full_size_and_what_it_costs(fq):
+    """c2 at full size in table mode: every element against the table-form oracle, and the relative Frobenius
+    distance of the two modes on the GPU, which must be the oracle's (about 2 %: ten times the error budget)."""
+    name = "c2_l2_7b_gateup"
+    w = workloads.WORKLOADS[name]
+    d = workloads.draw_workload(name)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    pk, gd = fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"])
+    Yl = bf16_bits_from_gpu(fq.fq_w4a8_gemm_lut(A, s, pk, gd, d["w_tscale"], w.N))
+    Ye = bf16_bits_from_gpu(fq.fq_w4a8_gemm(A, s, pk, gd, d["w_tscale"], w.N))
+    torch.cuda.synchronize()
+    An, sn = A.cpu().numpy(), s.cpu().numpy()
+    Y, B = oracle.w4a8_gemm_lut(An, sn, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(Yl, Y, B, name + " table mode")
+    rows = slice(0, 256)
+    exact = oracle.w4a8_gemm(An[rows], sn[rows], d["q"], d["gscale"], d["w_tscale"])
+    rel_oracle = np.linalg.norm(Y[rows] - exact) / np.linalg.norm(exact)
+    yl, ye = oracle.bf16_bits_to_f64(Yl[rows]), oracle.bf16_bits_to_f64(Ye[rows])
+    rel_gpu = np.linalg.norm(yl - ye) / np.linalg.norm(ye)
+    assert 0.01 < rel_oracle < 0.04 and abs(rel_gpu - rel_oracle) < 0.002, (rel_gpu, rel_oracle)

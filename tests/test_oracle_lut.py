@@ -56,3 +56,20 @@ def test_what_the_table_rounding_costs():
     w_table = np.array([oracle.e4m3_decode(oracle.e4m3_encode_rne(float(x))) for x in w_exact.ravel()[:20000]])
     rms = np.sqrt(np.mean((w_table - w_exact.ravel()[:20000]) ** 2) / np.mean(w_exact.ravel()[:20000] ** 2))
     assert 0.015 < rms < 0.035, rms
+
+
+def test_bound_is_the_sum_of_absolute_terms():
+    """The bound returned beside the table-form result is the same sum with every term's absolute value: equal
+    to |Y| when all terms have one sign, and never below |Y|."""
+    rng = np.random.default_rng(5)
+    M, N, K = 3, 5, 256
+    A = rng.integers(0x20, 0x60, (M, K)).astype(np.uint8)                      # positive activations
+    q = rng.integers(0, 8, (N, K), dtype=np.int8)                              # non-negative weights
+    gs = rng.integers(0x10, 0x40, (N, K // 128)).astype(np.uint8)
+    a = rng.uniform(0.5, 2, M).astype(np.float32)
+    Y, B = oracle.w4a8_gemm_lut(A, a, q, gs, 0.5, want_bound=True)
+    assert np.allclose(Y, B, rtol=1e-14) and np.all(Y > 0)
+    q2 = rng.integers(-8, 8, (N, K), dtype=np.int8)
+    Y2, B2 = oracle.w4a8_gemm_lut(A, a, q2, gs, -0.5, want_bound=True)
+    assert np.all(B2 >= np.abs(Y2)) and np.all(B2 > 0)
+    assert np.array_equal(Y2, oracle.w4a8_gemm_lut(A, a, q2, gs, -0.5))
