@@ -64,6 +64,10 @@ def _load():
     lib.fqo_w4a8_gemm_lut.restype = ctypes.c_int
     lib.fqo_w4a8_gemm_lut.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
                                       ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.fqo_kv4_scores.restype = ctypes.c_int
+    lib.fqo_kv4_scores.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
+    lib.fqo_kv4_output.restype = ctypes.c_int
+    lib.fqo_kv4_output.argtypes = [u8p, f32p, i8p, u8p, f64p, f64p, ctypes.c_int, ctypes.c_int, ctypes.c_int]
     lib.fqo_w4a8_gemm_swiglu.restype = ctypes.c_int
     lib.fqo_w4a8_gemm_swiglu.argtypes = [u8p, f32p, i8p, u8p, ctypes.c_float, f64p, f64p,
                                          ctypes.c_int, ctypes.c_int, ctypes.c_int]
@@ -327,3 +331,45 @@ def bf16_ulp_array(Y: np.ndarray) -> np.ndarray:
     out = np.empty(flat.shape, dtype=np.float64)
     _load().fqo_bf16_ulp_array(_ptr(flat, ctypes.c_double), _ptr(out, ctypes.c_double), flat.size)
     return out.reshape(np.shape(Y))
+
+
+def kv4_scores(Q, q_scale, Kq, k_scale, out_scale, want_bound: bool = False):
+    """FP64 attention scores of FP8 queries against an INT4 key cache with one E4M3 scale per token (Sec. 3.2.1):
+    ``S[h,r,t] = out_scale * q_scale[h,r] * e4m3(k_scale[h,t]) * sum_c e4m3(Q[h,r,c]) * Kq[h,t,c]``.
+    Q uint8 [H,R,128], q_scale float32 [H,R], Kq int8 [H,T,128], k_scale uint8 [H,T]."""
+    Q = _c(Q, np.uint8); q_scale = _c(q_scale, np.float32); Kq = _c(Kq, np.int8); k_scale = _c(k_scale, np.uint8)
+    H, R, D = Q.shape
+    T = Kq.shape[1]
+    if D != 128 or Kq.shape != (H, T, 128) or q_scale.shape != (H, R) or k_scale.shape != (H, T):
+        raise ValueError("operand shapes do not match")
+    if Kq.size and (Kq.min() < -8 or Kq.max() > 7):
+        raise ValueError("INT4 codes out of range")
+    S = np.zeros((H, R, T), dtype=np.float64)
+    B = np.zeros((H, R, T), dtype=np.float64) if want_bound else None
+    rc = _load().fqo_kv4_scores(_ptr(Q, ctypes.c_uint8), _ptr(q_scale, ctypes.c_float), _ptr(Kq, ctypes.c_int8),
+                                _ptr(k_scale, ctypes.c_uint8), ctypes.c_float(float(np.float32(out_scale))),
+                                _ptr(S, ctypes.c_double),
+                                _ptr(B, ctypes.c_double) if want_bound else ctypes.POINTER(ctypes.c_double)(), H, R, T)
+    if rc != 0:
+        raise ValueError("fqo_kv4_scores failed with %d" % rc)
+    return (S, B) if want_bound else S
+
+
+def kv4_output(P, p_scale, Vq, v_scale, want_bound: bool = False):
+    """FP64 attention output of FP8 probabilities against an INT4 value cache with one E4M3 scale per token:
+    ``O[h,r,c] = p_scale[h,r] * sum_t e4m3(P[h,r,t]) * e4m3(v_scale[h,t]) * Vq[h,t,c]``.
+    P uint8 [H,R,T], p_scale float32 [H,R], Vq int8 [H,T,128], v_scale uint8 [H,T]."""
+    P = _c(P, np.uint8); p_scale = _c(p_scale, np.float32); Vq = _c(Vq, np.int8); v_scale = _c(v_scale, np.uint8)
+    H, R, T = P.shape
+    if Vq.shape != (H, T, 128) or p_scale.shape != (H, R) or v_scale.shape != (H, T):
+        raise ValueError("operand shapes do not match")
+    if Vq.size and (Vq.min() < -8 or Vq.max() > 7):
+        raise ValueError("INT4 codes out of range")
+    O = np.zeros((H, R, 128), dtype=np.float64)
+    B = np.zeros((H, R, 128), dtype=np.float64) if want_bound else None
+    rc = _load().fqo_kv4_output(_ptr(P, ctypes.c_uint8), _ptr(p_scale, ctypes.c_float), _ptr(Vq, ctypes.c_int8),
+                                _ptr(v_scale, ctypes.c_uint8), _ptr(O, ctypes.c_double),
+                                _ptr(B, ctypes.c_double) if want_bound else ctypes.POINTER(ctypes.c_double)(), H, R, T)
+    if rc != 0:
+        raise ValueError("fqo_kv4_output failed with %d" % rc)
+    return (O, B) if want_bound else O

@@ -524,3 +524,78 @@ int fqo_num_threads(void)
     return 1;
 #endif
 }
+
+/* ---------------------------------------------------------------------------------------
+ * Attention operands with an INT4 key/value cache and FP8 queries (Sec. 3.2.1: queries are
+ * FP8, keys and values INT4, quantised per token -- each row, one token of one head, has its own
+ * scaling factor sigma; Sec. 2.1: those factors are FP8, like the weights'; Sec. 3.1.1: the
+ * INT4 x FP8 product also computes S = Q K^T and O = P V).  Heads are 128 wide, so a token's
+ * row of one head is exactly one quantisation group.  For every head h (an independent
+ * problem; "head" here is a key/value head of one sequence, R the query rows that attend
+ * to it):
+ *
+ *   S[h,r,t] = out_scale * q_scale[h,r] * dec8(k_scale[h,t]) * sum_c dec8(Q[h,r,c]) * Kq[h,t,c]
+ *   O[h,r,c] = p_scale[h,r] * sum_t dec8(P[h,r,t]) * dec8(v_scale[h,t]) * Vq[h,t,c]
+ *
+ * Q, P: E4M3 codes with one FP32 scale per row (eq. 2); Kq, Vq: INT4 codes -8..7, one int8
+ * each, [H][T][128]; k_scale, v_scale: E4M3 codes [H][T]; out_scale: the 1/sqrt(d) of the
+ * attention scores (any FP32).  Reading: the paper does not say where the per-token factor
+ * of V enters O = P V (its own kernel folds every factor into a rounded FP8 table); here it
+ * multiplies each term exactly, as the group scale does in the linear layers.
+ * B (may be NULL) receives the same sums over absolute values.
+ * ------------------------------------------------------------------------------------- */
+#define FQO_HEAD 128
+
+int fqo_kv4_scores(const uint8_t *Q, const float *q_scale, const int8_t *Kq, const uint8_t *k_scale,
+                   float out_scale, double *S, double *B, int H, int R, int T)
+{
+    if (H < 0 || R < 0 || T < 0)
+        return -1;
+    long hr;
+#pragma omp parallel for schedule(static)
+    for (hr = 0; hr < (long)H * R; ++hr) {
+        const long h = hr / R;
+        const uint8_t *qrow = Q + (size_t)hr * FQO_HEAD;
+        const double outer = (double)out_scale * (double)q_scale[hr];
+        for (int t = 0; t < T; ++t) {
+            const int8_t *krow = Kq + ((size_t)h * T + (size_t)t) * FQO_HEAD;
+            double dot = 0.0, adot = 0.0;
+            for (int c = 0; c < FQO_HEAD; ++c) {
+                const double term = fqo_e4m3_decode(qrow[c]) * (double)fqo_int4_decode((uint8_t)krow[c]);
+                dot += term;
+                adot += fabs(term);
+            }
+            const double sigma = fqo_e4m3_decode(k_scale[(size_t)h * T + (size_t)t]);
+            S[(size_t)hr * T + (size_t)t] = outer * (sigma * dot);
+            if (B)
+                B[(size_t)hr * T + (size_t)t] = fabs(outer) * (fabs(sigma) * adot);
+        }
+    }
+    return 0;
+}
+
+int fqo_kv4_output(const uint8_t *P, const float *p_scale, const int8_t *Vq, const uint8_t *v_scale,
+                   double *O, double *B, int H, int R, int T)
+{
+    if (H < 0 || R < 0 || T < 0)
+        return -1;
+    long hr;
+#pragma omp parallel for schedule(static)
+    for (hr = 0; hr < (long)H * R; ++hr) {
+        const long h = hr / R;
+        const uint8_t *prow = P + (size_t)hr * T;
+        for (int c = 0; c < FQO_HEAD; ++c) {
+            double sum = 0.0, asum = 0.0;
+            for (int t = 0; t < T; ++t) {
+                const double term = fqo_e4m3_decode(prow[t]) * fqo_e4m3_decode(v_scale[(size_t)h * T + (size_t)t]) *
+                                    (double)fqo_int4_decode((uint8_t)Vq[((size_t)h * T + (size_t)t) * FQO_HEAD + c]);
+                sum += term;
+                asum += fabs(term);
+            }
+            O[(size_t)hr * FQO_HEAD + c] = (double)p_scale[hr] * sum;
+            if (B)
+                B[(size_t)hr * FQO_HEAD + c] = fabs((double)p_scale[hr]) * asum;
+        }
+    }
+    return 0;
+}
