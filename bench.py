@@ -223,6 +223,44 @@ def main() -> int:
                 "frac_mfma_peak": flop / per[len(per) // 2] / 1e12 / PEAK_FP8_TFLOPS,
                 "rel_frobenius_distance_from_exact_mode": rel}
 
+    def attention_operands(H=128, R=4, T=4096):
+        """Decode attention operands on an INT4 key/value cache (fq_kv4_scores, fq_kv4_output): Llama3-8B, a batch of
+        16 sequences x 8 key/value heads, 4 query heads each, 4096 cached tokens; HBM rate of the algorithmic bytes
+        (packed cache + scales + FP8 operand + bf16 result), 6 rotating copies of the caches."""
+        d = workloads.draw_kv_cache(H, R, T, seed=12)
+        to_bf16 = lambda a: torch.from_numpy(a.view(np.int16)).cuda().view(torch.bfloat16)   # noqa: E731
+        Qc, qs = fq.fq_quantize_act(to_bf16(d["Q_bf16"].reshape(H * R, 128)))
+        Pc, ps = fq.fq_quantize_act(to_bf16(d["P_bf16"].reshape(H * R, T)))
+        Qc, qs, Pc, ps = Qc.view(H, R, 128), qs.view(H, R), Pc.view(H, R, T), ps.view(H, R)
+        copies = 6
+        kps = [fq.fq_kv4_pack(torch.from_numpy(d["Kq"]).cuda(), False) for _ in range(copies)]
+        vps = [fq.fq_kv4_pack(torch.from_numpy(d["Vq"]).cuda(), True) for _ in range(copies)]
+        ks, vs = torch.from_numpy(d["k_scale"]).cuda(), torch.from_numpy(d["v_scale"]).cuda()
+        res = {"H": H, "R": R, "T": T}
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for key, fn, nbytes in (
+                    ("fq_kv4_scores", lambda i: fq.fq_kv4_scores(Qc, qs, kps[i % copies], ks, 128 ** -0.5),
+                     H * T * 64 + H * T + H * R * 128 + 2 * H * R * T),
+                    ("fq_kv4_output", lambda i: fq.fq_kv4_output(Pc, ps, vps[i % copies], vs),
+                     H * T * 64 + H * T + H * R * T + 2 * H * R * 128)):
+                fn(0)
+                side.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    for i in range(copies):
+                        fn(i)
+                _, ev = timed_series(side, g, 10)
+                per = sorted(t / (10 * copies) for t in ev)
+                us = per[len(per) // 2] * 1e6
+                res[key] = {"us": us, "us_best": per[0] * 1e6, "algorithmic_bytes": nbytes, "GBps": nbytes / us / 1e3,
+                            "frac_hbm": nbytes / us / 1e3 / PEAK_HBM_GBPS}
+                del g
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.empty_cache()
+        return res
+
     def offline_quantiser(N, K, reps=20):
         """Mean duration of the three offline stages on a synthetic N x K bf16 matrix (graph replays of
         `reps` calls each) and the HBM rate of their algorithmic bytes."""
@@ -367,6 +405,7 @@ def main() -> int:
             torch.cuda.empty_cache()
         out["other_configs"] = others
         out["table_mode"] = table_mode(name)
+        out["attention_operands"] = attention_operands()
         # the offline step that produces the weight operands, on the gate/up matrix of the same model
         out["offline_quantiser"] = offline_quantiser(11008, 4096)
 

@@ -238,6 +238,43 @@ int fq_quantize_weights(const uint16_t *W_bf16, const float *lambda, int n_pts, 
                         int8_t *q, uint8_t *w_gscale, int N, int K, void *stream);
 
 /*
+ * Attention operands with an INT4 key/value cache and FP8 queries ("KV4/Q8", Sec. 3.2.1: queries
+ * FP8, keys and values INT4 quantised per token, each token's row having its own scaling factor;
+ * Sec. 2.1: those factors are FP8; Sec. 3.1.1: the INT4 x FP8 product also computes the attention
+ * scores S = Q K^T and the output O = P V).  Heads are 128 wide: one token of one head is one
+ * quantisation group.  A "head" below is one key/value head of one sequence, an independent
+ * problem; R is the number of query rows that attend to it (grouped-query heads, batch rows).
+ *
+ *   S[h,r,t] = bf16( out_scale * q_scale[h,r] * e4m3(k_scale[h,t]) * sum_c e4m3(Q[h,r,c]) * Kq[h,t,c] )
+ *   O[h,r,c] = bf16( p_scale[h,r] * sum_t e4m3(P[h,r,t]) * e4m3(v_scale[h,t]) * Vq[h,t,c] )
+ *
+ * Both are exact up to FP32 accumulation and one rounding to bf16: in S the token's factor
+ * multiplies the finished FP32 sum; in O it sits on the summation index, and the kernel forms
+ * P * sigma (at most 8 significant bits) and q exactly as bf16 operands of the matrix cores.
+ *
+ *   fq_kv4_pack      codes [H][T][128] int8 (INT4 codes -8..7, low four bits read) -> the packed
+ *                    cache, fq_kv4_packed_bytes(H, T, values) bytes, 16-byte aligned.  values = 0:
+ *                    a key cache (read by fq_kv4_scores), values != 0: a value cache (stored
+ *                    transposed, tokens padded to a multiple of 128; read by fq_kv4_output).
+ *                    fq_kv4_unpack is the exact inverse.
+ *   fq_kv4_scores    Q_fp8 [H][R][128] E4M3 codes (16-byte aligned), q_scale [H][R] FP32,
+ *                    k_scale [H][T] E4M3 codes (finite), out_scale FP32 (the 1/sqrt(128) of the
+ *                    scores, or any factor), S_bf16 [H][R][T].  R <= 64.
+ *   fq_kv4_output    P_fp8 [H][R][ldp] E4M3 codes, the first T of each row used (ldp >= T),
+ *                    p_scale [H][R] FP32, v_scale [H][T], O_bf16 [H][R][128].  R <= 32, T >= 1.
+ * H <= 65535.  Status codes as above; a zero H, R (or T for the scores) is a successful no-op.
+ */
+size_t fq_kv4_packed_bytes(int H, int T, int values);
+int fq_kv4_pack(const int8_t *codes, uint8_t *packed, int H, int T, int values, void *stream);
+int fq_kv4_unpack(const uint8_t *packed, int8_t *codes, int H, int T, int values, void *stream);
+int fq_kv4_scores(const uint8_t *Q_fp8, const float *q_scale, const uint8_t *K_packed,
+                  const uint8_t *k_scale, float out_scale, uint16_t *S_bf16,
+                  int H, int R, int T, void *stream);
+int fq_kv4_output(const uint8_t *P_fp8, const float *p_scale, const uint8_t *V_packed,
+                  const uint8_t *v_scale, uint16_t *O_bf16, int H, int R, int T, int ldp,
+                  void *stream);
+
+/*
  * Diagnostics (used by the tests; no kernel is launched).
  *
  * fq_w4a8_gemm_plan: how fq_w4a8_gemm_ws would run an M x N x K problem on a device with `cus`

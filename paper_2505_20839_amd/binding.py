@@ -42,6 +42,16 @@ def lib() -> ctypes.CDLL:
     L.fq_w4a8_gemm_static_max_workspace.argtypes = []
     L.fq_w4a8_gemm_lut.restype = ci
     L.fq_w4a8_gemm_lut.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
+    L.fq_kv4_packed_bytes.restype = ctypes.c_size_t
+    L.fq_kv4_packed_bytes.argtypes = [ci, ci, ci]
+    L.fq_kv4_pack.restype = ci
+    L.fq_kv4_pack.argtypes = [vp, vp, ci, ci, ci, vp]
+    L.fq_kv4_unpack.restype = ci
+    L.fq_kv4_unpack.argtypes = [vp, vp, ci, ci, ci, vp]
+    L.fq_kv4_scores.restype = ci
+    L.fq_kv4_scores.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp]
+    L.fq_kv4_output.restype = ci
+    L.fq_kv4_output.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, vp]
     L.fq_w4a8_gemm_ws.restype = ci
     L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
     L.fq_w4a8_gemm_add_ws.restype = ci
@@ -391,3 +401,62 @@ def fq_w4a8_gemm_lut(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Te
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_lut")
     return out
+
+
+def fq_kv4_pack(codes: torch.Tensor, values: bool) -> torch.Tensor:
+    """int8 [H,T,128] INT4 codes of a key (values=False) or value (values=True) cache -> the packed cache."""
+    codes = _dev(codes, torch.int8, "codes")
+    H, T, D = codes.shape
+    if D != GROUP:
+        raise FireqError(-2, "fq_kv4_pack")
+    out = torch.empty((lib().fq_kv4_packed_bytes(H, T, 1 if values else 0),), dtype=torch.uint8, device=codes.device)
+    rc = lib().fq_kv4_pack(codes.data_ptr(), out.data_ptr(), H, T, 1 if values else 0, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_kv4_pack")
+    return out
+
+
+def fq_kv4_unpack(packed: torch.Tensor, H: int, T: int, values: bool) -> torch.Tensor:
+    packed = _dev(packed, torch.uint8, "packed")
+    if packed.numel() < lib().fq_kv4_packed_bytes(H, T, 1 if values else 0):
+        raise FireqError(-2, "fq_kv4_unpack")
+    out = torch.empty((H, T, GROUP), dtype=torch.int8, device=packed.device)
+    rc = lib().fq_kv4_unpack(packed.data_ptr(), out.data_ptr(), H, T, 1 if values else 0, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_kv4_unpack")
+    return out
+
+
+def fq_kv4_scores(Q: torch.Tensor, q_scale: torch.Tensor, K_packed: torch.Tensor, k_scale: torch.Tensor,
+                  out_scale: float) -> torch.Tensor:
+    """S[H,R,T] (bf16): FP8 queries [H,R,128] against a packed INT4 key cache with E4M3 scales [H,T]."""
+    Q = _dev(Q, torch.uint8, "Q"); q_scale = _dev(q_scale, torch.float32, "q_scale")
+    K_packed = _dev(K_packed, torch.uint8, "K_packed"); k_scale = _dev(k_scale, torch.uint8, "k_scale")
+    H, R, D = Q.shape
+    T = k_scale.shape[1]
+    if D != GROUP or tuple(q_scale.shape) != (H, R) or k_scale.shape[0] != H \
+            or K_packed.numel() < lib().fq_kv4_packed_bytes(H, T, 0):
+        raise FireqError(-2, "fq_kv4_scores")
+    S = torch.empty((H, R, T), dtype=torch.bfloat16, device=Q.device)
+    rc = lib().fq_kv4_scores(Q.data_ptr(), q_scale.data_ptr(), K_packed.data_ptr(), k_scale.data_ptr(),
+                             ctypes.c_float(float(out_scale)), S.data_ptr(), H, R, T, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_kv4_scores")
+    return S
+
+
+def fq_kv4_output(P: torch.Tensor, p_scale: torch.Tensor, V_packed: torch.Tensor, v_scale: torch.Tensor) -> torch.Tensor:
+    """O[H,R,128] (bf16): FP8 probabilities [H,R,T] against a packed INT4 value cache with E4M3 scales [H,T]."""
+    P = _dev(P, torch.uint8, "P"); p_scale = _dev(p_scale, torch.float32, "p_scale")
+    V_packed = _dev(V_packed, torch.uint8, "V_packed"); v_scale = _dev(v_scale, torch.uint8, "v_scale")
+    H, R, ldp = P.shape
+    T = v_scale.shape[1]
+    if tuple(p_scale.shape) != (H, R) or v_scale.shape[0] != H or ldp < T \
+            or V_packed.numel() < lib().fq_kv4_packed_bytes(H, T, 1):
+        raise FireqError(-2, "fq_kv4_output")
+    O = torch.empty((H, R, GROUP), dtype=torch.bfloat16, device=P.device)
+    rc = lib().fq_kv4_output(P.data_ptr(), p_scale.data_ptr(), V_packed.data_ptr(), v_scale.data_ptr(), O.data_ptr(),
+                             H, R, T, ldp, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_kv4_output")
+    return O

@@ -316,6 +316,54 @@ int fq_w4a8_gemm_lut(const uint8_t* A_fp8, const float* a_scale, const uint8_t* 
     return after_launch();
 }
 
+size_t fq_kv4_packed_bytes(int H, int T, int values) {
+    if (H <= 0 || T <= 0) return 0;
+    return (size_t)H * (values ? fq_kv4_value_bytes(T) : fq_kv4_key_bytes(T));
+}
+
+int fq_kv4_pack(const int8_t* codes, uint8_t* packed, int H, int T, int values, void* stream) {
+    if (H < 0 || T < 0) return FQ_ERR_SHAPE;
+    if (H == 0 || T == 0) return FQ_OK;
+    if (!codes || !packed) return FQ_ERR_NULL;
+    if (!aligned16(packed)) return FQ_ERR_ALIGN;
+    if (fq_kv4_packed_bytes(1, T, values) >= 0xFFFFFF00ull || H > 65535) return FQ_ERR_SHAPE;
+    fq_launch_kv4_pack(codes, packed, H, T, values != 0, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_kv4_unpack(const uint8_t* packed, int8_t* codes, int H, int T, int values, void* stream) {
+    if (H < 0 || T < 0) return FQ_ERR_SHAPE;
+    if (H == 0 || T == 0) return FQ_OK;
+    if (!codes || !packed) return FQ_ERR_NULL;
+    if (!aligned16(packed)) return FQ_ERR_ALIGN;
+    if (fq_kv4_packed_bytes(1, T, values) >= 0xFFFFFF00ull || H > 65535) return FQ_ERR_SHAPE;
+    fq_launch_kv4_unpack(packed, codes, H, T, values != 0, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_kv4_scores(const uint8_t* Q_fp8, const float* q_scale, const uint8_t* K_packed, const uint8_t* k_scale,
+                  float out_scale, uint16_t* S_bf16, int H, int R, int T, void* stream) {
+    if (H < 0 || R < 0 || T < 0 || R > 64 || H > 65535) return FQ_ERR_SHAPE;
+    if (H == 0 || R == 0 || T == 0) return FQ_OK;
+    if (!Q_fp8 || !q_scale || !K_packed || !k_scale || !S_bf16) return FQ_ERR_NULL;
+    if (!aligned16(Q_fp8) || !aligned16(K_packed)) return FQ_ERR_ALIGN;
+    if (fq_kv4_key_bytes(T) >= 0xFFFFFF00ull) return FQ_ERR_SHAPE;
+    fq_launch_kv4_scores(Q_fp8, q_scale, K_packed, k_scale, out_scale, S_bf16, H, R, T, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
+int fq_kv4_output(const uint8_t* P_fp8, const float* p_scale, const uint8_t* V_packed, const uint8_t* v_scale,
+                  uint16_t* O_bf16, int H, int R, int T, int ldp, void* stream) {
+    if (H < 0 || R < 0 || T < 0 || R > 32 || ldp < T) return FQ_ERR_SHAPE;
+    if (H == 0 || R == 0) return FQ_OK;
+    if (T == 0) return FQ_ERR_SHAPE;                      // an empty sum: nothing to attend to
+    if (!P_fp8 || !p_scale || !V_packed || !v_scale || !O_bf16) return FQ_ERR_NULL;
+    if (!aligned16(V_packed)) return FQ_ERR_ALIGN;
+    if (fq_kv4_value_bytes(T) >= 0xFFFFFF00ull) return FQ_ERR_SHAPE;
+    fq_launch_kv4_output(P_fp8, p_scale, V_packed, v_scale, O_bf16, H, R, T, ldp, static_cast<hipStream_t>(stream));
+    return after_launch();
+}
+
 size_t fq_w4a8_gemm_static_max_workspace(void) { return FQ_STATIC_SCRATCH_BYTES; }
 
 int fq_w4a8_gemm_static(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,

@@ -79,3 +79,14 @@ void fq_launch_quantize_weights(const uint16_t* W, const float* lambda, int n_pt
 // to sink (fq_stream_read_blocks() words).
 unsigned fq_stream_read_blocks();
 void fq_launch_stream_read(const void* src, size_t bytes, unsigned* sink, hipStream_t stream);
+
+// Attention operands with an INT4 key/value cache (fq_kv4.hip).  codes: [H][T][128] int8; packed: per head
+// fq_kv4_key_bytes(T) / fq_kv4_value_bytes(T) bytes; scales: [H][T] E4M3 codes.
+size_t fq_kv4_key_bytes(int T);
+size_t fq_kv4_value_bytes(int T);
+void fq_launch_kv4_pack(const int8_t* codes, uint8_t* packed, int H, int T, bool values, hipStream_t stream);
+void fq_launch_kv4_unpack(const uint8_t* packed, int8_t* codes, int H, int T, bool values, hipStream_t stream);
+void fq_launch_kv4_scores(const uint8_t* Q, const float* q_scale, const uint8_t* kp, const uint8_t* ks, float out_scale,
+                          uint16_t* S, int H, int R, int T, hipStream_t stream);
+void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                          int H, int R, int T, int ldp, hipStream_t stream);

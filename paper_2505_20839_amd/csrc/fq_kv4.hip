@@ -1,0 +1,267 @@
+// Attention operands with an INT4 key/value cache and FP8 queries (Sec. 3.2.1: queries FP8, keys and
+// values INT4 with one scaling factor per token; Sec. 2.1: those factors are FP8; Sec. 3.1.1: the
+// INT4 x FP8 product also forms S = Q K^T and O = P V).  Heads are 128 wide, so one token of one head is
+// exactly one quantisation group, and both caches are kept in the packed layout of the linear layers
+// (fq_common.h), one matrix per head:
+//     keys    N = tokens (padded to 32), K = 128 head dimensions   (one group per token)
+//     values  N = 128 head dimensions,   K = tokens (padded to 128, padding = code of q = 0)
+// so that in both products the contraction index runs along the 32 consecutive codes a lane holds.
+//
+// Scores: the M <= 16 GEMM's arithmetic with a single group -- unpack to E4M3 (mask and shift; the
+// zero point of 8 comes out again through one more MFMA against a constant operand, computed once per
+// query tile), v_mfma_f32_16x16x128_f8f6f4, and the token's scale applied in FP32 to the finished sum.
+// Output: the token's scale sits on the contraction index, so it cannot multiply a finished sum.  It is
+// applied exactly all the same: P[r,t] * sigma[t] has at most 8 significant bits and q at most 4, both
+// are exact bf16 numbers, and v_mfma_f32_16x16x32_bf16 forms exact products and adds them in FP32.
+#include "fq_common.h"
+#include "fq_kernels.h"
+
+#define FQK_HEAD 128
+#define FQK_OOB 0xFFFFFF00u
+
+namespace {
+
+typedef __bf16 fqk_v8bf __attribute__((ext_vector_type(8)));
+
+// packed-cache bytes of one head
+__host__ __device__ inline size_t fqk_key_bytes(int T) { return (size_t)((T + 31) / 32) * 32u * (FQK_HEAD / 2); }
+__host__ __device__ inline size_t fqk_value_bytes(int T) { return (size_t)FQK_HEAD * (size_t)((T + 127) / 128 * 128) / 2u; }
+
+// One thread per packed byte.  VALUES = false: weight matrix row n = token, column k = dimension;
+// VALUES = true: row n = dimension, column k = token (tokens past T hold q = 0).
+template <bool VALUES>
+__global__ __launch_bounds__(256) void fqk_pack_kernel(const int8_t* __restrict__ codes, uint8_t* __restrict__ packed,
+                                                       int T, size_t per_head) {
+    const size_t idx = (size_t)blockIdx.x * 256u + threadIdx.x;
+    if (idx >= per_head) return;
+    const int h = blockIdx.y;
+    const int8_t* src = codes + (size_t)h * T * FQK_HEAD;
+    const int G = VALUES ? (T + 127) / 128 : 1;
+    const size_t blk = idx >> 11;
+    const int in = (int)(idx & 2047u);
+    const int nt = (int)(blk / (size_t)G), g = (int)(blk % (size_t)G);
+    const int hh = in >> 10, lane = (in >> 4) & 63, ij = in & 15;
+    const int n = nt * 32 + (lane & 31);
+    const int k_lo = g * FQ_GROUP + 64 * hh + 32 * (lane >> 5) + ij, k_hi = k_lo + 16;
+    unsigned lo = VALUES ? 8 : 0, hi = lo;                // padding: q = 0 along the sum over tokens; keys as fq_pack_weights pads
+    if (VALUES) {                                         // n = dimension (always < 128), k = token
+        if (k_lo < T) lo = fq_code_from_q(src[(size_t)k_lo * FQK_HEAD + n]);
+        if (k_hi < T) hi = fq_code_from_q(src[(size_t)k_hi * FQK_HEAD + n]);
+    } else if (n < T) {                                   // n = token, k = dimension
+        lo = fq_code_from_q(src[(size_t)n * FQK_HEAD + k_lo]);
+        hi = fq_code_from_q(src[(size_t)n * FQK_HEAD + k_hi]);
+    }
+    packed[(size_t)h * per_head + idx] = (uint8_t)(lo | (hi << 4));
+}
+
+template <bool VALUES>
+__global__ __launch_bounds__(256) void fqk_unpack_kernel(const uint8_t* __restrict__ packed, int8_t* __restrict__ codes,
+                                                         int T, size_t per_head) {
+    const size_t idx = (size_t)blockIdx.x * 256u + threadIdx.x;   // element (t, c) of the head
+    if (idx >= (size_t)T * FQK_HEAD) return;
+    const int h = blockIdx.y;
+    const int t = (int)(idx / FQK_HEAD), c = (int)(idx % FQK_HEAD);
+    int hi;
+    const size_t off = VALUES ? fq_weight_byte(c, t, (T + 127) / 128, &hi) : fq_weight_byte(t, c, 1, &hi);
+    const unsigned byte = packed[(size_t)h * per_head + off];
+    codes[(size_t)h * T * FQK_HEAD + idx] = (int8_t)fq_q_from_code(hi ? (byte >> 4) : (byte & 0xFu));
+}
+
+#define FQ_MFMA16(a, b, c) __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4((a), (b), (c), 0, 0, 0, 0, 0, 0)
+
+__device__ __forceinline__ fq_v8i fqk_join(fq_v4i lo, fq_v4i hi) {
+    fq_v8i r;
+    r[0] = lo[0]; r[1] = lo[1]; r[2] = lo[2]; r[3] = lo[3];
+    r[4] = hi[0]; r[5] = hi[1]; r[6] = hi[2]; r[7] = hi[3];
+    return r;
+}
+
+// ---- S = Q K^T ------------------------------------------------------------------------------------------
+// grid (token chunks, heads); a workgroup of 4 waves covers 4 * NSUB * 16 tokens, wave w the sub-tiles
+// w * NSUB .. of 16 tokens each.  Lane l = 16 * kq + r holds, of the A operand, dimensions 32 kq .. of query
+// row r, and of the B operand the same dimensions of token r of the sub-tile: one 16-byte chunk of the
+// packed cache.  MT row tiles of 16 queries share every unpacked operand.
+#define FQK_S_NSUB 4
+template <int MT>
+__global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
+    const uint8_t* __restrict__ Q, const float* __restrict__ q_scale, const uint8_t* __restrict__ kp,
+    const uint8_t* __restrict__ ks, float out_scale, uint16_t* __restrict__ S, int R, int T) {
+    const int h = blockIdx.y;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r16 = lane & 15, kq = lane >> 4;
+    const int t_first = (blockIdx.x * 4 + wave) * (FQK_S_NSUB * 16);
+    if (t_first >= T) return;
+    const size_t kbytes = fqk_key_bytes(T);
+    const __amdgpu_buffer_rsrc_t rsK = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(kp) + (size_t)h * kbytes, 0, (int)kbytes, 0x00020000);
+    // all of this wave's cache chunks are requested before anything else (streamed once: non-temporal)
+    fq_v4i bq[FQK_S_NSUB];
+    float sig[FQK_S_NSUB];
+#pragma unroll
+    for (int j = 0; j < FQK_S_NSUB; ++j) {
+        const int t = t_first + 16 * j + r16;
+        const unsigned off = t < T ? (unsigned)(t >> 5) * 2048u + (unsigned)(kq >> 1) * 1024u +
+                                     (unsigned)((kq & 1) * 32 + (t & 31)) * 16u
+                                   : FQK_OOB;
+        bq[j] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsK, off, 0, 2));
+        sig[j] = t < T ? fq_e4m3_to_float(ks[(size_t)h * T + t]) : 0.f;
+    }
+    fq_v8i a[MT];
+    fq_v4f c0[MT];
+    float rs[MT][4];
+    fq_v8i zp;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) zp[r] = (int)FQ_ZP_BYTES;
+    const fq_v4f zero4 = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int m = 0; m < MT; ++m) {
+        const int row = 16 * m + r16;
+        const fq_v4i* qrow = reinterpret_cast<const fq_v4i*>(Q + ((size_t)h * R + (row < R ? row : R - 1)) * FQK_HEAD + 32 * kq);
+        a[m] = fqk_join(qrow[0], qrow[1]);
+        c0[m] = FQ_MFMA16(a[m], zp, zero4);               // -2^-6 * sum_c Q[r, c] in every column
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                     // output rows of this lane: 16 m + 4 kq + i
+            const int orow = 16 * m + 4 * kq + i;
+            rs[m][i] = q_scale[(size_t)h * R + (orow < R ? orow : R - 1)] * (out_scale * 512.0f);   // codes were fed in units of 2^-9
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < FQK_S_NSUB; ++j) {
+        const fq_v8i b = fq_unpack_chunk(bq[j]);
+        const int t = t_first + 16 * j + r16;             // this lane's output column
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            const fq_v4f p = FQ_MFMA16(a[m], b, c0[m]);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int orow = 16 * m + 4 * kq + i;
+                if (orow < R && t < T) {
+                    const fq_v2f pr = {(sig[j] * p[i]) * rs[m][i], 0.f};
+                    const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+                    S[((size_t)h * R + orow) * T + t] = __builtin_bit_cast(unsigned short, pk[0]);
+                }
+            }
+        }
+    }
+}
+
+// ---- O = P V --------------------------------------------------------------------------------------------
+// One workgroup of 4 waves per head; wave w takes the 32-token blocks w, w + 4, ...; the four partial results
+// are added through LDS.  Per block: A' = bf16(P * sigma) for (16 query rows) x (32 tokens) -- lane
+// l = 16 * kq + r holds tokens 8 kq .. 8 kq + 7 of row r -- and, for each of the 8 tiles of 16 dimensions,
+// B = bf16(q) for (32 tokens) x (16 dimensions): lane l holds tokens 8 kq .. of dimension l % 16, which are
+// 8 nibbles of one 16-byte chunk of the packed cache (chunk: 32 consecutive tokens of one dimension; low
+// nibbles of bytes 0-7 are tokens 0-7, of bytes 8-15 tokens 8-15, the high nibbles tokens 16-31).
+template <int MT>
+__global__ __launch_bounds__(256) void fq_kv4_output_kernel(
+    const uint8_t* __restrict__ P, const float* __restrict__ p_scale, const uint8_t* __restrict__ vp,
+    const uint8_t* __restrict__ vs, uint16_t* __restrict__ O, int R, int T, int ldp) {
+    __shared__ float red[4][MT][8][4][64];
+    const int h = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r16 = lane & 15, kq = lane >> 4;
+    const int G = (T + 127) / 128;                        // 128-token groups of the packed value cache
+    const size_t vbytes = fqk_value_bytes(T);
+    const __amdgpu_buffer_rsrc_t rsV = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(vp) + (size_t)h * vbytes, 0, (int)vbytes, 0x00020000);
+    fq_v4f acc[MT][8];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int d = 0; d < 8; ++d) acc[m][d] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
+    const int nblocks = (T + 31) / 32;
+    for (int blk = wave; blk < nblocks; blk += 4) {
+        const int t0 = 32 * blk + 8 * kq;                 // this lane's first token of the block
+        // the 8 dimension tiles' codes: 8 bytes of chunk (group blk / 4, half, kh, dimension)
+        fq_v2i vq[8];
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            const int dim = 16 * d + r16;
+            const int g = blk >> 2, hh = (blk >> 1) & 1, kh = blk & 1;
+            const unsigned off = ((unsigned)(dim >> 5) * (unsigned)G + (unsigned)g) * 2048u + (unsigned)hh * 1024u +
+                                 (unsigned)(kh * 32 + (dim & 31)) * 16u + (unsigned)(kq & 1) * 8u;
+            vq[d] = __builtin_bit_cast(fq_v2i, __builtin_amdgcn_raw_buffer_load_b64(rsV, off, 0, 2));
+        }
+        // sigma of the lane's 8 tokens (zero past T), as FP32
+        float sg[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sg[j] = (t0 + j < T) ? fq_e4m3_to_float(vs[(size_t)h * T + t0 + j]) : 0.f;
+        fqk_v8bf a[MT];
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            const int row = 16 * m + r16;
+            const uint8_t* prow = P + ((size_t)h * R + (row < R ? row : R - 1)) * ldp + t0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                // P * sigma: at most 8 significant bits, exact in FP32 and in bf16 (tokens past T: sigma = 0)
+                const float pv = (t0 + j < T) ? fq_e4m3_to_float(prow[j]) : 0.f;
+                a[m][j] = __builtin_bit_cast(__bf16, (unsigned short)(__float_as_uint(pv * sg[j]) >> 16));
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < 8; ++d) {
+            fqk_v8bf b;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const unsigned word = (unsigned)vq[d][j >> 2];
+                const unsigned byte = (word >> (8 * (j & 3))) & 0xFFu;
+                const unsigned code = (kq & 2) ? (byte >> 4) : (byte & 0xFu);
+                b[j] = __builtin_bit_cast(__bf16, (unsigned short)(__float_as_uint((float)((int)code - 8)) >> 16));
+            }
+#pragma unroll
+            for (int m = 0; m < MT; ++m) acc[m][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], b, acc[m][d], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int d = 0; d < 8; ++d)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[wave][m][d][i][lane] = acc[m][d][i];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < MT * 8 * 4 * 64; idx += 256) {
+        const int l = idx & 63, i = (idx >> 6) & 3, d = (idx >> 8) & 7, m = idx >> 11;
+        const int row = 16 * m + 4 * (l >> 4) + i, dim = 16 * d + (l & 15);
+        if (row < R) {
+            const float v = (red[0][m][d][i][l] + red[1][m][d][i][l]) + (red[2][m][d][i][l] + red[3][m][d][i][l]);
+            const fq_v2f pr = {v * p_scale[(size_t)h * R + row], 0.f};
+            const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+            O[((size_t)h * R + row) * FQK_HEAD + dim] = __builtin_bit_cast(unsigned short, pk[0]);
+        }
+    }
+}
+
+}  // namespace
+
+size_t fq_kv4_key_bytes(int T) { return fqk_key_bytes(T); }
+size_t fq_kv4_value_bytes(int T) { return fqk_value_bytes(T); }
+
+void fq_launch_kv4_pack(const int8_t* codes, uint8_t* packed, int H, int T, bool values, hipStream_t stream) {
+    const size_t per_head = values ? fqk_value_bytes(T) : fqk_key_bytes(T);
+    const dim3 grid((unsigned)((per_head + 255u) / 256u), (unsigned)H);
+    if (values) hipLaunchKernelGGL(fqk_pack_kernel<true>, grid, dim3(256), 0, stream, codes, packed, T, per_head);
+    else        hipLaunchKernelGGL(fqk_pack_kernel<false>, grid, dim3(256), 0, stream, codes, packed, T, per_head);
+}
+
+void fq_launch_kv4_unpack(const uint8_t* packed, int8_t* codes, int H, int T, bool values, hipStream_t stream) {
+    const size_t per_head = values ? fqk_value_bytes(T) : fqk_key_bytes(T);
+    const dim3 grid((unsigned)(((size_t)T * FQK_HEAD + 255u) / 256u), (unsigned)H);
+    if (values) hipLaunchKernelGGL(fqk_unpack_kernel<true>, grid, dim3(256), 0, stream, packed, codes, T, per_head);
+    else        hipLaunchKernelGGL(fqk_unpack_kernel<false>, grid, dim3(256), 0, stream, packed, codes, T, per_head);
+}
+
+void fq_launch_kv4_scores(const uint8_t* Q, const float* q_scale, const uint8_t* kp, const uint8_t* ks, float out_scale,
+                          uint16_t* S, int H, int R, int T, hipStream_t stream) {
+    const dim3 grid((unsigned)((T + 4 * FQK_S_NSUB * 16 - 1) / (4 * FQK_S_NSUB * 16)), (unsigned)H);
+    switch ((R + 15) / 16) {
+        case 1: hipLaunchKernelGGL(fq_kv4_scores_kernel<1>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
+        case 2: hipLaunchKernelGGL(fq_kv4_scores_kernel<2>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
+        case 3: hipLaunchKernelGGL(fq_kv4_scores_kernel<3>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
+        default: hipLaunchKernelGGL(fq_kv4_scores_kernel<4>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
+    }
+}
+
+void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                          int H, int R, int T, int ldp, hipStream_t stream) {
+    const dim3 grid((unsigned)H);
+    if (R <= 16) hipLaunchKernelGGL(fq_kv4_output_kernel<1>, grid, dim3(256), 0, stream, P, p_scale, vp, vs, O, R, T, ldp);
+    else         hipLaunchKernelGGL(fq_kv4_output_kernel<2>, grid, dim3(256), 0, stream, P, p_scale, vp, vs, O, R, T, ldp);
+}

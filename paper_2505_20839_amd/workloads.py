@@ -137,3 +137,25 @@ def draw_workload(name: str, rows: Optional[int] = None):
     w = WORKLOADS[name]
     return draw(w.M, w.N, w.K, seed=w.seed, act=w.act, outlier_frac=w.outlier_frac,
                 gs_lo=w.gs_lo, gs_hi=w.gs_hi, w_tscale=w.w_tscale, rows=rows)
+
+
+def draw_kv_cache(H: int, R: int, T: int, *, seed: int):
+    """Operands of decode attention with an INT4 key/value cache (Sec. 3.2.1): shapes and value distributions only.
+
+    H key/value heads of width 128 (Llama heads), R query rows per head, T cached tokens.  Returns
+      Q_bf16, P_bf16  uint16 [H,R,128] / [H,R,T]  queries N(0,1) and attention probabilities (softmax of N(0, 2^2)
+                      logits) before their FP8 quantisation (bf16 bit patterns)
+      Kq, Vq          int8 [H,T,128]  INT4 codes, uniform on -8..7
+      k_scale, v_scale uint8 [H,T]    E4M3 codes of U[0.02, 0.2] draws (one per token)
+    """
+    rng = np.random.default_rng([seed, 0xA77])
+    Q = rng.standard_normal((H, R, GROUP), dtype=np.float32)
+    logits = 2.0 * rng.standard_normal((H, R, T), dtype=np.float32)
+    P = np.exp(logits - logits.max(axis=2, keepdims=True))
+    P /= P.sum(axis=2, keepdims=True)
+    Kq = rng.integers(-8, 8, size=(H, T, GROUP), dtype=np.int8)
+    Vq = rng.integers(-8, 8, size=(H, T, GROUP), dtype=np.int8)
+    ks = rng.uniform(0.02, 0.2, size=(H, T)).astype(np.float32)
+    vs = rng.uniform(0.02, 0.2, size=(H, T)).astype(np.float32)
+    return {"Q_bf16": f32_to_bf16_bits(Q), "P_bf16": f32_to_bf16_bits(P.astype(np.float32)), "Kq": Kq, "Vq": Vq,
+            "k_scale": f32_to_e4m3_codes(ks), "v_scale": f32_to_e4m3_codes(vs)}

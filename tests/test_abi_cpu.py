@@ -26,7 +26,8 @@ def test_library_exports_every_declared_symbol():
                             "fq_w4a8_linear_ws", "fq_w4a8_linear_workspace_bytes",
                             "fq_w4a8_gemm_plan", "fq_test_force_kernel",
                             "fq_w4a8_gemm_static", "fq_w4a8_gemm_static_max_workspace",
-                            "fq_diag_stream_read", "fq_diag_stream_read_sink_bytes", "fq_w4a8_gemm_lut"])
+                            "fq_diag_stream_read", "fq_diag_stream_read_sink_bytes", "fq_w4a8_gemm_lut",
+                            "fq_kv4_packed_bytes", "fq_kv4_pack", "fq_kv4_unpack", "fq_kv4_scores", "fq_kv4_output"])
     for name in names:
         assert hasattr(L, name), name
     assert os.path.samefile(L._name, build.LIB_PATH)
