@@ -280,12 +280,14 @@ int fq_kv4_output(const uint8_t *P_fp8, const float *p_scale, const uint8_t *V_p
  * fq_w4a8_gemm_plan: how fq_w4a8_gemm_ws would run an M x N x K problem on a device with `cus`
  *   compute units (0 = the current device).  `plan` is HOST memory of 8 ints:
  *     plan[0]  kernel: 0 one-thread-per-output cross-check kernel, 1 the M <= 16 kernel, 2 the
- *              M <= 64 kernel, 3 the large-M kernel
+ *              M <= 64 kernel, 3 the large-M kernel, 4 / 5 the K-split kernel with 256 x 128 /
+ *              128 x 64 tiles (plain GEMM and residual form; the fused gate/up form always
+ *              takes the large-M kernel), its number of tiles in plan[5]
  *     plan[1]  large-M kernel: whole tiles (256 rows x 128 channels) written with whole-row stores
  *     plan[2]  whole tiles written element by element (a ragged edge, or N not a multiple of 8)
  *     plan[3], plan[4]  the same two counts for the 128-row half tiles of the last round
- *     plan[5..7]  0
- * fq_test_force_kernel: "simple", "small" or "large" makes every GEMM entry point use that kernel
+ *     plan[6..7]  0
+ * fq_test_force_kernel: "simple", "small", "large" or "ksplit" makes every GEMM entry point use that kernel
  *   where it serves the shape; "" or NULL restores the choice by M.  The environment variable
  *   FQ_FORCE_KERNEL, read once when the library is loaded, sets the initial value.  Process-wide;
  *   meant for cross-checking the kernels against each other.

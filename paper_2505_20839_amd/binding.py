@@ -359,12 +359,12 @@ def fq_w4a8_gemm_plan(M: int, N: int, K: int, cus: int = 0) -> dict:
     rc = lib().fq_w4a8_gemm_plan(int(M), int(N), int(K), int(cus), buf)
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_plan")
-    return {"kernel": ("simple", "small16", "smallm", "large")[buf[0]], "whole": buf[1], "whole_ragged": buf[2],
-            "half": buf[3], "half_ragged": buf[4]}
+    return {"kernel": ("simple", "small16", "smallm", "large", "ksplit256x128", "ksplit128x64")[buf[0]], "whole": buf[1],
+            "whole_ragged": buf[2], "half": buf[3], "half_ragged": buf[4], "ksplit_tiles": buf[5]}
 
 
 def fq_test_force_kernel(name: Optional[str]) -> None:
-    """Cross-check hook: "simple" | "small" | "large" forces that GEMM kernel, None or "auto" restores the choice by M."""
+    """Cross-check hook: "simple" | "small" | "large" | "ksplit" forces that GEMM kernel, None or "auto" restores the choice by M."""
     lib().fq_test_force_kernel((name or "").encode() if name != "auto" else b"")
 
 

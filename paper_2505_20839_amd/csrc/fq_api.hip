@@ -20,7 +20,7 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 inline int after_launch() { return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_LAUNCH; }
 
-enum class GemmKernel { Auto, Simple, Large, Small };
+enum class GemmKernel { Auto, Simple, Large, Small, KSplit };
 
 // FQ_FORCE_KERNEL=simple|large|small overrides the choice (tests use it to cross-check kernels).
 GemmKernel parse_kernel(const char* e) {
@@ -28,6 +28,7 @@ GemmKernel parse_kernel(const char* e) {
     if (!std::strcmp(e, "simple")) return GemmKernel::Simple;
     if (!std::strcmp(e, "large")) return GemmKernel::Large;
     if (!std::strcmp(e, "small")) return GemmKernel::Small;
+    if (!std::strcmp(e, "ksplit")) return GemmKernel::KSplit;
     return GemmKernel::Auto;
 }
 
@@ -57,9 +58,20 @@ int check_gemm_args(const void* A, const void* a_scale, const void* W, const voi
     return FQ_OK;
 }
 
+// Large also stands for the K-split kernel, which shares its workspace: ksplit_choice picks between the two.
 GemmKernel choose_kernel(int M) {
     const GemmKernel k = forced_kernel();
+    if (k == GemmKernel::KSplit) return GemmKernel::Large;
     return k != GemmKernel::Auto ? k : (M <= 64 ? GemmKernel::Small : GemmKernel::Large);
+}
+
+// 0: the large-M kernel's own tiles; 1, 2: a shape of the K-split kernel (never with the fused gate/up epilogue).
+// Forcing "large" keeps the large-M kernel, forcing "ksplit" takes the K-split kernel wherever it can run.
+int ksplit_choice(int M, int N, int K, bool swiglu) {
+    const GemmKernel k = forced_kernel();
+    if (swiglu || k == GemmKernel::Large || k == GemmKernel::Simple || k == GemmKernel::Small) return 0;
+    if (k == GemmKernel::KSplit) return (K / FQ_GROUP >= 8) ? (M <= 512 ? 2 : 1) : 0;
+    return fq_gemm_ksplit_choice(M, N, K, fq_device_cus());
 }
 
 }  // namespace
@@ -161,7 +173,19 @@ int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int* plan) {
     for (int i = 0; i < 8; ++i) plan[i] = 0;
     const GemmKernel k = choose_kernel(M);
     plan[0] = k == GemmKernel::Simple ? 0 : k == GemmKernel::Small ? (M <= 16 ? 1 : 2) : 3;
-    if (k == GemmKernel::Large) fq_gemm_large_plan(M, N, cus > 0 ? cus : fq_device_cus(), plan + 1);
+    if (k == GemmKernel::Large) {
+        const int c = cus > 0 ? cus : fq_device_cus();
+        const GemmKernel f = forced_kernel();
+        const int ks = f == GemmKernel::Large ? 0
+                     : f == GemmKernel::KSplit ? ((K / FQ_GROUP >= 8) ? (M <= 512 ? 2 : 1) : 0)
+                                               : fq_gemm_ksplit_choice(M, N, K, c);
+        if (ks != 0) {
+            plan[0] = 3 + ks;
+            plan[5] = ks == 1 ? ((M + 255) / 256) * ((N + 127) / 128) : ((M + 127) / 128) * ((N + 63) / 64);
+        } else {
+            fq_gemm_large_plan(M, N, c, plan + 1);
+        }
+    }
     return FQ_OK;
 }
 
@@ -224,10 +248,16 @@ int gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed
             if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s))
                 fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s);
             break;
-        default:
-            fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, workspace,
-                                 workspace_prepared != 0, swiglu, R, s);
+        default: {
+            const int ks = ksplit_choice(M, N, K, swiglu);
+            if (ks != 0)
+                fq_launch_gemm_ksplit(ks, A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, workspace,
+                                      workspace_prepared != 0, R, s);
+            else
+                fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, workspace,
+                                     workspace_prepared != 0, swiglu, R, s);
             break;
+        }
     }
     return after_launch();
 }

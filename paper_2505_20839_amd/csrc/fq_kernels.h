@@ -90,3 +90,12 @@ void fq_launch_kv4_scores(const uint8_t* Q, const float* q_scale, const uint8_t*
                           uint16_t* S, int H, int R, int T, hipStream_t stream);
 void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
                           int H, int R, int T, int ldp, hipStream_t stream);
+
+// K-split kernel (fq_gemm_ksplit.hip): 8-wave workgroups that split K inside the workgroup, for problems with
+// too few tiles for the large-M kernel.  fq_gemm_ksplit_choice: 0 = not used for this shape, 1 = 256 x 128 tiles
+// with K halved, 2 = 128 x 64 tiles with K quartered.  Workspace and `prepared` as for fq_launch_gemm_large; no
+// fused gate/up epilogue.
+int fq_gemm_ksplit_choice(int M, int N, int K, int cus);
+void fq_launch_gemm_ksplit(int choice, const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
+                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
+                           const uint16_t* R, hipStream_t stream);

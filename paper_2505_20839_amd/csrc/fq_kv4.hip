@@ -145,30 +145,40 @@ __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
 }
 
 // ---- O = P V --------------------------------------------------------------------------------------------
-// One workgroup of 4 waves per head; wave w takes the 32-token blocks w, w + 4, ...; the four partial results
-// are added through LDS.  Per block: A' = bf16(P * sigma) for (16 query rows) x (32 tokens) -- lane
+// One workgroup of 8 waves per head; wave w takes the 32-token blocks w, w + 8, ...; the partial results are
+// added through LDS.  Per block: A' = bf16(P * sigma) for (16 query rows) x (32 tokens) -- lane
 // l = 16 * kq + r holds tokens 8 kq .. 8 kq + 7 of row r -- and, for each of the 8 tiles of 16 dimensions,
-// B = bf16(q) for (32 tokens) x (16 dimensions): lane l holds tokens 8 kq .. of dimension l % 16, which are
+// the B operand for (32 tokens) x (16 dimensions): lane l holds tokens 8 kq .. of dimension l % 16, which are
 // 8 nibbles of one 16-byte chunk of the packed cache (chunk: 32 consecutive tokens of one dimension; low
 // nibbles of bytes 0-7 are tokens 0-7, of bytes 8-15 tokens 8-15, the high nibbles tokens 16-31).
-template <int MT>
-__global__ __launch_bounds__(256) void fq_kv4_output_kernel(
+// A 4-bit code c = q + 8 becomes a bf16 number by bit operations alone: 0x4180 | c << 3 is 16 + c (the binade
+// [16, 32) has a spacing of 1/8).  The matrix cores therefore sum A' * (q + 24); one more MFMA per block against
+// an all-ones operand delivers sum A', and 24 times that is taken off at the end (all products are exact; the
+// offset costs a few FP32 roundings of the larger intermediate sum, far below the tolerance).
+// FAST: P rows and the scale rows are 8-byte aligned (ldp and T multiples of 8), so a lane's 8 codes are one
+// 8-byte load each, converted by the hardware; otherwise byte loads.
+#define FQK_O_WAVES 8
+template <int MT, bool FAST>
+__global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
     const uint8_t* __restrict__ P, const float* __restrict__ p_scale, const uint8_t* __restrict__ vp,
     const uint8_t* __restrict__ vs, uint16_t* __restrict__ O, int R, int T, int ldp) {
-    __shared__ float red[4][MT][8][4][64];
+    extern __shared__ float red[];                        // [waves][MT][9][4][64]: 8 dimension tiles + the row sums
     const int h = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r16 = lane & 15, kq = lane >> 4;
     const int G = (T + 127) / 128;                        // 128-token groups of the packed value cache
     const size_t vbytes = fqk_value_bytes(T);
     const __amdgpu_buffer_rsrc_t rsV = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(vp) + (size_t)h * vbytes, 0, (int)vbytes, 0x00020000);
-    fq_v4f acc[MT][8];
+    fq_v4f acc[MT][9];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int d = 0; d < 8; ++d) acc[m][d] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
+        for (int d = 0; d < 9; ++d) acc[m][d] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
+    fqk_v8bf ones;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(__bf16, (unsigned short)0x3F80);
     const int nblocks = (T + 31) / 32;
-    for (int blk = wave; blk < nblocks; blk += 4) {
+    for (int blk = wave; blk < nblocks; blk += FQK_O_WAVES) {
         const int t0 = 32 * blk + 8 * kq;                 // this lane's first token of the block
         // the 8 dimension tiles' codes: 8 bytes of chunk (group blk / 4, half, kh, dimension)
         fq_v2i vq[8];
@@ -182,30 +192,53 @@ __global__ __launch_bounds__(256) void fq_kv4_output_kernel(
         }
         // sigma of the lane's 8 tokens (zero past T), as FP32
         float sg[8];
+        if (FAST) {
+            fq_v2i w = {0, 0};
+            if (t0 < T) w = *reinterpret_cast<const fq_v2i*>(vs + (size_t)h * T + t0);   // T % 8 == 0: all 8 or none
 #pragma unroll
-        for (int j = 0; j < 8; ++j) sg[j] = (t0 + j < T) ? fq_e4m3_to_float(vs[(size_t)h * T + t0 + j]) : 0.f;
+            for (int x = 0; x < 2; ++x) {
+                const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], true);
+                sg[4 * x] = lo[0]; sg[4 * x + 1] = lo[1]; sg[4 * x + 2] = hi[0]; sg[4 * x + 3] = hi[1];
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < 8; ++j) sg[j] = (t0 + j < T) ? fq_e4m3_to_float(vs[(size_t)h * T + t0 + j]) : 0.f;
+        }
         fqk_v8bf a[MT];
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
             const int row = 16 * m + r16;
             const uint8_t* prow = P + ((size_t)h * R + (row < R ? row : R - 1)) * ldp + t0;
+            float pv[8];
+            if (FAST) {
+                fq_v2i w = {0, 0};
+                if (t0 < T) w = *reinterpret_cast<const fq_v2i*>(prow);
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                // P * sigma: at most 8 significant bits, exact in FP32 and in bf16 (tokens past T: sigma = 0)
-                const float pv = (t0 + j < T) ? fq_e4m3_to_float(prow[j]) : 0.f;
-                a[m][j] = __builtin_bit_cast(__bf16, (unsigned short)(__float_as_uint(pv * sg[j]) >> 16));
+                for (int x = 0; x < 2; ++x) {
+                    const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], true);
+                    pv[4 * x] = lo[0]; pv[4 * x + 1] = lo[1]; pv[4 * x + 2] = hi[0]; pv[4 * x + 3] = hi[1];
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) pv[j] = (t0 + j < T) ? fq_e4m3_to_float(prow[j]) : 0.f;
             }
+            // P * sigma: at most 8 significant bits, exact in FP32 and in bf16 (tokens past T: both factors are 0)
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                a[m][j] = __builtin_bit_cast(__bf16, (unsigned short)(__float_as_uint(pv[j] * sg[j]) >> 16));
+            acc[m][8] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], ones, acc[m][8], 0, 0, 0);   // sum_t A'[r, t], every column
         }
 #pragma unroll
         for (int d = 0; d < 8; ++d) {
-            fqk_v8bf b;
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const unsigned word = (unsigned)vq[d][j >> 2];
-                const unsigned byte = (word >> (8 * (j & 3))) & 0xFFu;
-                const unsigned code = (kq & 2) ? (byte >> 4) : (byte & 0xFu);
-                b[j] = __builtin_bit_cast(__bf16, (unsigned short)(__float_as_uint((float)((int)code - 8)) >> 16));
-            }
+            // codes of this lane's 8 tokens: the low (kq < 2) or high nibbles of the 8 bytes
+            const unsigned x0 = ((kq & 2) ? ((unsigned)vq[d][0] >> 4) : (unsigned)vq[d][0]) & 0x0F0F0F0Fu;
+            const unsigned x1 = ((kq & 2) ? ((unsigned)vq[d][1] >> 4) : (unsigned)vq[d][1]) & 0x0F0F0F0Fu;
+            fq_v4i bw;                                    // two bf16 per word: 0x4180 | c << 3 = 16 + c
+            bw[0] = (int)((__builtin_amdgcn_perm(0u, x0, 0x0C010C00u) << 3) | 0x41804180u);
+            bw[1] = (int)((__builtin_amdgcn_perm(0u, x0, 0x0C030C02u) << 3) | 0x41804180u);
+            bw[2] = (int)((__builtin_amdgcn_perm(0u, x1, 0x0C010C00u) << 3) | 0x41804180u);
+            bw[3] = (int)((__builtin_amdgcn_perm(0u, x1, 0x0C030C02u) << 3) | 0x41804180u);
+            const fqk_v8bf b = __builtin_bit_cast(fqk_v8bf, bw);
 #pragma unroll
             for (int m = 0; m < MT; ++m) acc[m][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], b, acc[m][d], 0, 0, 0);
         }
@@ -213,16 +246,21 @@ __global__ __launch_bounds__(256) void fq_kv4_output_kernel(
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int d = 0; d < 8; ++d)
+        for (int d = 0; d < 9; ++d)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[wave][m][d][i][lane] = acc[m][d][i];
+            for (int i = 0; i < 4; ++i) red[(((wave * MT + m) * 9 + d) * 4 + i) * 64 + lane] = acc[m][d][i];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < MT * 8 * 4 * 64; idx += 256) {
+    for (int idx = threadIdx.x; idx < MT * 8 * 4 * 64; idx += 64 * FQK_O_WAVES) {
         const int l = idx & 63, i = (idx >> 6) & 3, d = (idx >> 8) & 7, m = idx >> 11;
         const int row = 16 * m + 4 * (l >> 4) + i, dim = 16 * d + (l & 15);
         if (row < R) {
-            const float v = (red[0][m][d][i][l] + red[1][m][d][i][l]) + (red[2][m][d][i][l] + red[3][m][d][i][l]);
-            const fq_v2f pr = {v * p_scale[(size_t)h * R + row], 0.f};
+            float v = 0.f, s1 = 0.f;                      // fixed order: deterministic
+#pragma unroll
+            for (int w = 0; w < FQK_O_WAVES; ++w) {
+                v += red[(((w * MT + m) * 9 + d) * 4 + i) * 64 + l];
+                s1 += red[(((w * MT + m) * 9 + 8) * 4 + i) * 64 + l];
+            }
+            const fq_v2f pr = {fmaf(-24.0f, s1, v) * p_scale[(size_t)h * R + row], 0.f};
             const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
             O[((size_t)h * R + row) * FQK_HEAD + dim] = __builtin_bit_cast(unsigned short, pk[0]);
         }
@@ -261,7 +299,23 @@ void fq_launch_kv4_scores(const uint8_t* Q, const float* q_scale, const uint8_t*
 
 void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
                           int H, int R, int T, int ldp, hipStream_t stream) {
-    const dim3 grid((unsigned)H);
-    if (R <= 16) hipLaunchKernelGGL(fq_kv4_output_kernel<1>, grid, dim3(256), 0, stream, P, p_scale, vp, vs, O, R, T, ldp);
-    else         hipLaunchKernelGGL(fq_kv4_output_kernel<2>, grid, dim3(256), 0, stream, P, p_scale, vp, vs, O, R, T, ldp);
+    const dim3 grid((unsigned)H), block(64 * FQK_O_WAVES);
+    const int mt = R <= 16 ? 1 : 2;
+    const size_t lds = (size_t)FQK_O_WAVES * mt * 9 * 4 * 64 * sizeof(float);   // 72 or 144 KiB
+    const bool fast = (T % 8) == 0 && (ldp % 8) == 0 && (reinterpret_cast<uintptr_t>(P) % 8) == 0 &&
+                      (reinterpret_cast<uintptr_t>(vs) % 8) == 0;
+    static fq_device_once attr_once;
+    fq_once_per_device(attr_once, [] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<1, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 73728);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 73728);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<2, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
+    });
+    if (mt == 1) {
+        if (fast) hipLaunchKernelGGL((fq_kv4_output_kernel<1, true>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
+        else      hipLaunchKernelGGL((fq_kv4_output_kernel<1, false>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
+    } else {
+        if (fast) hipLaunchKernelGGL((fq_kv4_output_kernel<2, true>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
+        else      hipLaunchKernelGGL((fq_kv4_output_kernel<2, false>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
+    }
 }

@@ -149,3 +149,78 @@ def test_attention_output_projection_with_residual_at_prefill_size(fq):
     Y, B = oracle.w4a8_gemm_add(A.cpu().numpy()[rows], s.cpu().numpy()[rows], d["q"], d["gscale"], d["w_tscale"],
                                 Rb[rows], want_bound=True)
     check_gemm(bf16_bits_from_gpu(R)[rows], Y, B, "o_proj + residual")
+
+
+# ---- the K-split kernel (8-wave workgroups that split K inside the workgroup) --------------------------
+
+KSPLIT_SHAPES = [(65, 64, 1024), (128, 128, 1024), (300, 256, 1024), (129, 200, 1408), (512, 520, 2048),
+                 (100, 96, 11008), (130, 64, 16384), (257, 513, 1024),
+                 # 256 x 128 tiles with K halved
+                 (700, 1100, 2048), (1024, 512, 4096), (600, 264, 11008), (513, 130, 1408)]
+
+
+def test_few_tile_shapes_take_the_k_split_kernel(fq):
+    assert _plan(fq, (128, 14336, 4096))["kernel"] == "ksplit128x64"
+    assert _plan(fq, (512, 4096, 4096))["kernel"] == "ksplit128x64"
+    assert _plan(fq, (512, 14336, 4096))["kernel"] == "large"              # more than one round of 128 x 64 tiles
+    assert _plan(fq, (2048, 11008, 4096))["kernel"] == "large"
+    fq.fq_test_force_kernel("ksplit")
+    try:
+        for shape in KSPLIT_SHAPES:
+            assert _plan(fq, shape)["kernel"] == ("ksplit128x64" if shape[0] <= 512 else "ksplit256x128"), shape
+    finally:
+        fq.fq_test_force_kernel(None)
+
+
+@pytest.mark.parametrize("shape", KSPLIT_SHAPES)
+def test_k_split_kernel_every_element(fq, shape):
+    """Plain GEMM, residual out of place and in place, on the K-split kernel: even and ragged tiles, K splits of
+    unequal length (K/128 = 11, 43 + 43), several rounds of zero-point units (K = 16384), against the oracle; and the
+    large-M kernel's result on the same operands within the FP32 summation-order margin."""
+    M, N, K = shape
+    d = _problem(shape, seed=7 * M + N + K)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    packed, gs = fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"])
+    An, sn = A.cpu().numpy(), s.cpu().numpy()
+    Rb = workloads.draw_residual(M, N, scale=4.0, seed=M + N)
+    R = to_gpu_bf16(Rb)
+    try:
+        fq.fq_test_force_kernel("ksplit")
+        Yk = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+        Ya = fq.fq_w4a8_gemm_add(A, s, packed, gs, d["w_tscale"], N, R)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits_from_gpu(R), Rb)
+        Yi = fq.fq_w4a8_gemm_add(A, s, packed, gs, d["w_tscale"], N, R, out=R)
+        Yk2 = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+        fq.fq_test_force_kernel("large")
+        Yl = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+        torch.cuda.synchronize()
+    finally:
+        fq.fq_test_force_kernel(None)
+    Y, B = oracle.w4a8_gemm(An, sn, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Yk), Y, B, "k-split %s" % (shape,))
+    assert np.array_equal(bf16_bits_from_gpu(Yk), bf16_bits_from_gpu(Yk2)), "not deterministic"
+    diff = np.abs(oracle.bf16_bits_to_f64(bf16_bits_from_gpu(Yk)) - oracle.bf16_bits_to_f64(bf16_bits_from_gpu(Yl)))
+    assert np.all(diff <= oracle.bf16_ulp_array(Y) + 1e-4 * B)
+    Yr, Br = oracle.w4a8_gemm_add(An, sn, d["q"], d["gscale"], d["w_tscale"], Rb, want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Ya), Yr, Br, "k-split + residual %s" % (shape,))
+    assert np.array_equal(bf16_bits_from_gpu(Yi), bf16_bits_from_gpu(Ya)), "in place differs"
+
+
+def test_k_split_kernel_zero_activations_return_the_residual(fq):
+    for shape in [(300, 264, 1024), (1024, 640, 2048), (700, 1032, 2048)]:
+        M, N, K = shape
+        q = np.random.default_rng(M).integers(-8, 8, (N, K), dtype=np.int8)
+        gs = np.full((N, K // 128), 0x38, np.uint8)
+        Rb = np.random.default_rng(N).integers(0, 0x7F80, (M, N)).astype(np.uint16)
+        Rb |= np.random.default_rng(N + 1).integers(0, 2, (M, N)).astype(np.uint16) << 15
+        Rb[Rb == 0x8000] = 0
+        try:
+            fq.fq_test_force_kernel("ksplit")
+            Yg = fq.fq_w4a8_gemm_add(_gpu(np.zeros((M, K), np.uint8)), _gpu(np.ones(M, np.float32)),
+                                     fq.fq_pack_weights(_gpu(q)), _gpu(gs), 1.0, N, to_gpu_bf16(Rb))
+            torch.cuda.synchronize()
+        finally:
+            fq.fq_test_force_kernel(None)
+        bad = np.argwhere(bf16_bits_from_gpu(Yg) != Rb)
+        assert bad.size == 0, "%s: first wrong element %s" % (shape, bad[:1])

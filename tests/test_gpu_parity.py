@@ -217,7 +217,12 @@ def test_gemm_invariants_on_gpu(fq, kernel_choice):
     _, B = oracle.w4a8_gemm(A[5:6], a[5:6], q, gs, t, want_bound=True)
     assert np.all(d <= oracle.bf16_ulp_array(oracle.bf16_bits_to_f64(Y1)[5]) + 1e-4 * B[0])
     kernel_choice("auto")
-    assert np.array_equal(_run_gemm(fq, A, a, q, gs, t), Y1)
+    # the kernel chosen by shape (for this one the K-split kernel): the same sums in another FP32 order
+    Yauto = _run_gemm(fq, A, a, q, gs, t)
+    _, Bf = oracle.w4a8_gemm(A, a, q, gs, t, want_bound=True)
+    assert np.all(np.abs(oracle.bf16_bits_to_f64(Yauto) - oracle.bf16_bits_to_f64(Y1))
+                  <= oracle.bf16_ulp_array(oracle.bf16_bits_to_f64(Y1)) + 1e-4 * Bf)
+    assert np.array_equal(_run_gemm(fq, A, a, q, gs, t), Yauto)
 
 
 def test_own_workspace_and_callers_workspace_agree(fq):
