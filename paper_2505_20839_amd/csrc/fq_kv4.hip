@@ -145,8 +145,9 @@ __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
 }
 
 // ---- O = P V --------------------------------------------------------------------------------------------
-// One workgroup of 8 waves per head; wave w takes the 32-token blocks w, w + 8, ...; the partial results are
-// added through LDS.  Per block: A' = bf16(P * sigma) for (16 query rows) x (32 tokens) -- lane
+// A workgroup of 8 waves per head and slice of DT of the 8 dimension tiles (grid: heads x 8 / DT; fewer tiles per
+// workgroup when there are few heads, so that the grid still covers the chip); wave w takes the 32-token blocks
+// w, w + 8, ...; the partial results are added through LDS.  Per block: A' = bf16(P * sigma) for (16 query rows) x (32 tokens) -- lane
 // l = 16 * kq + r holds tokens 8 kq .. 8 kq + 7 of row r -- and, for each of the 8 tiles of 16 dimensions,
 // the B operand for (32 tokens) x (16 dimensions): lane l holds tokens 8 kq .. of dimension l % 16, which are
 // 8 nibbles of one 16-byte chunk of the packed cache (chunk: 32 consecutive tokens of one dimension; low
@@ -158,22 +159,23 @@ __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
 // FAST: P rows and the scale rows are 8-byte aligned (ldp and T multiples of 8), so a lane's 8 codes are one
 // 8-byte load each, converted by the hardware; otherwise byte loads.
 #define FQK_O_WAVES 8
-template <int MT, bool FAST>
+template <int MT, bool FAST, int DT>
 __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
     const uint8_t* __restrict__ P, const float* __restrict__ p_scale, const uint8_t* __restrict__ vp,
     const uint8_t* __restrict__ vs, uint16_t* __restrict__ O, int R, int T, int ldp) {
-    extern __shared__ float red[];                        // [waves][MT][9][4][64]: 8 dimension tiles + the row sums
+    extern __shared__ float red[];                        // [waves][MT][DT + 1][4][64]: DT dimension tiles + the row sums
+    const int d0 = blockIdx.y * DT;                       // first dimension tile of this workgroup
     const int h = blockIdx.x;
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r16 = lane & 15, kq = lane >> 4;
     const int G = (T + 127) / 128;                        // 128-token groups of the packed value cache
     const size_t vbytes = fqk_value_bytes(T);
     const __amdgpu_buffer_rsrc_t rsV = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(vp) + (size_t)h * vbytes, 0, (int)vbytes, 0x00020000);
-    fq_v4f acc[MT][9];
+    fq_v4f acc[MT][DT + 1];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int d = 0; d < 9; ++d) acc[m][d] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
+        for (int d = 0; d < DT + 1; ++d) acc[m][d] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
     fqk_v8bf ones;
 #pragma unroll
     for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(__bf16, (unsigned short)0x3F80);
@@ -181,10 +183,10 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
     for (int blk = wave; blk < nblocks; blk += FQK_O_WAVES) {
         const int t0 = 32 * blk + 8 * kq;                 // this lane's first token of the block
         // the 8 dimension tiles' codes: 8 bytes of chunk (group blk / 4, half, kh, dimension)
-        fq_v2i vq[8];
+        fq_v2i vq[DT];
 #pragma unroll
-        for (int d = 0; d < 8; ++d) {
-            const int dim = 16 * d + r16;
+        for (int d = 0; d < DT; ++d) {
+            const int dim = 16 * (d0 + d) + r16;
             const int g = blk >> 2, hh = (blk >> 1) & 1, kh = blk & 1;
             const unsigned off = ((unsigned)(dim >> 5) * (unsigned)G + (unsigned)g) * 2048u + (unsigned)hh * 1024u +
                                  (unsigned)(kh * 32 + (dim & 31)) * 16u + (unsigned)(kq & 1) * 8u;
@@ -226,10 +228,10 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
 #pragma unroll
             for (int j = 0; j < 8; ++j)
                 a[m][j] = __builtin_bit_cast(__bf16, (unsigned short)(__float_as_uint(pv[j] * sg[j]) >> 16));
-            acc[m][8] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], ones, acc[m][8], 0, 0, 0);   // sum_t A'[r, t], every column
+            acc[m][DT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], ones, acc[m][DT], 0, 0, 0);   // sum_t A'[r, t], every column
         }
 #pragma unroll
-        for (int d = 0; d < 8; ++d) {
+        for (int d = 0; d < DT; ++d) {
             // codes of this lane's 8 tokens: the low (kq < 2) or high nibbles of the 8 bytes
             const unsigned x0 = ((kq & 2) ? ((unsigned)vq[d][0] >> 4) : (unsigned)vq[d][0]) & 0x0F0F0F0Fu;
             const unsigned x1 = ((kq & 2) ? ((unsigned)vq[d][1] >> 4) : (unsigned)vq[d][1]) & 0x0F0F0F0Fu;
@@ -246,19 +248,19 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int d = 0; d < 9; ++d)
+        for (int d = 0; d < DT + 1; ++d)
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[(((wave * MT + m) * 9 + d) * 4 + i) * 64 + lane] = acc[m][d][i];
+            for (int i = 0; i < 4; ++i) red[(((wave * MT + m) * (DT + 1) + d) * 4 + i) * 64 + lane] = acc[m][d][i];
     __syncthreads();
-    for (int idx = threadIdx.x; idx < MT * 8 * 4 * 64; idx += 64 * FQK_O_WAVES) {
-        const int l = idx & 63, i = (idx >> 6) & 3, d = (idx >> 8) & 7, m = idx >> 11;
-        const int row = 16 * m + 4 * (l >> 4) + i, dim = 16 * d + (l & 15);
+    for (int idx = threadIdx.x; idx < MT * DT * 4 * 64; idx += 64 * FQK_O_WAVES) {
+        const int l = idx & 63, i = (idx >> 6) & 3, d = (idx >> 8) % DT, m = (idx >> 8) / DT;
+        const int row = 16 * m + 4 * (l >> 4) + i, dim = 16 * (d0 + d) + (l & 15);
         if (row < R) {
             float v = 0.f, s1 = 0.f;                      // fixed order: deterministic
 #pragma unroll
             for (int w = 0; w < FQK_O_WAVES; ++w) {
-                v += red[(((w * MT + m) * 9 + d) * 4 + i) * 64 + l];
-                s1 += red[(((w * MT + m) * 9 + 8) * 4 + i) * 64 + l];
+                v += red[(((w * MT + m) * (DT + 1) + d) * 4 + i) * 64 + l];
+                s1 += red[(((w * MT + m) * (DT + 1) + DT) * 4 + i) * 64 + l];
             }
             const fq_v2f pr = {fmaf(-24.0f, s1, v) * p_scale[(size_t)h * R + row], 0.f};
             const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
@@ -297,25 +299,45 @@ void fq_launch_kv4_scores(const uint8_t* Q, const float* q_scale, const uint8_t*
     }
 }
 
+namespace {
+
+template <int MT, bool FAST, int DT>
+void fqk_launch_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                       int H, int R, int T, int ldp, hipStream_t stream) {
+    constexpr size_t lds = (size_t)FQK_O_WAVES * MT * (DT + 1) * 4 * 64 * sizeof(float);
+    static fq_device_once attr_once;                      // (one per template instance)
+    fq_once_per_device(attr_once, [] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<MT, FAST, DT>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    hipLaunchKernelGGL((fq_kv4_output_kernel<MT, FAST, DT>), dim3((unsigned)H, 8 / DT), dim3(64 * FQK_O_WAVES), lds, stream,
+                       P, p_scale, vp, vs, O, R, T, ldp);
+}
+
+template <int MT, bool FAST>
+void fqk_launch_output_dt(int dt, const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                          int H, int R, int T, int ldp, hipStream_t stream) {
+    if (dt == 8)      fqk_launch_output<MT, FAST, 8>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else if (dt == 4) fqk_launch_output<MT, FAST, 4>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else if (dt == 2) fqk_launch_output<MT, FAST, 2>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else              fqk_launch_output<MT, FAST, 1>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+}
+
+}  // namespace
+
 void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
                           int H, int R, int T, int ldp, hipStream_t stream) {
-    const dim3 grid((unsigned)H), block(64 * FQK_O_WAVES);
-    const int mt = R <= 16 ? 1 : 2;
-    const size_t lds = (size_t)FQK_O_WAVES * mt * 9 * 4 * 64 * sizeof(float);   // 72 or 144 KiB
     const bool fast = (T % 8) == 0 && (ldp % 8) == 0 && (reinterpret_cast<uintptr_t>(P) % 8) == 0 &&
                       (reinterpret_cast<uintptr_t>(vs) % 8) == 0;
-    static fq_device_once attr_once;
-    fq_once_per_device(attr_once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<1, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 73728);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<1, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 73728);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<2, true>), hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<2, false>), hipFuncAttributeMaxDynamicSharedMemorySize, 147456);
-    });
-    if (mt == 1) {
-        if (fast) hipLaunchKernelGGL((fq_kv4_output_kernel<1, true>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
-        else      hipLaunchKernelGGL((fq_kv4_output_kernel<1, false>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
+    // dimension tiles per workgroup: the most that still give two workgroups per compute unit
+    const int cus = fq_device_cus();
+    int dt = 8;
+    while (dt > 1 && (long)H * (8 / dt) < 2L * cus) dt >>= 1;
+    if (R <= 16) {
+        if (fast) fqk_launch_output_dt<1, true>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+        else      fqk_launch_output_dt<1, false>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
     } else {
-        if (fast) hipLaunchKernelGGL((fq_kv4_output_kernel<2, true>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
-        else      hipLaunchKernelGGL((fq_kv4_output_kernel<2, false>), grid, block, lds, stream, P, p_scale, vp, vs, O, R, T, ldp);
+        if (fast) fqk_launch_output_dt<2, true>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+        else      fqk_launch_output_dt<2, false>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
     }
 }
