@@ -34,22 +34,25 @@ __device__ __forceinline__ int fqw_log2_over_7(unsigned bits) {
 }  // namespace
 
 // ---- channel-wise absmean scaling ------------------------------------------------------------------
-// One workgroup per 32 input channels.  16 lanes cover the 32 channels of a row (a dword = two channels
-// each), so a wave reads 4 rows per instruction and the 4 waves 16; FQW_CAS_UNROLL such loads are in flight
-// per lane.  FP64 sums, combined in a fixed order: the result does not depend on timing.
-#define FQW_CAS_UNROLL 8
-__global__ __launch_bounds__(256) void fq_cas_scales_kernel(const uint16_t* __restrict__ W, float target,
+// One workgroup of 16 waves per 32 input channels (a column sum has to stay inside one workgroup to keep its
+// order fixed without a scratch buffer, so the bytes in flight come from the workgroup's size).  16 lanes cover
+// the 32 channels of a row (a dword = two channels each), so a wave reads 4 rows per instruction and the 16
+// waves 64; FQW_CAS_UNROLL such loads are in flight per lane.  FP64 sums, combined in a fixed order: the result
+// does not depend on timing.
+#define FQW_CAS_UNROLL 16
+#define FQW_CAS_ROWS 64
+__global__ __launch_bounds__(16 * FQW_CAS_ROWS) void fq_cas_scales_kernel(const uint16_t* __restrict__ W, float target,
                                                             float* __restrict__ lambda, int N, int K) {
-    __shared__ double part[16][32];
-    const int sub = threadIdx.x >> 4;                     // which of the 16 rows of a pass
+    __shared__ double part[FQW_CAS_ROWS][32];
+    const int sub = threadIdx.x >> 4;                     // which of the 64 rows of a pass
     const int k = blockIdx.x * 32 + 2 * (threadIdx.x & 15);
     const bool two = k + 1 < K, one = k < K;              // K may be odd: the last channel then loads 2 bytes
     double s0 = 0.0, s1 = 0.0;
-    for (int n0 = sub; n0 < N; n0 += 16 * FQW_CAS_UNROLL) {
+    for (int n0 = sub; n0 < N; n0 += FQW_CAS_ROWS * FQW_CAS_UNROLL) {
         unsigned w[FQW_CAS_UNROLL];
 #pragma unroll
         for (int u = 0; u < FQW_CAS_UNROLL; ++u) {
-            const int n = n0 + 16 * u;
+            const int n = n0 + FQW_CAS_ROWS * u;
             w[u] = 0u;
             if (n < N && one) {
                 const uint16_t* src = W + (size_t)n * K + k;
@@ -70,89 +73,104 @@ __global__ __launch_bounds__(256) void fq_cas_scales_kernel(const uint16_t* __re
     if (threadIdx.x < 32 && blockIdx.x * 32 + (int)threadIdx.x < K) {
         double t = 0.0;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) t += part[r][threadIdx.x];
+        for (int r = 0; r < FQW_CAS_ROWS; ++r) t += part[r][threadIdx.x];
         lambda[blockIdx.x * 32 + threadIdx.x] =
             t == 0.0 ? 1.0f : (float)((double)target / (t / (double)N));            // an all-zero channel keeps 1
     }
 }
 
 // ---- per-tensor scaling: statistics, then the choice of n --------------------------------------------
-// stats[0]: bits of the smallest non-zero |v| (0xFFFFFFFF: none); stats[1..4]: bit n of this 128-bit mask
-// is set when some element lies in the band of condition 2 for that n.
+// stats[0]: bits of the smallest non-zero |v| (0xFFFFFFFF: none); stats[1]: bits of the largest |v| below
+// 7 * 2^6 (0: none) -- the bands of condition 2 are ordered by magnitude, so the lowest band n >= 0 that holds an
+// element is the band of that element.
+#define FQW_BAND0_END 0x43E00000u                         // bits of 448 = 7 * 2^6: at or above it the band index is negative
 __global__ void fq_pts_init_kernel(unsigned* __restrict__ stats) {
     if (threadIdx.x < 8) stats[threadIdx.x] = threadIdx.x == 0 ? 0xFFFFFFFFu : 0u;
-}
-
-__global__ __launch_bounds__(256) void fq_pts_stats_kernel(const uint16_t* __restrict__ W,
-                                                           const float* __restrict__ lambda,
-                                                           unsigned* __restrict__ stats, size_t chunks, int K) {
-    unsigned vmin = 0xFFFFFFFFu;
-    unsigned long long mlo = 0ull, mhi = 0ull;            // bands 0..63 and 64..127
-    const size_t stride = (size_t)gridDim.x * 256u;
-    for (size_t c = (size_t)blockIdx.x * 256u + threadIdx.x; c < chunks; c += stride) {   // 8 weights per chunk
-        const fq_v4i w = *reinterpret_cast<const fq_v4i*>(W + c * 8);
-        const int k0 = (int)((c * 8) % (size_t)K);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const unsigned word = (unsigned)w[i >> 1];
-            float v = fqw_bf16((unsigned short)((i & 1) ? (word >> 16) : (word & 0xFFFFu)));
-            if (lambda) v *= lambda[k0 + i];
-            const unsigned b = __float_as_uint(v) & 0x7FFFFFFFu;
-            if (b != 0u) {
-                vmin = b < vmin ? b : vmin;
-                const int n = 5 - fqw_log2_over_7(b);     // the n whose band holds this element
-                const unsigned long long bit = 1ull << (n & 63);
-                mlo |= (n >= 0 && n < 64) ? bit : 0ull;
-                mhi |= (n >= 64 && n <= 126) ? bit : 0ull;
-            }
-        }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        const unsigned other = (unsigned)__shfl_xor((int)vmin, o, 64);
-        vmin = other < vmin ? other : vmin;
-        mlo |= (unsigned long long)__shfl_xor((long long)mlo, o, 64);
-        mhi |= (unsigned long long)__shfl_xor((long long)mhi, o, 64);
-    }
-    // one set of atomics per workgroup, and only those that would change the statistics (the plain reads
-    // may be stale: that costs at most an atomic that changes nothing): thousands of atomics on five
-    // addresses would otherwise take longer than reading the matrix
-    __shared__ unsigned red[4][5];
-    if ((threadIdx.x & 63) == 0) {
-        unsigned* r = red[threadIdx.x >> 6];
-        r[0] = vmin;
-        r[1] = (unsigned)mlo; r[2] = (unsigned)(mlo >> 32); r[3] = (unsigned)mhi; r[4] = (unsigned)(mhi >> 32);
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        unsigned m0 = red[0][0];
-#pragma unroll
-        for (int w = 1; w < 4; ++w) m0 = red[w][0] < m0 ? red[w][0] : m0;
-        const volatile unsigned* seen = stats;
-        if (m0 < seen[0]) atomicMin(&stats[0], m0);
-#pragma unroll
-        for (int j = 1; j < 5; ++j) {
-            const unsigned m = red[0][j] | red[1][j] | red[2][j] | red[3][j];
-            if (m & ~seen[j]) atomicOr(&stats[j], m);
-        }
-    }
 }
 
 // Condition 1 holds from the n at which the smallest non-zero element reaches 7 * 2^-9 (then no
 // non-zero element adds to S any more, and zeros add the same for every n); condition 2 at the
 // lowest band that holds an element.  n is the smaller of the two, at most 126.
-__global__ void fq_pts_resolve_kernel(const unsigned* __restrict__ stats, int* __restrict__ n_out) {
-    if (threadIdx.x != 0) return;
+__device__ __forceinline__ int fqw_pts_resolve(unsigned vmin, unsigned vmax) {
     int n1 = 0;
-    if (stats[0] != 0xFFFFFFFFu) {
-        n1 = -9 - fqw_log2_over_7(stats[0]);
+    if (vmin != 0xFFFFFFFFu) {
+        n1 = -9 - fqw_log2_over_7(vmin);
         n1 = n1 < 0 ? 0 : n1;
     }
     int n2 = 127;
-    for (int j = 3; j >= 0; --j)
-        if (stats[1 + j]) n2 = 32 * j + __builtin_ctz(stats[1 + j]);
-    int n = n1 < n2 ? n1 : n2;
-    n_out[0] = n > 126 ? 126 : n;
+    if (vmax != 0u) {
+        n2 = 5 - fqw_log2_over_7(vmax);                   // >= 0 by the choice of vmax
+        n2 = n2 > 126 ? 127 : n2;
+    }
+    const int n = n1 < n2 ? n1 : n2;
+    return n > 126 ? 126 : n;
+}
+
+// Thread t works on the 16-byte chunk (8 weights) t % (K / 8) of the rows t / (K / 8), + rows_par, ...: its 8
+// input channels never change, so their lambda sit in registers, and neighbouring threads read neighbouring
+// chunks.  FQW_PTS_UNROLL rows are in flight per thread.
+#define FQW_PTS_UNROLL 4
+__global__ __launch_bounds__(256) void fq_pts_stats_kernel(const uint16_t* __restrict__ W,
+                                                           const float* __restrict__ lambda,
+                                                           unsigned* __restrict__ stats,
+                                                           int N, int K, int rows_par) {
+    unsigned vmin = 0xFFFFFFFFu, vmax = 0u;
+    const int KC = K / 8;
+    const unsigned t = blockIdx.x * 256u + threadIdx.x;
+    const int r0 = (int)(t / (unsigned)KC), cc = (int)(t % (unsigned)KC);
+    float lam[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) lam[i] = lambda ? lambda[8 * cc + i] : 1.0f;
+    for (int n0 = r0; n0 < N && r0 < rows_par; n0 += FQW_PTS_UNROLL * rows_par) {
+        fq_v4i w[FQW_PTS_UNROLL];
+#pragma unroll
+        for (int u = 0; u < FQW_PTS_UNROLL; ++u) {
+            const int n = n0 + u * rows_par;
+            w[u] = (fq_v4i){0, 0, 0, 0};                  // zeros change neither statistic
+            if (n < N) w[u] = *reinterpret_cast<const fq_v4i*>(W + ((size_t)n * KC + cc) * 8);
+        }
+#pragma unroll
+        for (int u = 0; u < FQW_PTS_UNROLL; ++u)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const unsigned word = (unsigned)w[u][i >> 1];
+                float v = fqw_bf16((unsigned short)((i & 1) ? (word >> 16) : (word & 0xFFFFu)));
+                if (lambda) v *= lam[i];
+                const unsigned b = __float_as_uint(v) & 0x7FFFFFFFu;
+                vmin = (b != 0u && b < vmin) ? b : vmin;
+                vmax = (b < FQW_BAND0_END && b > vmax) ? b : vmax;
+            }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const unsigned lo = (unsigned)__shfl_xor((int)vmin, o, 64), hi = (unsigned)__shfl_xor((int)vmax, o, 64);
+        vmin = lo < vmin ? lo : vmin;
+        vmax = hi > vmax ? hi : vmax;
+    }
+    __shared__ unsigned red[4][2];
+    if ((threadIdx.x & 63) == 0) {
+        red[threadIdx.x >> 6][0] = vmin;
+        red[threadIdx.x >> 6][1] = vmax;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        unsigned m0 = red[0][0], m1 = red[0][1];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            m0 = red[w][0] < m0 ? red[w][0] : m0;
+            m1 = red[w][1] > m1 ? red[w][1] : m1;
+        }
+        // only the atomics that would change a statistic (the plain reads may be stale: that costs at most an
+        // atomic that changes nothing): thousands of atomics on two addresses would otherwise take longer than
+        // reading the matrix
+        const volatile unsigned* seen = stats;
+        if (m0 < seen[0]) atomicMin(&stats[0], m0);
+        if (m1 > seen[1]) atomicMax(&stats[1], m1);
+    }
+}
+
+__global__ void fq_pts_resolve_kernel(const unsigned* __restrict__ stats, int* __restrict__ n_out) {
+    if (threadIdx.x == 0) n_out[0] = fqw_pts_resolve(stats[0], stats[1]);
 }
 
 // ---- group-wise INT4 quantisation ------------------------------------------------------------------
@@ -210,16 +228,19 @@ __global__ __launch_bounds__(256) void fq_quantize_weights_kernel(const uint16_t
 }
 
 void fq_launch_cas_scales(const uint16_t* W, float target, float* lambda, int N, int K, hipStream_t stream) {
-    hipLaunchKernelGGL(fq_cas_scales_kernel, dim3((unsigned)((K + 31) / 32)), dim3(256), 0, stream, W, target, lambda, N, K);
+    hipLaunchKernelGGL(fq_cas_scales_kernel, dim3((unsigned)((K + 31) / 32)), dim3(16 * FQW_CAS_ROWS), 0, stream, W, target, lambda, N, K);
 }
 
 void fq_launch_pts_exponent(const uint16_t* W, const float* lambda, int* n_out, int N, int K, hipStream_t stream) {
-    unsigned* stats = reinterpret_cast<unsigned*>(n_out) + 8;     // the caller's 64 bytes: [0] = n, [8..12] statistics
-    const size_t chunks = (size_t)N * (size_t)K / 8u;
-    size_t blocks = (chunks + 255u) / 256u;
-    if (blocks > 2048u) blocks = 2048u;
+    unsigned* stats = reinterpret_cast<unsigned*>(n_out) + 8;     // the caller's 64 bytes: [0] = n, [8..9] statistics
+    // about 512 workgroups' worth of threads (two per compute unit: few enough that their closing atomics stay cheap),
+    // as whole rows of K / 8 chunk columns
+    const int KC = K / 8;
+    int rows_par = (512 * 256 + KC - 1) / KC;
+    if (rows_par > N) rows_par = N;
+    const size_t blocks = ((size_t)KC * (size_t)rows_par + 255u) / 256u;
     hipLaunchKernelGGL(fq_pts_init_kernel, dim3(1), dim3(64), 0, stream, stats);
-    hipLaunchKernelGGL(fq_pts_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, W, lambda, stats, chunks, K);
+    hipLaunchKernelGGL(fq_pts_stats_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, W, lambda, stats, N, K, rows_par);
     hipLaunchKernelGGL(fq_pts_resolve_kernel, dim3(1), dim3(64), 0, stream, stats, n_out);
 }
 
