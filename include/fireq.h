@@ -58,7 +58,9 @@ enum {
  *   Y_bf16     [M,N]  row-major bfloat16 bit patterns (output)
  *
  * For M > 64 the kernels need device scratch (the packed codes carry a zero point, and the
- * term that takes it out again, one number per row of A_fp8 and group, is computed first).
+ * term that takes it out again, one number per row of A_fp8 and group, is computed first; for
+ * 64 < M <= 512 with few output tiles, several workgroups share a tile along K and exchange
+ * their FP32 partial tiles and arrival counters through it as well).
  * fq_w4a8_gemm_ws takes that scratch from the caller: `workspace` is device memory, 16-byte
  * aligned, at least fq_w4a8_gemm_workspace_bytes(M,N,K) bytes (0 = none needed, NULL is fine
  * then); it may be reused or freed once the work enqueued by the call has finished.  With
@@ -83,11 +85,11 @@ int fq_w4a8_gemm(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_p
  * fq_w4a8_gemm for callers that cannot allocate device memory and have none to pass: code under
  * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operands, result
  * and status codes as fq_w4a8_gemm_ws with workspace_prepared = 0, bit for bit; the scratch is a
- * fixed array inside the library's code object (fq_w4a8_gemm_static_max_workspace() bytes, 4 MiB,
+ * fixed array inside the library's code object (fq_w4a8_gemm_static_max_workspace() bytes, 16 MiB,
  * one copy on every GPU the library is loaded on, held until the process ends).  The call
  * allocates nothing (no hipMalloc, hipFree or allocating library routine) and never synchronises.
  * A problem whose fq_w4a8_gemm_workspace_bytes(M,N,K) exceeds that size is refused with
- * FQ_ERR_MEMORY before anything is enqueued (M = 8192 with K = 16384 still fits).  All calls on
+ * FQ_ERR_MEMORY before anything is enqueued (M = 32768 with K = 16384 still fits).  All calls on
  * one GPU share that GPU's array: calls that overlap in time on one GPU (different streams) race
  * on it and give wrong results; calls on one stream, or ordered by events, are fine.  Nothing in
  * the array has to survive or be cleared between calls: each call writes every byte it reads.
@@ -282,11 +284,12 @@ int fq_kv4_output(const uint8_t *P_fp8, const float *p_scale, const uint8_t *V_p
  *     plan[0]  kernel: 0 one-thread-per-output cross-check kernel, 1 the M <= 16 kernel, 2 the
  *              M <= 64 kernel, 3 the large-M kernel, 4 / 5 the K-split kernel with 256 x 128 /
  *              128 x 64 tiles (plain GEMM and residual form; the fused gate/up form always
- *              takes the large-M kernel), its number of tiles in plan[5]
+ *              takes the large-M kernel), its number of tiles in plan[5] and the number of
+ *              workgroups that share a tile along K in plan[6]
  *     plan[1]  large-M kernel: whole tiles (256 rows x 128 channels) written with whole-row stores
  *     plan[2]  whole tiles written element by element (a ragged edge, or N not a multiple of 8)
  *     plan[3], plan[4]  the same two counts for the 128-row half tiles of the last round
- *     plan[6..7]  0
+ *     plan[7]  0
  * fq_test_force_kernel: "simple", "small", "large" or "ksplit" makes every GEMM entry point use that kernel
  *   where it serves the shape; "" or NULL restores the choice by M.  The environment variable
  *   FQ_FORCE_KERNEL, read once when the library is loaded, sets the initial value.  Process-wide;

@@ -360,7 +360,7 @@ def fq_w4a8_gemm_plan(M: int, N: int, K: int, cus: int = 0) -> dict:
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_plan")
     return {"kernel": ("simple", "small16", "smallm", "large", "ksplit256x128", "ksplit128x64")[buf[0]], "whole": buf[1],
-            "whole_ragged": buf[2], "half": buf[3], "half_ragged": buf[4], "ksplit_tiles": buf[5]}
+            "whole_ragged": buf[2], "half": buf[3], "half_ragged": buf[4], "ksplit_tiles": buf[5], "ksplit_slices": buf[6]}
 
 
 def fq_test_force_kernel(name: Optional[str]) -> None:

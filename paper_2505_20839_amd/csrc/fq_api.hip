@@ -11,7 +11,7 @@
 
 // Scratch of fq_w4a8_gemm_static: one array per GPU the library runs on, part of the code object, held
 // until the process ends.  In host code the name is only a handle for hipGetSymbolAddress.
-#define FQ_STATIC_SCRATCH_BYTES (4u << 20)
+#define FQ_STATIC_SCRATCH_BYTES (16u << 20)
 static __device__ __align__(256) unsigned char scratch[FQ_STATIC_SCRATCH_BYTES];
 
 namespace {
@@ -182,6 +182,7 @@ int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int* plan) {
         if (ks != 0) {
             plan[0] = 3 + ks;
             plan[5] = ks == 1 ? ((M + 255) / 256) * ((N + 127) / 128) : ((M + 127) / 128) * ((N + 63) / 64);
+            plan[6] = fq_gemm_ksplit_slices(ks, M, N, K, c);
         } else {
             fq_gemm_large_plan(M, N, c, plan + 1);
         }
@@ -191,7 +192,10 @@ int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int* plan) {
 
 size_t fq_w4a8_gemm_workspace_bytes(int M, int N, int K) {
     if (M <= 0 || N <= 0 || K <= 0 || (K % FQ_GROUP) != 0) return 0;
-    return choose_kernel(M) == GemmKernel::Large ? fq_gemm_large_workspace_bytes(M, K) : 0;
+    if (choose_kernel(M) != GemmKernel::Large) return 0;
+    // (the fused gate/up epilogue never takes the K-split kernel and leaves the partial tiles unused)
+    return fq_gemm_large_workspace_bytes(M, K) +
+           fq_gemm_ksplit_partial_bytes(ksplit_choice(M, N, K, false), M, N, K, fq_device_cus());
 }
 
 int fq_quantize_act_ws(const uint16_t* X_bf16, uint8_t* A_fp8, float* a_scale, int M, int K,

@@ -1,7 +1,8 @@
 // W4A8-FP GEMM for problems with too few output tiles to fill the chip (Sec. 3.1.1; same arithmetic and
 // operand formats as fq_gemm_large.hip): a workgroup of 8 waves owns one tile of 32 * NMT rows x 32 * NW
 // channels and splits K over KS = 8 / NW groups of NW waves.  Each K split streams its own A tiles through
-// its own two LDS stages and its own packed weights, with the main loop of the large-M kernel (two chained
+// its own two LDS stages and its own packed weights (128 x 64 tiles: straight into registers, two groups
+// ahead -- a lane consumes exactly the 32 bytes it loads), with the main loop of the large-M kernel (two chained
 // v_mfma_f32_32x32x64_f8f6f4 per row tile and group, the group scale applied in FP32 to each group's
 // partial sum); the splits' partial tiles are then added through LDS, each wave taking over NMT / KS row
 // tiles, and the zero-point update and the epilogue finish those.  Two shapes are built:
@@ -11,6 +12,15 @@
 //                               prefill), where 128-channel tiles are too few and the small-M kernels
 //                               re-read the activations once per compute unit from L2
 // One workgroup per compute unit (160 KiB of LDS, two waves per SIMD).
+//
+// K slices: when even these tiles are fewer than the compute units, S workgroups share a tile, each taking a
+// contiguous 1/S of the groups (and splitting that among its waves as above).  A workgroup's loop is bound by
+// what one compute unit can pull from L2 (about 110 GB/s measured, and every step of a 128 x 64 tile moves
+// 80 KiB for 8 matrix instructions per wave), so a tile finishes S times sooner.  Each slice writes its folded
+// partial tile (FP32, in the accumulators' own layout) to the workspace and counts itself in; the workgroup that
+// arrives last adds the S partial tiles in the order of the slices -- a fixed order, so the result does not
+// depend on which one that is -- and goes on to the zero-point update and the epilogue; it leaves the counter at
+// zero for the next call.  The S workgroups of a tile run on the same XCD, so the partial tiles stay in its L2.
 #include <type_traits>
 #include "fq_common.h"
 #include "fq_kernels.h"
@@ -28,7 +38,8 @@ struct fqk_cfg {
     static constexpr int BM = 32 * NMT, BN = 32 * NW;
     static constexpr int STG = 8 * BM;                    // 16-byte chunks per A stage
     static constexpr int OUT_STRIDE = BN * 2 + 16;        // bytes per row of the output tile staged in LDS
-    static constexpr int LOOP_LDS = KS * 2 * STG * 16 + FQK_WAVES * 4096;
+    static constexpr bool WREG = NMT <= 4;                // packed weights through registers instead of LDS
+    static constexpr int LOOP_LDS = KS * 2 * STG * 16 + (WREG ? 0 : FQK_WAVES * 4096);
     static constexpr int FOLD_LDS = FQK_WAVES * (NMT / 2 > 0 ? NMT / 2 : 1) * 4096;
     static constexpr int EPI_LDS = BM * OUT_STRIDE + 1024;
     static constexpr int LDS = LOOP_LDS > FOLD_LDS ? (LOOP_LDS > EPI_LDS ? LOOP_LDS : EPI_LDS)
@@ -42,7 +53,8 @@ __global__ __launch_bounds__(FQK_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
 void fq_gemm_ksplit_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K,
-    int tiles_m, int tiles_n, int pm, const uint16_t* __restrict__ planes, const uint16_t* R) {
+    int tiles_m, int tiles_n, int pm, const uint16_t* __restrict__ planes, const uint16_t* R,
+    int S, unsigned* counters, float* partials) {
     typedef fqk_cfg<NMT, NW, KS> cfg;
     constexpr int NT = 4 * NMT / NW;                      // A transfers (8 rows each) per wave and stage
     constexpr int OWN = NMT / KS;                         // row tiles a wave finishes
@@ -52,18 +64,30 @@ void fq_gemm_ksplit_kernel(
     const int nw = wave % NW, kw = wave / NW;             // position along the channels / which K split
     // which tile: XCD x = blockIdx % 8 runs a contiguous range of the tiles, panels of `pm` row tiles, row
     // tile fastest inside a panel, so that the tiles an XCD runs at one time share rows of A and channels of W
-    int m0, n0;
+    // (with K slices: workgroup j of an XCD is slice j % S of the XCD's tile j / S)
+    int m0, n0, tile, slice;
     {
-        const int x = blockIdx.x % FQL_XCDS, j = blockIdx.x / FQL_XCDS;
+        const int x = blockIdx.x % FQL_XCDS, js = blockIdx.x / FQL_XCDS;
+        const int j = js / S;
+        slice = js - j * S;
         const int ntiles = tiles_m * tiles_n, base = ntiles / FQL_XCDS, rem = ntiles % FQL_XCDS;
         if (j >= base + (x < rem ? 1 : 0)) return;
         const int t = x * base + (x < rem ? x : rem) + j;
+        tile = t;
         const int per_panel = pm * tiles_n;
         const int panel = t / per_panel, rest = t - panel * per_panel;
         const int ph = tiles_m - panel * pm < pm ? tiles_m - panel * pm : pm;
         const int tn = rest / ph, tm = panel * pm + (rest - tn * ph);
         m0 = tm * cfg::BM;
         n0 = tn * cfg::BN;
+    }
+    // the output factor of row m0 + threadIdx.x, fetched now so that the epilogue does not wait for it
+    // (x 2^9: the weights are fed in units of 2^-9)
+    static_assert(cfg::BM <= FQK_THREADS, "one row factor per thread");
+    float row_factor = 0.f;
+    if ((int)threadIdx.x < cfg::BM) {
+        const int m = m0 + (int)threadIdx.x;
+        row_factor = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);
     }
     const int nw0 = n0 + nw * 32;                         // first output channel of this wave
     const bool wave_on = nw0 < N;                         // waves past N compute a duplicate tile and store nothing
@@ -81,12 +105,18 @@ void fq_gemm_ksplit_kernel(
         const_cast<uint16_t*>(planes), 0, (int)((unsigned)ZU * (unsigned)M * 16u), 0x00020000);
     const unsigned abase = fql_a_lane_base(nw, lane, K, NT);
     const uint8_t* gsrow = gs + (size_t)(n_ok ? n : N - 1) * G;
-    // this split's groups: [gb, ge); every split runs `gper` steps, the surplus ones as ghosts with scale 0
-    const int gper = (G + KS - 1) / KS;
-    const int gb = kw * gper < G ? kw * gper : G;
-    const int ge = gb + gper < G ? gb + gper : G;
+    // this workgroup's slice of the groups: [sb, se); this split's groups: [gb, ge); every split runs `gper`
+    // steps, the surplus ones as ghosts with scale 0
+    const int sper = (G + S - 1) / S;
+    const int sb = slice * sper < G ? slice * sper : G;
+    const int se = sb + sper < G ? sb + sper : G;
+    const int gper = (se - sb + KS - 1) / KS;
+    const int gb = sb + kw * gper < se ? sb + kw * gper : se;
+    const int ge = gb + gper < se ? gb + gper : se;
     const int glast = G - 1;
     auto gclamp = [&](int j) { const int g = gb + j; return g < ge ? g : (ge > gb ? ge - 1 : glast); };
+    // ghost steps request their operands out of range: zeros arrive at once and nothing is fetched
+    auto ghost = [&](int j) { return gb + j < ge ? 0u : FQL_OOB; };
 
     const int r32 = lane & 31, sw = (r32 >> 1) & 7;
     const int o00 = r32 * 8 + ((2 * (lane >> 5)) ^ sw);
@@ -104,17 +134,30 @@ void fq_gemm_ksplit_kernel(
     // ---- prologue ----
     fq_v4i* stages = lds + kw * (2 * cfg::STG);           // this split's two A stages
     fq_v4i* wbuf = lds + KS * 2 * cfg::STG + wave * 256;  // this wave's two weight buffers
-    fql_issue_a<NT>(rsA, abase, m0, K, stages, nw, gclamp(0));
-    fql_issue_b(rsW, wbuf, lane16, wblk + (unsigned)gclamp(0) * 2048u);
-    fql_issue_b(rsW, wbuf + 128, lane16, wblk + (unsigned)gclamp(1) * 2048u);
+    // (both A stages are free at the start: the second group's tile travels with the first instead of one step later)
+    fq_v4i wraw[2][2];                                    // (WREG) the packed weights of the next two groups
+    auto load_w = [&](int slot, int j) __attribute__((always_inline)) {
+        const unsigned off = wblk + (unsigned)gclamp(j) * 2048u;
+        wraw[slot][0] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsW, lane16 | ghost(j), off, 0));
+        wraw[slot][1] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsW, lane16 | ghost(j), off + 1024u, 0));
+    };
+    fql_issue_a<NT>(rsA, abase, m0, K, stages, nw, gclamp(0), ghost(0));
+    if (cfg::WREG) {
+        load_w(0, 0);
+        load_w(1, 1);
+    } else {
+        fql_issue_b(rsW, wbuf, lane16 | ghost(0), wblk + (unsigned)gclamp(0) * 2048u);
+        fql_issue_b(rsW, wbuf + 128, lane16 | ghost(1), wblk + (unsigned)gclamp(1) * 2048u);
+    }
+    fql_issue_a<NT>(rsA, abase, m0, K, stages + cfg::STG, nw, gclamp(1), ghost(1));
     unsigned psb[2];
     psb[0] = gsrow[gclamp(0)];
     psb[1] = gsrow[gclamp(1)];
     fq_v8i b0[2], b1[2];
     float sc[2];
     __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
-    b0[0] = fq_unpack_chunk(wbuf[lane]);
-    b1[0] = fq_unpack_chunk(wbuf[64 + lane]);
+    b0[0] = fq_unpack_chunk(cfg::WREG ? wraw[0][0] : wbuf[lane]);
+    b1[0] = fq_unpack_chunk(cfg::WREG ? wraw[0][1] : wbuf[64 + lane]);
     sc[0] = gb < ge ? __builtin_amdgcn_cvt_f32_fp8((int)psb[0], 0) : 0.f;
     b0[1] = b0[0]; b1[1] = b1[0]; sc[1] = 0.f;
     __syncthreads();
@@ -128,17 +171,16 @@ void fq_gemm_ksplit_kernel(
         for (int u = 0; u < 2; ++u) {
             const int j = 2 * p + u;                      // step of this split; group gb + j
             const fq_v4i* cur = stages + u * cfg::STG;
-            fql_issue_a<NT>(rsA, abase, m0, K, stages + (u ^ 1) * cfg::STG, nw, gclamp(j + 1));
+            if (j > 0) fql_issue_a<NT>(rsA, abase, m0, K, stages + (u ^ 1) * cfg::STG, nw, gclamp(j + 1), ghost(j + 1));
             const unsigned qs = psb[u ^ 1];
-            {
-                const int g2 = gclamp(j + 2);
-                fql_issue_b(rsW, wbuf + u * 128, lane16, wblk + (unsigned)g2 * 2048u);
-                psb[u] = gsrow[g2];
-            }
-            __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(NT + 3));
+            // (WREG: slot u held group j, unpacked during the last step; the compiler times the wait for slot u ^ 1)
+            if (cfg::WREG) load_w(u, j + 2);
+            else           fql_issue_b(rsW, wbuf + u * 128, lane16 | ghost(j + 2), wblk + (unsigned)gclamp(j + 2) * 2048u);
+            psb[u] = gsrow[gclamp(j + 2)];
+            if (!cfg::WREG) __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(NT + 3));
             const fq_v4i* nxt = wbuf + (u ^ 1) * 128 + lane;
             const float s = sc[u];
-            fq_v4i q = nxt[0];
+            fq_v4i q = cfg::WREG ? wraw[u ^ 1][0] : nxt[0];
             fq_v16f pt;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -165,7 +207,7 @@ void fq_gemm_ksplit_kernel(
                         if (slot < 4) b0[u ^ 1][4 * h + (slot & 3)] = ev;
                         else          b1[u ^ 1][4 * h + (slot & 3)] = ev;
                     }
-                    if (mt == NMT / 2 - 1 && h == 1) q = nxt[64];
+                    if (mt == NMT / 2 - 1 && h == 1) q = cfg::WREG ? wraw[u ^ 1][1] : nxt[64];
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);
@@ -192,13 +234,14 @@ void fq_gemm_ksplit_kernel(
     // ---- fold: add the K splits' partial tiles through LDS ----
     // Row tiles are handed out in blocks: split kw finishes row tiles kw * OWN .. kw * OWN + OWN - 1 (for its
     // NW waves' channels).  Half of the row tiles go through LDS at a time: every wave writes its partial
-    // tiles of that half ([wave][tile of the half][16 registers][64 lanes]), and the waves that own one of them
-    // add up the KS partials in the order of the splits (a fixed order: the result is deterministic).
+    // tiles of that half ([wave][tile of the half][4 x 4 registers][64 lanes], 16 bytes per lane and access), and
+    // the waves that own one of them add up the KS partials in the order of the splits (a fixed order: the result
+    // is deterministic).
     __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));           // ghost transfers have landed: the stages can be reused
     __syncthreads();
     fq_v16f fin[OWN];
     {
-        float* fold = reinterpret_cast<float*>(lds);
+        fq_v4f* fold = reinterpret_cast<fq_v4f*>(lds);
         constexpr int HALF = NMT / 2 > 0 ? NMT / 2 : 1;   // row tiles per pass
         constexpr int PASSES = NMT / HALF;
 #pragma unroll
@@ -206,7 +249,10 @@ void fq_gemm_ksplit_kernel(
 #pragma unroll
             for (int t = 0; t < HALF; ++t)
 #pragma unroll
-                for (int r = 0; r < 16; ++r) fold[((wave * HALF + t) * 16 + r) * 64 + lane] = acc[pass * HALF + t][r];
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const fq_v16f& a = acc[pass * HALF + t];
+                    fold[((wave * HALF + t) * 4 + r4) * 64 + lane] = (fq_v4f){a[4 * r4], a[4 * r4 + 1], a[4 * r4 + 2], a[4 * r4 + 3]};
+                }
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < OWN; ++i) {
@@ -214,11 +260,12 @@ void fq_gemm_ksplit_kernel(
                 if (mt / HALF == pass) {
                     const int t = mt - pass * HALF;
 #pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        float v = 0.f;
+                    for (int r4 = 0; r4 < 4; ++r4) {
+                        fq_v4f v = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                        for (int k2 = 0; k2 < KS; ++k2) v += fold[(((k2 * NW + nw) * HALF + t) * 16 + r) * 64 + lane];
-                        fin[i][r] = v;
+                        for (int k2 = 0; k2 < KS; ++k2) v += fold[(((k2 * NW + nw) * HALF + t) * 4 + r4) * 64 + lane];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) fin[i][4 * r4 + e] = v[e];
                     }
                 }
             }
@@ -227,16 +274,71 @@ void fq_gemm_ksplit_kernel(
     }
     const int mown = m0 + kw * (32 * OWN);                // first row of this wave's own row tiles
 
+    // the first round of zero-point units is requested now: it travels while the slices hand over
+    const int rounds = (ZU + 7) >> 3;
+    fql_issue_z<NMT, FQK_WAVES>(rsZ, lds, wave, lane, m0, M, 0, ZU < 8 ? ZU : 8);
+
+    // ---- K slices: hand the partial tile over; the workgroup that arrives last adds them up and goes on ----
+    // The partial tiles and the counter are written and read with device-scope accesses (the sc1 bit: they go to
+    // the level at which all XCDs agree and bypass the caches on the way back), and a wave's stores have been
+    // acknowledged there (vmcnt = 0) before its workgroup counts itself in: a device-scope fence would do the same
+    // by writing back the whole L2, once per workgroup, which cost more than the GEMM.  A tile's partial sums are
+    // laid out [slice][wave][own row tile][4 x 4 registers][64 lanes], 16 bytes per lane and access.
+    if (S > 1) {
+        constexpr int SC1 = 16;                           // cache policy of the buffer builtins: device scope
+        constexpr unsigned WAVE_BYTES = (unsigned)OWN * 4096u;
+        const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(
+            partials + (size_t)tile * S * FQK_WAVES * (WAVE_BYTES / 4), 0, (int)((unsigned)S * FQK_WAVES * WAVE_BYTES), 0x00020000);
+#pragma unroll
+        for (int i = 0; i < OWN; ++i)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const fq_v4f v = {fin[i][4 * r4], fin[i][4 * r4 + 1], fin[i][4 * r4 + 2], fin[i][4 * r4 + 3]};
+                __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(fq_v4i, v), rsP, lane16,
+                                                       (unsigned)(slice * FQK_WAVES + wave) * WAVE_BYTES + (unsigned)(i * 4 + r4) * 1024u, SC1);
+            }
+        __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));       // this wave's partial sums have arrived ...
+        __syncthreads();
+        unsigned* flag = reinterpret_cast<unsigned*>(lds + cfg::LDS / 16 - 1);   // (past the zero-point units on their way)
+        if (threadIdx.x == 0)                             // ... before the workgroup counts itself in
+            flag[0] = __hip_atomic_fetch_add(&counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        const unsigned arrived = *reinterpret_cast<volatile unsigned*>(flag);
+        if (arrived != (unsigned)(S - 1)) return;
+        if (threadIdx.x == 0)                             // every slice has counted: ready for the next call
+            __hip_atomic_store(&counters[tile], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // four slices' worth of loads are in flight at a time; the sum runs in the order of the slices
+#pragma unroll
+        for (int i = 0; i < OWN; ++i) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) fin[i][r] = 0.f;
+            for (int sl0 = 0; sl0 < S; sl0 += 4) {
+                fq_v4f part[4][4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int sl = sl0 + q < S ? sl0 + q : S - 1;       // (a repeat of the last slice, dropped below)
+#pragma unroll
+                    for (int r4 = 0; r4 < 4; ++r4)
+                        part[q][r4] = __builtin_bit_cast(fq_v4f, __builtin_amdgcn_raw_buffer_load_b128(
+                            rsP, lane16, (unsigned)(sl * FQK_WAVES + wave) * WAVE_BYTES + (unsigned)(i * 4 + r4) * 1024u, SC1));
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (sl0 + q < S) {
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) fin[i][r] += part[q][r >> 2][r & 3];
+                    }
+            }
+        }
+    }
+
     // ---- zero point: fin += Z * gscale^T over all groups (fp16 matrix cores), 8 units of Z per round ----
     {
         constexpr int RT = 32 * NMT;
         const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
         const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : 0xFFFFFF00u;
-        const bool unaligned_rows = (G & 3) != 0;
         const int hl = lane >> 5;
-        const int rounds = (ZU + 7) >> 3;
-        fql_issue_z<NMT, FQK_WAVES>(rsZ, lds, wave, lane, m0, M, 0, ZU < 8 ? ZU : 8);
         for (int r = 0; r < rounds; ++r) {
             const int u0 = 8 * r;
             const int nu = ZU - u0 < 8 ? ZU - u0 : 8;
@@ -246,33 +348,7 @@ void fq_gemm_ksplit_kernel(
                 fql_issue_z<NMT, FQK_WAVES>(rsZ, lds + ((r + 1) & 1) * cfg::STG, wave, lane, m0, M, u0 + 8,
                                             ZU - u0 - 8 < 8 ? ZU - u0 - 8 : 8);
             fql_v8h sig[4];
-#pragma unroll
-            for (int ci = 0; ci < 4; ++ci) {
-                const int c = ((u0 + 2 * ci) % C2) >> 1;
-                const int g0 = 16 * c + 8 * hl;
-                unsigned w[2] = {0u, 0u};
-                if (2 * ci < nu) {
-                    const unsigned o = srow + (unsigned)g0;
-                    const unsigned ob = (n_ok && g0 < G) ? (o & ~3u) : 0xFFFFFF00u;
-                    const unsigned d0 = __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 0, 0);
-                    const unsigned d1 = __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 4, 0);
-                    const unsigned d2 = unaligned_rows ? __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 8, 0) : 0u;
-                    w[0] = __builtin_amdgcn_alignbyte(d1, d0, o & 3u);
-                    w[1] = __builtin_amdgcn_alignbyte(d2, d1, o & 3u);
-                    const int nv = G - g0;
-                    if (nv < 4) w[0] &= nv <= 0 ? 0u : (1u << (8 * nv)) - 1u;
-                    if (nv < 8) w[1] &= nv <= 4 ? 0u : (1u << (8 * (nv - 4))) - 1u;
-                }
-                fq_v4i pk;
-#pragma unroll
-                for (int x = 0; x < 2; ++x) {
-                    pk[2 * x]     = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
-                        __builtin_amdgcn_cvt_f32_fp8((int)w[x], 0), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 1)));
-                    pk[2 * x + 1] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
-                        __builtin_amdgcn_cvt_f32_fp8((int)w[x], 2), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 3)));
-                }
-                sig[ci] = __builtin_bit_cast(fql_v8h, pk);
-            }
+            fql_round_scales(rsS, srow, n_ok, G, C2, u0, nu, hl, sig);
             const fq_v4i* stage = lds + (r & 1) * cfg::STG;
 #pragma unroll
             for (int ci = 0; ci < 4; ++ci) {
@@ -289,10 +365,7 @@ void fq_gemm_ksplit_kernel(
 
     // ---- epilogue: per-token and per-tensor factors, the residual if any, one rounding to bf16, store ----
     float* osc = reinterpret_cast<float*>(reinterpret_cast<char*>(lds) + cfg::BM * cfg::OUT_STRIDE);
-    for (int i = threadIdx.x; i < cfg::BM; i += FQK_THREADS) {
-        const int m = m0 + i;
-        osc[i] = a_scale[m < M ? m : M - 1] * (tscale * 512.0f);   // x 2^9: the weights were fed in units of 2^-9
-    }
+    if ((int)threadIdx.x < cfg::BM) osc[threadIdx.x] = row_factor;
     __syncthreads();
     const bool full_tile = (m0 + cfg::BM <= M) && (n0 + cfg::BN <= N) && ((N & 7) == 0);
     if (full_tile) {
@@ -352,7 +425,8 @@ void fq_gemm_ksplit_kernel(
 
 template <int NMT, int NW, int KS>
 void fqk_launch(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y,
-                int M, int N, int K, const uint16_t* planes, const uint16_t* R, hipStream_t stream) {
+                int M, int N, int K, const uint16_t* planes, const uint16_t* R, int S, unsigned* counters, float* partials,
+                hipStream_t stream) {
     typedef fqk_cfg<NMT, NW, KS> cfg;
     static fq_device_once attr_once;                      // (one per template instance)
     fq_once_per_device(attr_once, [] {
@@ -362,9 +436,9 @@ void fqk_launch(const uint8_t* A, const float* a_scale, const uint8_t* wp, const
     const int tiles_m = (M + cfg::BM - 1) / cfg::BM, tiles_n = (N + cfg::BN - 1) / cfg::BN;
     const int ntiles = tiles_m * tiles_n;
     const int pm = tiles_m < 4 ? tiles_m : 4;
-    const unsigned grid = (unsigned)((ntiles + FQL_XCDS - 1) / FQL_XCDS * FQL_XCDS);
+    const unsigned grid = (unsigned)((ntiles + FQL_XCDS - 1) / FQL_XCDS * FQL_XCDS * S);
     hipLaunchKernelGGL((fq_gemm_ksplit_kernel<NMT, NW, KS>), dim3(grid), dim3(FQK_THREADS), cfg::LDS, stream,
-                       A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, pm, planes, R);
+                       A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, pm, planes, R, S, counters, partials);
 }
 
 }  // namespace
@@ -384,11 +458,38 @@ int fq_gemm_ksplit_choice(int M, int N, int K, int cus) {
     return (long long)((M + 127) / 128) * ((N + 63) / 64) <= cus ? 2 : 0;
 }
 
+// K slices of the 128 x 64 shape: as many as fill the compute units, each with at least two groups per K split
+// of its workgroup, none of them empty, at most 8; 1 where the shape is not the 128 x 64 one or the tiles exceed
+// the counters.
+int fq_gemm_ksplit_slices(int choice, int M, int N, int K, int cus) {
+    if (choice != 2 || M > FQ_KSPLIT_MAX_M) return 1;
+    const int G = K / FQ_GROUP;
+    const long long tiles = (long long)((M + 127) / 128) * ((N + 63) / 64);
+    if (tiles > FQ_KSPLIT_COUNTERS) return 1;
+    int S = (int)(cus / tiles);
+    if (S > G / 8) S = G / 8;
+    if (S > 8) S = 8;
+    if (S < 1) S = 1;
+    while (S > 1 && (long long)((G + S - 1) / S) * (S - 1) >= G) --S;
+    return S;
+}
+
+size_t fq_gemm_ksplit_partial_bytes(int choice, int M, int N, int K, int cus) {
+    const int S = fq_gemm_ksplit_slices(choice, M, N, K, cus);
+    if (S <= 1) return 0;
+    return (size_t)S * (size_t)((M + 127) / 128) * (size_t)((N + 63) / 64) * (128u * 64u * sizeof(float));
+}
+
 void fq_launch_gemm_ksplit(int choice, const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                            float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
                            const uint16_t* R, hipStream_t stream) {
     if (!prepared) fq_launch_zero_point(A, workspace, M, K, stream);
     const uint16_t* planes = static_cast<const uint16_t*>(workspace);
-    if (choice == 1) fqk_launch<8, 4, 2>(A, a_scale, wp, gs, tscale, Y, M, N, K, planes, R, stream);
-    else             fqk_launch<4, 2, 4>(A, a_scale, wp, gs, tscale, Y, M, N, K, planes, R, stream);
+    // behind the planes: the tiles' arrival counters (zeroed by whatever prepared the workspace), then the partial tiles
+    const size_t plane_bytes = fq_gemm_plane_bytes(M, K);
+    unsigned* counters = reinterpret_cast<unsigned*>(static_cast<char*>(workspace) + plane_bytes);
+    float* partials = reinterpret_cast<float*>(counters + FQ_KSPLIT_COUNTERS);
+    const int S = fq_gemm_ksplit_slices(choice, M, N, K, fq_device_cus());
+    if (choice == 1) fqk_launch<8, 4, 2>(A, a_scale, wp, gs, tscale, Y, M, N, K, planes, R, 1, counters, partials, stream);
+    else             fqk_launch<4, 2, 4>(A, a_scale, wp, gs, tscale, Y, M, N, K, planes, R, S, counters, partials, stream);
 }

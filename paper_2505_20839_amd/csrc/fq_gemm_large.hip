@@ -106,6 +106,10 @@ __global__ __launch_bounds__(256) void fq_zero_point_kernel(const uint8_t* __res
     const int m = blockIdx.x;
     const int sub = threadIdx.x & 7;
     const uint8_t* row = A + (size_t)m * K + 16 * sub;
+    if (M <= FQ_KSPLIT_MAX_M) {                           // the arrival counters behind the planes start at zero
+        unsigned* counters = reinterpret_cast<unsigned*>(planes + (size_t)FQL_ZPLANES * C2 * M * 8);
+        for (int i = blockIdx.x * 256 + threadIdx.x; i < FQ_KSPLIT_COUNTERS; i += gridDim.x * 256) counters[i] = 0u;
+    }
     for (int g0 = 0; g0 < G8; g0 += FQL_ZP_MAXG) {        // (one pass unless K > 131072)
         const int gn = G8 - g0 < FQL_ZP_MAXG ? G8 - g0 : FQL_ZP_MAXG;
         for (int gl = threadIdx.x >> 3; gl < gn; gl += 32) {
@@ -358,13 +362,9 @@ __device__ __forceinline__ void fql_item(
         __syncthreads();
     } else {
         constexpr int RT = 32 * NMT;                      // rows of the item
-        // (range rounded up to whole words: the array's last word may hold fewer than four scales, and a
-        // word that crosses the end of the range would read as zero; the array is 16-byte aligned, so that
-        // word lies in the same cache line as its valid bytes, and the surplus bytes are cleared below)
         const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
         const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : 0xFFFFFF00u;   // channels past N read zeros
-        const bool unaligned_rows = (G & 3) != 0;         // (the array itself is 16-byte aligned)
         const int hl = lane >> 5;                         // which half of a chunk's 16 groups this lane holds
         const int rounds = (ZU + 7) >> 3;
         for (int r = 0; r < rounds; ++r) {
@@ -375,37 +375,7 @@ __device__ __forceinline__ void fql_item(
                                  ZU - u0 - 8 < 8 ? ZU - u0 - 8 : 8);
             // gscale operands of this round's chunks: 8 consecutive groups of this lane's channel as fp16
             fql_v8h sig[4];
-#pragma unroll
-            for (int ci = 0; ci < 4; ++ci) {
-                const int c = ((u0 + 2 * ci) % C2) >> 1;  // chunk index inside its plane
-                const int g0 = 16 * c + 8 * hl;
-                unsigned w[2] = {0u, 0u};
-                if (2 * ci < nu) {
-                    // The 8 scale bytes of groups g0 .. g0 + 7 start at byte n * G + g0 of the array,
-                    // which is a multiple of 4 only when G is: fetch the aligned words around them
-                    // (out-of-range words read zero) and shift them into place.
-                    const unsigned o = srow + (unsigned)g0;
-                    const unsigned ob = (n_ok && g0 < G) ? (o & ~3u) : 0xFFFFFF00u;
-                    const unsigned d0 = __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 0, 0);
-                    const unsigned d1 = __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 4, 0);
-                    const unsigned d2 = unaligned_rows ? __builtin_amdgcn_raw_buffer_load_b32(rsS, ob, 8, 0) : 0u;
-                    w[0] = __builtin_amdgcn_alignbyte(d1, d0, o & 3u);
-                    w[1] = __builtin_amdgcn_alignbyte(d2, d1, o & 3u);
-                    // bytes of groups >= G belong to the next channel: cleared
-                    const int nv = G - g0;                // valid groups from g0 on
-                    if (nv < 4) w[0] &= nv <= 0 ? 0u : (1u << (8 * nv)) - 1u;
-                    if (nv < 8) w[1] &= nv <= 4 ? 0u : (1u << (8 * (nv - 4))) - 1u;
-                }
-                fq_v4i pk;                                // E4M3 -> fp16 is exact, whatever the rounding mode
-#pragma unroll
-                for (int x = 0; x < 2; ++x) {
-                    pk[2 * x]     = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
-                        __builtin_amdgcn_cvt_f32_fp8((int)w[x], 0), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 1)));
-                    pk[2 * x + 1] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
-                        __builtin_amdgcn_cvt_f32_fp8((int)w[x], 2), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 3)));
-                }
-                sig[ci] = __builtin_bit_cast(fql_v8h, pk);
-            }
+            fql_round_scales(rsS, srow, n_ok, G, C2, u0, nu, hl, sig);
             const fq_v4i* stage = lds + (r & 1) * FQL_STAGE_CHUNKS;
 #pragma unroll
             for (int ci = 0; ci < 4; ++ci) {
@@ -601,8 +571,12 @@ void fq_gemm_large_lut_kernel(
                           swiglu, R);
 }
 
-size_t fq_gemm_large_workspace_bytes(int M, int K) {
+size_t fq_gemm_plane_bytes(int M, int K) {
     return (size_t)FQL_ZPLANES * fql_c2(K / FQ_GROUP) * (size_t)M * 16;
+}
+
+size_t fq_gemm_large_workspace_bytes(int M, int K) {
+    return fq_gemm_plane_bytes(M, K) + (M <= FQ_KSPLIT_MAX_M ? FQ_KSPLIT_COUNTERS * sizeof(unsigned) : 0);
 }
 
 void fq_gemm_large_plan(int M, int N, int cus, int out[4]) {

@@ -39,15 +39,17 @@ __device__ __forceinline__ unsigned fql_a_lane_base(int wave, int lane, int K, i
     return (unsigned)row * (unsigned)K + (unsigned)c0 * 16u;
 }
 
+// `oob` = FQL_OOB requests the tile out of range instead: zeros arrive, and nothing is fetched.
+#define FQL_OOB 0xFFFFFF00u
 template <int NT>
 __device__ __forceinline__ void fql_issue_a(__amdgpu_buffer_rsrc_t rsrc, unsigned abase, int m0, int K,
-                                            fq_v4i* lds_stage, int wave, int g) {
+                                            fq_v4i* lds_stage, int wave, int g, unsigned oob = 0u) {
     fq_v4i* dst = lds_stage + wave * (64 * NT);           // this wave's 8 * NT rows
     const int sg = g * FQ_GROUP;
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
         // odd transfers start 8 rows further, where the swizzle flips bit 2 of the column
-        const unsigned v = (abase ^ ((j & 1) ? 64u : 0u)) + (unsigned)(m0 + 8 * j) * (unsigned)K;
+        const unsigned v = ((abase ^ ((j & 1) ? 64u : 0u)) + (unsigned)(m0 + 8 * j) * (unsigned)K) | oob;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (fql_lds_ptr)(dst + 64 * j), 16, v, sg, 0, 0);
     }
 }
@@ -122,6 +124,60 @@ __device__ __forceinline__ fq_v8i fql_unpack_chunk_lut(fq_v4i w, fq_v4i t) {
 // s_waitcnt immediate (gfx9 encoding) that waits until at most n vector-memory transfers are pending
 // and leaves the other counters alone.
 #define FQL_WAIT_VM(n) ((((n) & 0xF) | (((n) >> 4) << 14)) | 0x0F70)
+
+// The gscale operands of one round of zero-point units (numbers u0 .. u0 + nu - 1; unit pairs 2 ci, 2 ci + 1 are
+// the two lane halves of MFMA chunk ci): for each of the round's up to 4 chunks, 8 consecutive groups of this
+// lane's channel as fp16 (E4M3 -> fp16 is exact, whatever the rounding mode).  The 8 scale bytes of groups
+// g0 .. g0 + 7 start at byte n * G + g0 of the array, which is a multiple of 4 only when G is: the aligned words
+// around them are fetched and shifted into place.  `rsS` covers the scale array rounded up to whole words (the
+// array's last word may hold fewer than four scales, and a word that crosses the end of the range would read as
+// zero; the array is 16-byte aligned, so that word lies in the same cache line as its valid bytes).  Everything
+// that is not wanted -- a chunk past the round's units, groups past G, a channel past N -- is requested out of
+// range and reads as zero, so all the loads are issued back to back without a branch and the round waits for
+// memory once.
+__device__ __forceinline__ void fql_round_scales(__amdgpu_buffer_rsrc_t rsS, unsigned srow, bool n_ok, int G, int C2,
+                                                 int u0, int nu, int hl, fql_v8h sig[4]) {
+    const bool unaligned_rows = (G & 3) != 0;             // (the array itself is 16-byte aligned)
+    unsigned d[4][3], o[4];
+    int g0[4];
+#pragma unroll
+    for (int ci = 0; ci < 4; ++ci) {
+        const int c = ((u0 + 2 * ci) % C2) >> 1;          // chunk index inside its plane
+        g0[ci] = 16 * c + 8 * hl;
+        o[ci] = srow + (unsigned)g0[ci];
+        const unsigned ob = (2 * ci < nu && n_ok && g0[ci] < G) ? (o[ci] & ~3u) : FQL_OOB;
+        // one load instruction per chunk: the address path takes as long for a lane's 4 bytes as for its 12
+        if (unaligned_rows) {
+            typedef unsigned v3u __attribute__((ext_vector_type(3)));
+            const v3u t = __builtin_bit_cast(v3u, __builtin_amdgcn_raw_buffer_load_b96(rsS, ob, 0, 0));
+            d[ci][0] = t[0]; d[ci][1] = t[1]; d[ci][2] = t[2];
+        } else {
+            typedef unsigned v2u __attribute__((ext_vector_type(2)));
+            const v2u t = __builtin_bit_cast(v2u, __builtin_amdgcn_raw_buffer_load_b64(rsS, ob, 0, 0));
+            d[ci][0] = t[0]; d[ci][1] = t[1]; d[ci][2] = 0u;
+        }
+    }
+#pragma unroll
+    for (int ci = 0; ci < 4; ++ci) {
+        unsigned w[2];
+        w[0] = __builtin_amdgcn_alignbyte(d[ci][1], d[ci][0], o[ci] & 3u);
+        w[1] = __builtin_amdgcn_alignbyte(d[ci][2], d[ci][1], o[ci] & 3u);
+        // bytes of groups >= G belong to the next channel: cleared
+        const int nv = G - g0[ci];                        // valid groups from g0 on
+        if (nv < 4) w[0] &= nv <= 0 ? 0u : (1u << (8 * nv)) - 1u;
+        if (nv < 8) w[1] &= nv <= 4 ? 0u : (1u << (8 * (nv - 4))) - 1u;
+        fq_v4i pk;
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            pk[2 * x]     = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
+                __builtin_amdgcn_cvt_f32_fp8((int)w[x], 0), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 1)));
+            pk[2 * x + 1] = __builtin_bit_cast(int, __builtin_amdgcn_cvt_pkrtz(
+                __builtin_amdgcn_cvt_f32_fp8((int)w[x], 2), __builtin_amdgcn_cvt_f32_fp8((int)w[x], 3)));
+        }
+        sig[ci] = __builtin_bit_cast(fql_v8h, pk);
+    }
+}
+
 
 __device__ __forceinline__ fq_v8i fql_join(fq_v4i lo, fq_v4i hi) {
     fq_v8i r;

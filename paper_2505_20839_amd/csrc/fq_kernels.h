@@ -47,6 +47,11 @@ void fq_launch_gemm_simple(const uint8_t* A, const float* a_scale, const uint8_t
 // The large-M kernel needs fq_gemm_large_workspace_bytes(M, K) bytes of device scratch (16-byte aligned)
 // holding the zero-point term of every (row, group) of A: fq_launch_zero_point writes it, and
 // fq_launch_gemm_large calls that first unless `prepared` says the workspace already holds it.
+// For M <= FQ_KSPLIT_MAX_M the planes are followed by FQ_KSPLIT_COUNTERS arrival counters (32-bit), which whatever
+// writes the planes also sets to zero; the K-split kernel's partial tiles come after those.
+#define FQ_KSPLIT_COUNTERS 1024
+#define FQ_KSPLIT_MAX_M 512
+size_t fq_gemm_plane_bytes(int M, int K);
 size_t fq_gemm_large_workspace_bytes(int M, int K);
 // How the large-M kernel cuts an M x N problem on `cus` compute units: out[0] whole tiles (256 rows x
 // 128 channels) stored with whole-row vector stores, out[1] whole tiles stored element by element (rows
@@ -96,6 +101,10 @@ void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t*
 // with K halved, 2 = 128 x 64 tiles with K quartered.  Workspace and `prepared` as for fq_launch_gemm_large; no
 // fused gate/up epilogue.
 int fq_gemm_ksplit_choice(int M, int N, int K, int cus);
+// K slices per tile (workgroups that share a tile and add their partial tiles through the workspace) and the
+// bytes of partial tiles, which follow the arrival counters in the workspace; 1 and 0 when there are none.
+int fq_gemm_ksplit_slices(int choice, int M, int N, int K, int cus);
+size_t fq_gemm_ksplit_partial_bytes(int choice, int M, int N, int K, int cus);
 void fq_launch_gemm_ksplit(int choice, const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                            float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
                            const uint16_t* R, hipStream_t stream);

@@ -51,6 +51,12 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
     const int m = blockIdx.x;
     const fq_v4i* x = reinterpret_cast<const fq_v4i*>(X + (size_t)m * K);
     fq_v2i* a = reinterpret_cast<fq_v2i*>(A + (size_t)m * K);
+    if (ZP && M <= FQ_KSPLIT_MAX_M) {                     // the arrival counters behind the planes start at zero
+        const int G = K >> 7, C2 = 2 * ((G + 15) >> 4);
+        unsigned* counters = reinterpret_cast<unsigned*>(planes + (size_t)2 * C2 * M * 8);
+        for (int i = blockIdx.x * FQ_Q_THREADS + threadIdx.x; i < FQ_KSPLIT_COUNTERS; i += gridDim.x * FQ_Q_THREADS)
+            counters[i] = 0u;
+    }
     const int nchunk = K >> 3;
     const bool in_regs = nchunk <= FQ_Q_THREADS * FQ_Q_MAXCHUNK;
     fq_v4i keep[FQ_Q_MAXCHUNK];

@@ -44,7 +44,9 @@ def test_sizes_version_and_status_strings():
     assert len(seen) == 6 and binding.status_string(0) == "ok"
     # workspace: none for the small-M kernels, two fp16 planes of [M][16 * ceil(K / 2048)] for the rest
     assert binding.fq_w4a8_gemm_workspace_bytes(64, 256, 4096) == 0
-    assert binding.fq_w4a8_gemm_workspace_bytes(65, 256, 4096) == 2 * 4 * 65 * 16
+    # zero-point planes, arrival counters, and 4 K slices x 4 tiles of 128 x 64 FP32 partial sums (256 compute units assumed without a GPU)
+    assert binding.fq_w4a8_gemm_workspace_bytes(65, 256, 4096) == 2 * 4 * 65 * 16 + 4096 + 4 * 4 * 32768
+    assert binding.fq_w4a8_gemm_workspace_bytes(513, 256, 4096) == 2 * 4 * 513 * 16
     assert binding.fq_w4a8_gemm_workspace_bytes(2048, 4096, 11008) == 2 * 12 * 2048 * 16
     assert binding.fq_w4a8_gemm_workspace_bytes(128, 256, 100) == 0      # invalid shape
     assert binding.status_string(-99) == "unknown status"

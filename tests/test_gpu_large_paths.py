@@ -164,6 +164,13 @@ def test_few_tile_shapes_take_the_k_split_kernel(fq):
     assert _plan(fq, (512, 4096, 4096))["kernel"] == "ksplit128x64"
     assert _plan(fq, (512, 14336, 4096))["kernel"] == "large"              # more than one round of 128 x 64 tiles
     assert _plan(fq, (2048, 11008, 4096))["kernel"] == "large"
+    # workgroups that share a tile along K: as many as fill the compute units, two groups or more per K split each
+    assert _plan(fq, (128, 4096, 4096))["ksplit_slices"] == 4
+    assert _plan(fq, (128, 4096, 11008))["ksplit_slices"] == 4
+    assert _plan(fq, (256, 4096, 4096))["ksplit_slices"] == 2
+    assert _plan(fq, (512, 4096, 4096))["ksplit_slices"] == 1
+    assert _plan(fq, (100, 96, 11008))["ksplit_slices"] == 8
+    assert _plan(fq, (129, 200, 1408))["ksplit_slices"] == 1
     fq.fq_test_force_kernel("ksplit")
     try:
         for shape in KSPLIT_SHAPES:
@@ -224,3 +231,31 @@ def test_k_split_kernel_zero_activations_return_the_residual(fq):
             fq.fq_test_force_kernel(None)
         bad = np.argwhere(bf16_bits_from_gpu(Yg) != Rb)
         assert bad.size == 0, "%s: first wrong element %s" % (shape, bad[:1])
+
+
+def test_a_prepared_workspace_serves_several_sliced_gemms(fq):
+    """Projections that share one activation matrix run one after the other on the workspace the quantiser
+    prepared: the tiles' arrival counters are back at zero after every call, so each result equals the one a
+    freshly prepared workspace gives, bit for bit, and matches the oracle."""
+    M, K = 128, 4096
+    shapes_n = [1024, 320, 1024]
+    ds = [_problem((M, N, K), seed=90 + i) for i, N in enumerate(shapes_n)]
+    X = to_gpu_bf16(ds[0]["X_bf16"])
+    need = max(fq.fq_w4a8_gemm_workspace_bytes(M, N, K) for N in shapes_n)
+    for N in shapes_n:
+        assert _plan(fq, (M, N, K))["ksplit_slices"] == 4
+    ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+    A, s = fq.fq_quantize_act(X, workspace=ws)
+    outs = []
+    for d, N in zip(ds, shapes_n):
+        packed, gs = fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"])
+        outs.append(fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N, workspace=ws, workspace_prepared=True))
+    torch.cuda.synchronize()
+    An, sn = A.cpu().numpy(), s.cpu().numpy()
+    for d, N, Yg in zip(ds, shapes_n, outs):
+        packed, gs = fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"])
+        fresh = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits_from_gpu(Yg), bf16_bits_from_gpu(fresh)), N
+        Y, B = oracle.w4a8_gemm(An, sn, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+        check_gemm(bf16_bits_from_gpu(Yg), Y, B, "shared workspace, N = %d" % N)

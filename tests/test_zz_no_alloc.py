@@ -46,8 +46,8 @@ def test_static_scratch_entry_point_matches_the_workspace_one():
         check_gemm(bf16_bits_from_gpu(Y_st), Y, B, "static scratch %dx%dx%d" % (M, N, K))
     # a problem that needs more than the built-in scratch is refused before anything is enqueued
     cap = L.fq_w4a8_gemm_static_max_workspace()
-    M, N, K = 8192 + 256, 128, 16384
+    M, N, K = 32768 + 256, 128, 16384
     assert fq.fq_w4a8_gemm_workspace_bytes(M, N, K) > cap
     p = ctypes.c_void_p(0x1000)                               # never dereferenced: the size check comes first
     assert L.fq_w4a8_gemm_static(p, p, p, p, ctypes.c_float(1.0), p, M, N, K, stream) == -5
-    assert fq.fq_w4a8_gemm_workspace_bytes(8192, 128, 16384) == cap
+    assert fq.fq_w4a8_gemm_workspace_bytes(32768, 128, 16384) == cap
