@@ -32,6 +32,7 @@ PEAK_FP8_TFLOPS = 5033.0      # 256 CU x 2.4 GHz x 8192 flop/clk/CU, dense FP8 M
 PEAK_HBM_GBPS = 8000.0
 DEFAULT_WORKLOAD = "c2_l2_7b_gateup"
 DECODE_COPIES = 12            # rotating weight copies so that small-M launches read HBM, not cache
+MID_COPIES = 6                # rotating weight copies for 64 < M <= 512
 LARGE_GRAPH_STEPS = 10        # steps per captured graph at large M (one copy of the weights: they do not fit a cache)
 REPS = 5                      # timed repetitions; median and best are reported
 MIN_LAUNCHES = 50             # GEMM launches per repetition of the kernel timing (500 at small M), whatever --steps says
@@ -306,8 +307,9 @@ def main() -> int:
     decode_like = w0.M <= 64
     steps = args.steps if args.steps is not None else (2000 if decode_like else 200)
     warmup = args.warmup if args.warmup is not None else (50 if decode_like else 20)
-    r = run(name, steps, warmup, DECODE_COPIES if decode_like else 1,
-            DECODE_COPIES if decode_like else LARGE_GRAPH_STEPS, with_read_floor=decode_like)
+    mid = 64 < w0.M <= 512                                # weights dominate the traffic: rotate copies here as well
+    r = run(name, steps, warmup, DECODE_COPIES if decode_like else MID_COPIES if mid else 1,
+            DECODE_COPIES if decode_like else MID_COPIES if mid else LARGE_GRAPH_STEPS, with_read_floor=decode_like)
     w, d, steps = r["w"], r["d"], r["steps"]
     step_s, gemm_s, quant_s = med(r["step_s"]), med(r["gemm_s"]), med(r["quant_s"])
 
@@ -339,7 +341,7 @@ def main() -> int:
     # what one fq_w4a8_gemm call launches: kernel_us is the median duration of the whole call over REPS
     # repetitions of `kernel_launches` launches each
     roof["kernel"] = ("fq_gemm_small16_kernel" if w.M <= 16 else "fq_gemm_smallm_kernel") if decode_like \
-        else "fq_gemm_large_kernel"
+        else ("fq_gemm_ksplit_kernel" if fq.fq_w4a8_gemm_plan(w.M, w.N, w.K)["kernel"].startswith("ksplit") else "fq_gemm_large_kernel")
     roof["kernel_us"] = gemm_s * 1e6
     roof["kernel_us_best"] = min(r["gemm_s"]) * 1e6
     roof["kernel_us_all"] = [round(t * 1e6, 3) for t in r["gemm_s"]]
@@ -389,7 +391,25 @@ def main() -> int:
         if not args.no_other_configs:
             out["decode_sweep"] = {wl: decode_entry(wl) for wl in ("c5_decode_m1", "c5_decode_m4", "c5_decode_m64")}
 
+    def mid_entry(wl):
+        """The GEMM call between decode and prefill (64 < M <= 512), over rotating weight copies: duration, which
+        kernel served it, and both roofline fractions of its algorithmic bytes and operations."""
+        rm = run(wl, 120, 12, MID_COPIES, MID_COPIES)
+        wm = rm["w"]
+        g, g_best = med(rm["gemm_s"]), min(rm["gemm_s"])
+        nbytes = wm.N * wm.K / 2 + wm.N * (wm.K // 128) + wm.M * wm.K + 4 * wm.M + 2 * wm.M * wm.N
+        fl = 2.0 * wm.M * wm.N * wm.K
+        plan = fq.fq_w4a8_gemm_plan(wm.M, wm.N, wm.K)
+        torch.cuda.empty_cache()
+        return {"M": wm.M, "N": wm.N, "K": wm.K, "kernel": plan["kernel"], "k_slices": plan["ksplit_slices"],
+                "kernel_us": g * 1e6, "kernel_us_best": g_best * 1e6, "quantize_us": med(rm["quant_s"]) * 1e6,
+                "step_us": med(rm["step_s"]) * 1e6, "algorithmic_GBps": nbytes / g / 1e9,
+                "frac_hbm": nbytes / g / 1e9 / PEAK_HBM_GBPS, "gemm_TFLOPs": fl / g / 1e12,
+                "frac_mfma_peak": fl / g / 1e12 / PEAK_FP8_TFLOPS, "weight_copies_rotated": MID_COPIES}
+
     if not args.no_other_configs and not decode_like and name == DEFAULT_WORKLOAD:
+        out["mid_m"] = {wl: mid_entry(wl) for wl in ("mid_l3_8b_up_m128", "mid_l3_8b_up_m256", "mid_l3_8b_up_m512",
+                                                     "mid_l2_7b_down_m128", "mid_l2_7b_down_m256", "mid_l2_7b_down_m512")}
         others = {}
         for other in ("c3_l2_7b_down", "c4a_l3_8b_qkv", "c4b_l3_8b_up", "ffn_l2_7b_gateup_swiglu",
                       "ffn_l2_7b_down_residual"):

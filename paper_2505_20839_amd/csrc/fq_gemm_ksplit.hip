@@ -445,17 +445,21 @@ void fqk_launch(const uint8_t* A, const float* a_scale, const uint8_t* wp, const
 
 // Which shape of this kernel, if any, serves the problem better than the large-M kernel's own tiles:
 // 0 = none, 1 = 256 x 128 tiles with K halved, 2 = 128 x 64 tiles with K quartered.
-// Measured on MI355X (K = 4096 unless noted; large-M kernel -> this kernel): the 128 x 64 shape wins wherever its
-// tiles fit one round of the compute units -- M = 128: N = 14336 28.3 -> 21.1 us, N = 11008 26.3 -> 19.4,
-// N = 4096 21.0 -> 15.9 (K = 11008: 67.9 -> 40.7); M = 256 and 512 at N = 4096: 21.1 -> 16.4 and 21.9 -> 18.3 --
-// and loses beyond that (M = 256, N = 14336: 29.4 -> 38.3; M = 512: 40.0 -> 72.9): a workgroup has one group of
-// each K split in flight, so a tile is bound by the latency of its transfers, and several rounds of such tiles
-// add up.  The 256 x 128 shape brought nothing on the shapes tried (down projection 2048 x 4096 x 11008: 105 us
+// Measured on MI355X (large-M kernel -> this kernel, prepared workspace): the 128 x 64 shape wins wherever its
+// tiles fit one round of the compute units -- M = 128, K = 4096: N = 4096 20.7 -> 14.0 us, N = 11008 21.5 -> 16.5,
+// N = 14336 23.6 -> 17.4; M = 128, N = 4096, K = 11008: 55.4 -> 21.7 (4 K slices); M = 512, N = 4096: K = 4096
+// 21.1 -> 16.4, K = 11008 55.5 -> 38.9; 8192 x 8192 at M = 256: 49.3 -> 29.9 -- and loses beyond one round
+// (M = 256, N = 11008: 23.4 -> 29.9; M = 512, N = 14336: 33.0 -> 59.4), except for a single row tile with a long K,
+// where two rounds still win (M = 128: 20480 x 5120 46.7 -> 43.7, 28672 x 8192 74.5 -> 63.3; at K = 4096 the two
+// are equal).  A step of a workgroup moves 80 KiB for 8 matrix instructions per wave and takes as long as that
+// transfer (1.2 us measured), so one compute unit cannot run more than one round of such tiles well.
+// The 256 x 128 shape brought nothing on the shapes tried (down projection 2048 x 4096 x 11008: 105 us
 // either way; 1024 x 4096 x 4096: 29.3 -> 37.1) and is not chosen automatically.
 int fq_gemm_ksplit_choice(int M, int N, int K, int cus) {
     const int G = K / FQ_GROUP;
-    if (M <= 64 || M > 512 || G < 8) return 0;
-    return (long long)((M + 127) / 128) * ((N + 63) / 64) <= cus ? 2 : 0;
+    if (M <= 64 || M > FQ_KSPLIT_MAX_M || G < 8) return 0;
+    const long long rounds = (M <= 128 && G >= 40) ? 2 : 1;
+    return (long long)((M + 127) / 128) * ((N + 63) / 64) <= rounds * cus ? 2 : 0;
 }
 
 // K slices of the 128 x 64 shape: as many as fill the compute units, each with at least two groups per K split

@@ -57,6 +57,14 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     _w("ffn_l2_7b_gateup_swiglu", 2048, 22016, 4096, "gauss", 0.01, 0.005, 0.05, 1.0, 9, "swiglu"),
     # the down projection of the same block with the residual stream added in the epilogue (step 3)
     _w("ffn_l2_7b_down_residual", 2048, 4096, 11008, "gauss", 0.01, 0.005, 0.05, 1.0, 10, "add"),
+    # between decode and prefill (batched decode, chunked prefill): the up projection and the down projection
+    # of configuration 4 / 3 at 128, 256 and 512 rows
+    _w("mid_l3_8b_up_m128",   128, 14336,  4096, "gauss", 0.01, 0.005, 0.05, 1.0, 11),
+    _w("mid_l3_8b_up_m256",   256, 14336,  4096, "gauss", 0.01, 0.005, 0.05, 1.0, 12),
+    _w("mid_l3_8b_up_m512",   512, 14336,  4096, "gauss", 0.01, 0.005, 0.05, 1.0, 13),
+    _w("mid_l2_7b_down_m128", 128,  4096, 11008, "gauss", 0.01, 0.005, 0.05, 1.0, 14),
+    _w("mid_l2_7b_down_m256", 256,  4096, 11008, "gauss", 0.01, 0.005, 0.05, 1.0, 15),
+    _w("mid_l2_7b_down_m512", 512,  4096, 11008, "gauss", 0.01, 0.005, 0.05, 1.0, 16),
 ]}
 
 

@@ -472,6 +472,14 @@ def test_large_configs_full_size(fq, name, rows):
     _full_config(fq, name, range(M) if rows is None else _every_8th_row(M))
 
 
+@pytest.mark.parametrize("name", ["mid_l3_8b_up_m128", "mid_l3_8b_up_m256", "mid_l3_8b_up_m512",
+                                  "mid_l2_7b_down_m128", "mid_l2_7b_down_m256", "mid_l2_7b_down_m512"])
+def test_mid_m_configs_full_size(fq, name):
+    """Batched-decode / chunked-prefill sizes that bench.py times (64 < M <= 512: the K-split kernel with and without
+    K slices, and the large-M kernel), every element against the oracle."""
+    _full_config(fq, name, range(workloads.WORKLOADS[name].M))
+
+
 def test_ws_entry_points_replay_in_a_hip_graph(fq):
     """The explicit-workspace entry points allocate nothing and keep no state, so a captured graph of
     quantiser + GEMM (plain, with residual, fused gate/up) can be replayed: three replays on fresh inputs,
