@@ -277,6 +277,11 @@ void fq_gemm_ksplit_kernel(
     // the first round of zero-point units is requested now: it travels while the slices hand over
     const int rounds = (ZU + 7) >> 3;
     fql_issue_z<NMT, FQK_WAVES>(rsZ, lds, wave, lane, m0, M, 0, ZU < 8 ? ZU : 8);
+    const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
+    const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : FQL_OOB;    // channels past N read zeros
+    fql_raw_scales zraw;                                  // the round's scale words, requested a round ahead
+    fql_scales_issue(rsS, srow, n_ok, G, C2, 0, ZU < 8 ? ZU : 8, lane >> 5, zraw);
 
     // ---- K slices: hand the partial tile over; the workgroup that arrives last adds them up and goes on ----
     // The partial tiles and the counter are written and read with device-scope accesses (the sc1 bit: they go to
@@ -335,20 +340,19 @@ void fq_gemm_ksplit_kernel(
     // ---- zero point: fin += Z * gscale^T over all groups (fp16 matrix cores), 8 units of Z per round ----
     {
         constexpr int RT = 32 * NMT;
-        const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
-        const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : 0xFFFFFF00u;
         const int hl = lane >> 5;
         for (int r = 0; r < rounds; ++r) {
             const int u0 = 8 * r;
             const int nu = ZU - u0 < 8 ? ZU - u0 : 8;
             __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));
             __syncthreads();                              // round r has landed (stage r & 1)
-            if (r + 1 < rounds)
-                fql_issue_z<NMT, FQK_WAVES>(rsZ, lds + ((r + 1) & 1) * cfg::STG, wave, lane, m0, M, u0 + 8,
-                                            ZU - u0 - 8 < 8 ? ZU - u0 - 8 : 8);
             fql_v8h sig[4];
-            fql_round_scales(rsS, srow, n_ok, G, C2, u0, nu, hl, sig);
+            fql_scales_finish(zraw, srow, G, C2, u0, hl, sig);
+            if (r + 1 < rounds) {
+                const int nn = ZU - u0 - 8 < 8 ? ZU - u0 - 8 : 8;
+                fql_issue_z<NMT, FQK_WAVES>(rsZ, lds + ((r + 1) & 1) * cfg::STG, wave, lane, m0, M, u0 + 8, nn);
+                fql_scales_issue(rsS, srow, n_ok, G, C2, u0 + 8, nn, hl, zraw);
+            }
             const fq_v4i* stage = lds + (r & 1) * cfg::STG;
 #pragma unroll
             for (int ci = 0; ci < 4; ++ci) {

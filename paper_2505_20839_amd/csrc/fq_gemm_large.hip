@@ -197,6 +197,13 @@ __device__ __forceinline__ void fql_item(
     for (int r = 0; r < 16; ++r) zero[r] = 0.f;
 
     // ---- prologue ----
+    // The scale words of the first zero-point round are requested before anything else and wait in registers until
+    // the main loop is over: asked for at that point, with every compute unit streaming, they take about 5 us.
+    const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
+    const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : FQL_OOB;    // channels past N read zeros
+    fql_raw_scales zraw;
+    if (!LUT) fql_scales_issue(rsS, srow, n_ok, G, C2, 0, ZU < 8 ? ZU : 8, lane >> 5, zraw);
     fql_issue_a<NT>(rsA, abase, m0, K, lds, wave, 0);
     // Packed weights also travel global -> LDS directly, into two 2 KiB buffers private to the wave
     // ([half h][lane][16 bytes], the order they have in memory); buffer g & 1 holds group g.
@@ -362,20 +369,20 @@ __device__ __forceinline__ void fql_item(
         __syncthreads();
     } else {
         constexpr int RT = 32 * NMT;                      // rows of the item
-        const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
-        const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : 0xFFFFFF00u;   // channels past N read zeros
         const int hl = lane >> 5;                         // which half of a chunk's 16 groups this lane holds
         const int rounds = (ZU + 7) >> 3;
         for (int r = 0; r < rounds; ++r) {
             const int u0 = 8 * r;
             const int nu = ZU - u0 < 8 ? ZU - u0 : 8;
-            if (r + 1 < rounds)                           // that stage was last read before the previous barrier
-                fql_issue_z<NMT>(rsZ, lds + ((r + 1) & 1) * FQL_STAGE_CHUNKS, wave, lane, m0, M, u0 + 8,
-                                 ZU - u0 - 8 < 8 ? ZU - u0 - 8 : 8);
-            // gscale operands of this round's chunks: 8 consecutive groups of this lane's channel as fp16
+            // gscale operands of this round's chunks (8 consecutive groups of this lane's channel as fp16), from the
+            // words requested a round ago (the first time: before the main loop)
             fql_v8h sig[4];
-            fql_round_scales(rsS, srow, n_ok, G, C2, u0, nu, hl, sig);
+            fql_scales_finish(zraw, srow, G, C2, u0, hl, sig);
+            if (r + 1 < rounds) {                         // that stage was last read before the previous barrier
+                const int nn = ZU - u0 - 8 < 8 ? ZU - u0 - 8 : 8;
+                fql_issue_z<NMT>(rsZ, lds + ((r + 1) & 1) * FQL_STAGE_CHUNKS, wave, lane, m0, M, u0 + 8, nn);
+                fql_scales_issue(rsS, srow, n_ok, G, C2, u0 + 8, nn, hl, zraw);
+            }
             const fq_v4i* stage = lds + (r & 1) * FQL_STAGE_CHUNKS;
 #pragma unroll
             for (int ci = 0; ci < 4; ++ci) {
@@ -470,10 +477,19 @@ __device__ __forceinline__ void fql_item(
     }
     if (full_tile) {
         // Transpose through LDS so that every store instruction writes whole 256-byte rows.
-        // Registers r, r+1 of a lane are rows rl, rl+1 of its column: one v_cvt_pk_bf16_f32 rounds
-        // both, and the two halves go to their rows with 16-bit LDS writes.
+        // A step covers four rows of the lane's channel (registers 4 j .. 4 j + 3).  The four lanes of a quad hold
+        // the same four rows of four neighbouring channels: a 4 x 4 transpose inside the quad (bf16 pairs, two
+        // exchanges by DPP) leaves lane q of the quad with row q of the step for all four channels, 8 bytes that
+        // go to LDS in one write -- a quarter of the LDS instructions that one 16-bit write per value takes.
+        // LDS tile: 256 bytes per row, no padding; the 64-byte segment of wave w in row r sits at segment
+        // w ^ (r & 3), so that the four rows a quad writes fall on different segments (two per bank half: the
+        // least a 512-byte instruction can do).
         char* tile = reinterpret_cast<char*>(lds);
-        char* wcol = tile + 4 * (lane >> 5) * FQL_OUT_STRIDE + (wave * 32 + (lane & 31)) * 2;
+        const int q4 = lane & 3;                          // row of the step this lane ends up with
+        char* wrow = tile + (4 * (lane >> 5) + q4) * 256 + ((wave ^ q4) * 64) + (lane & 28) * 2;
+        const bool oddl = lane & 1, upper = (lane & 2) != 0;
+        // byte selectors of v_perm_b32 (operand order {partner, own}: bytes 0-3 own, 4-7 partner)
+        const unsigned sel_a = oddl ? 0x03020706u : 0x05040100u;   // even: (own.lo, partner.lo); odd: (partner.hi, own.hi)
         // The row factors are fetched from LDS three steps (of four rows) ahead of their use: the
         // compiler may not move these reads across the tile writes, so the distance is spelled out.
         constexpr int AHEAD = 3;
@@ -489,25 +505,34 @@ __device__ __forceinline__ void fql_item(
             const fq_v4f sc4 = scq[it % (AHEAD + 1)];
             fq_v4f res = {0.f, 0.f, 0.f, 0.f};
             if (add_full) {                               // this lane's four residual values (see the loads above)
-                const bool odd = lane & 1;
                 const unsigned d0 = rres[it][0], d1 = rres[it][1];
                 const unsigned p0 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d0, 0xB1, 0xF, 0xF, false);
                 const unsigned p1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)d1, 0xB1, 0xF, 0xF, false);
-                const unsigned a[4] = {odd ? p0 : d0, odd ? p1 : d1, odd ? d0 : p0, odd ? d1 : p1};
-                const unsigned sh = odd ? 0u : 16u;
+                const unsigned a[4] = {oddl ? p0 : d0, oddl ? p1 : d1, oddl ? d0 : p0, oddl ? d1 : p1};
+                const unsigned sh = oddl ? 0u : 16u;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) res[e] = __uint_as_float((a[e] << sh) & 0xFFFF0000u);
             }
+            unsigned pk[2];                               // (row 0, row 1) and (row 2, row 3) of this lane's channel
 #pragma unroll
             for (int e = 0; e < 4; e += 2) {
                 const fq_v2f pr = add_full ? (fq_v2f){fmaf(acc[mt][4 * j + e], sc4[e], res[e]),
                                                       fmaf(acc[mt][4 * j + e + 1], sc4[e + 1], res[e + 1])}
                                            : (fq_v2f){acc[mt][4 * j + e] * sc4[e], acc[mt][4 * j + e + 1] * sc4[e + 1]};
-                const unsigned pk = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, fq_v2bf));
-                char* dst = wcol + (8 * it + e) * FQL_OUT_STRIDE;
-                *reinterpret_cast<unsigned short*>(dst) = (unsigned short)pk;
-                *reinterpret_cast<unsigned short*>(dst + FQL_OUT_STRIDE) = (unsigned short)(pk >> 16);
+                pk[e >> 1] = __builtin_bit_cast(unsigned, __builtin_convertvector(pr, fq_v2bf));
             }
+            // lanes (0,1) and (2,3) of the quad swap halves: even lanes then hold rows 0 and 2, odd lanes rows 1 and 3,
+            // each for the pair's two channels
+            const unsigned n0p = (unsigned)__builtin_amdgcn_update_dpp(0, (int)pk[0], 0xB1, 0xF, 0xF, false);
+            const unsigned n1p = (unsigned)__builtin_amdgcn_update_dpp(0, (int)pk[1], 0xB1, 0xF, 0xF, false);
+            const unsigned a0 = __builtin_amdgcn_perm(n0p, pk[0], sel_a);   // row 0 (even) / row 1 (odd), channels of the pair
+            const unsigned a1 = __builtin_amdgcn_perm(n1p, pk[1], sel_a);   // row 2 (even) / row 3 (odd)
+            // the two pairs of the quad swap: lanes 0, 1 keep rows 0, 1 and receive the other pair's channels of
+            // them, lanes 2, 3 keep rows 2, 3
+            const unsigned give = upper ? a0 : a1;
+            const unsigned got = (unsigned)__builtin_amdgcn_update_dpp(0, (int)give, 0x4E, 0xF, 0xF, false);
+            const fq_v2i out = upper ? (fq_v2i){(int)got, (int)a1} : (fq_v2i){(int)a0, (int)got};
+            *reinterpret_cast<fq_v2i*>(wrow + it * (8 * 256)) = out;
         }
         __syncthreads();
         // wave w stores rows 8*NMT*w ..., four rows of 256 bytes per instruction; the row steps
@@ -515,10 +540,12 @@ __device__ __forceinline__ void fql_item(
         const __amdgpu_buffer_rsrc_t rsY = __builtin_amdgcn_make_buffer_rsrc(
             Y + (size_t)(m0 + wave * (8 * NMT)) * N + n0, 0, (int)((unsigned)(8 * NMT) * (unsigned)N * 2u), 0x00020000);
         const unsigned ylane = (unsigned)(lane >> 4) * (unsigned)N * 2u + (unsigned)(lane & 15) * 16u;
-        const char* rd = tile + (wave * (8 * NMT) + (lane >> 4)) * FQL_OUT_STRIDE + (lane & 15) * 16;
+        // (row R of the tile keeps its segment s at s ^ (R & 3); R & 3 = (lane / 16) & 3 for every row this lane reads)
+        const int rq = (lane >> 4) & 3, ch = lane & 15;
+        const char* rd = tile + (wave * (8 * NMT) + (lane >> 4)) * 256 + (((ch >> 2) ^ rq) * 64) + (ch & 3) * 16;
 #pragma unroll
         for (int j = 0; j < 2 * NMT; ++j) {
-            const fq_v4i v = *reinterpret_cast<const fq_v4i*>(rd + 4 * j * FQL_OUT_STRIDE);
+            const fq_v4i v = *reinterpret_cast<const fq_v4i*>(rd + 4 * j * 256);
             __builtin_amdgcn_raw_buffer_store_b128(v, rsY, ylane, 4 * j * N * 2, 0);
         }
         return;

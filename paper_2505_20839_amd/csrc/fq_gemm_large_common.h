@@ -133,37 +133,45 @@ __device__ __forceinline__ fq_v8i fql_unpack_chunk_lut(fq_v4i w, fq_v4i t) {
 // array's last word may hold fewer than four scales, and a word that crosses the end of the range would read as
 // zero; the array is 16-byte aligned, so that word lies in the same cache line as its valid bytes).  Everything
 // that is not wanted -- a chunk past the round's units, groups past G, a channel past N -- is requested out of
-// range and reads as zero, so all the loads are issued back to back without a branch and the round waits for
-// memory once.
-__device__ __forceinline__ void fql_round_scales(__amdgpu_buffer_rsrc_t rsS, unsigned srow, bool n_ok, int G, int C2,
-                                                 int u0, int nu, int hl, fql_v8h sig[4]) {
+// range and reads as zero, so all the loads are issued back to back without a branch.
+// Two halves, so that the loads can be issued long before their use (under load they take several microseconds):
+// fql_scales_issue requests the raw words, fql_scales_finish turns them into operands.
+struct fql_raw_scales { unsigned d[4][3]; };
+
+__device__ __forceinline__ void fql_scales_issue(__amdgpu_buffer_rsrc_t rsS, unsigned srow, bool n_ok, int G, int C2,
+                                                 int u0, int nu, int hl, fql_raw_scales& raw) {
     const bool unaligned_rows = (G & 3) != 0;             // (the array itself is 16-byte aligned)
-    unsigned d[4][3], o[4];
-    int g0[4];
 #pragma unroll
     for (int ci = 0; ci < 4; ++ci) {
         const int c = ((u0 + 2 * ci) % C2) >> 1;          // chunk index inside its plane
-        g0[ci] = 16 * c + 8 * hl;
-        o[ci] = srow + (unsigned)g0[ci];
-        const unsigned ob = (2 * ci < nu && n_ok && g0[ci] < G) ? (o[ci] & ~3u) : FQL_OOB;
+        const int g0 = 16 * c + 8 * hl;
+        const unsigned o = srow + (unsigned)g0;
+        const unsigned ob = (2 * ci < nu && n_ok && g0 < G) ? (o & ~3u) : FQL_OOB;
         // one load instruction per chunk: the address path takes as long for a lane's 4 bytes as for its 12
         if (unaligned_rows) {
             typedef unsigned v3u __attribute__((ext_vector_type(3)));
             const v3u t = __builtin_bit_cast(v3u, __builtin_amdgcn_raw_buffer_load_b96(rsS, ob, 0, 0));
-            d[ci][0] = t[0]; d[ci][1] = t[1]; d[ci][2] = t[2];
+            raw.d[ci][0] = t[0]; raw.d[ci][1] = t[1]; raw.d[ci][2] = t[2];
         } else {
             typedef unsigned v2u __attribute__((ext_vector_type(2)));
             const v2u t = __builtin_bit_cast(v2u, __builtin_amdgcn_raw_buffer_load_b64(rsS, ob, 0, 0));
-            d[ci][0] = t[0]; d[ci][1] = t[1]; d[ci][2] = 0u;
+            raw.d[ci][0] = t[0]; raw.d[ci][1] = t[1]; raw.d[ci][2] = 0u;
         }
     }
+}
+
+__device__ __forceinline__ void fql_scales_finish(const fql_raw_scales& raw, unsigned srow, int G, int C2, int u0, int hl,
+                                                  fql_v8h sig[4]) {
 #pragma unroll
     for (int ci = 0; ci < 4; ++ci) {
+        const int c = ((u0 + 2 * ci) % C2) >> 1;
+        const int g0 = 16 * c + 8 * hl;
+        const unsigned o = srow + (unsigned)g0;
         unsigned w[2];
-        w[0] = __builtin_amdgcn_alignbyte(d[ci][1], d[ci][0], o[ci] & 3u);
-        w[1] = __builtin_amdgcn_alignbyte(d[ci][2], d[ci][1], o[ci] & 3u);
+        w[0] = __builtin_amdgcn_alignbyte(raw.d[ci][1], raw.d[ci][0], o & 3u);
+        w[1] = __builtin_amdgcn_alignbyte(raw.d[ci][2], raw.d[ci][1], o & 3u);
         // bytes of groups >= G belong to the next channel: cleared
-        const int nv = G - g0[ci];                        // valid groups from g0 on
+        const int nv = G - g0;                            // valid groups from g0 on
         if (nv < 4) w[0] &= nv <= 0 ? 0u : (1u << (8 * nv)) - 1u;
         if (nv < 8) w[1] &= nv <= 4 ? 0u : (1u << (8 * (nv - 4))) - 1u;
         fq_v4i pk;
