@@ -224,6 +224,47 @@ def main() -> int:
                 "frac_mfma_peak": flop / per[len(per) // 2] / 1e12 / PEAK_FP8_TFLOPS,
                 "rel_frobenius_distance_from_exact_mode": rel}
 
+    def ffn_chain(wl="ffn_l2_7b_gateup_swiglu"):
+        """The gate/up layer with its fused epilogue followed by the quantisation of its output for the down
+        projection: the separate quantiser (fq_w4a8_gemm_swiglu_ws + fq_quantize_act_ws, which searches each row for
+        its largest magnitude) against fq_w4a8_gemm_swiglu_quant_ws (row maxima raised by the GEMM's epilogue, then an
+        element-wise kernel); both leave the same codes, scales and prepared workspace."""
+        w, d, X, packed, gs = upload(wl)
+        NH = w.N // 2
+        need = fq.fq_w4a8_gemm_workspace_bytes(w.M, w.N, w.K)
+        ws = torch.empty((need,), dtype=torch.uint8, device="cuda")
+        A, a_s = fq.fq_quantize_act(X, workspace=ws)
+        ws_next = torch.empty((fq.fq_w4a8_gemm_workspace_bytes(w.M, 4096, NH),), dtype=torch.uint8, device="cuda")
+        H = torch.empty((w.M, NH), dtype=torch.bfloat16, device="cuda")
+
+        def separate():
+            fq.fq_w4a8_gemm_swiglu(A, a_s, packed, gs, d["w_tscale"], w.N, out=H, workspace=ws, workspace_prepared=True)
+            fq.fq_quantize_act(H, workspace=ws_next)
+
+        def fused():
+            fq.fq_w4a8_gemm_swiglu_quant(A, a_s, packed, gs, d["w_tscale"], w.N, out=H, workspace=ws,
+                                         workspace_prepared=True, next_workspace=ws_next)
+
+        res = {"workload": wl, "M": w.M, "N": w.N, "K": w.K}
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for key, fn in (("separate_quantiser_us", separate), ("fused_row_maximum_us", fused)):
+                fn()
+                side.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g, stream=side):
+                    for _ in range(LARGE_GRAPH_STEPS):
+                        fn()
+                _, ev = timed_series(side, g, MIN_LAUNCHES // LARGE_GRAPH_STEPS)
+                per = sorted(t / MIN_LAUNCHES for t in ev)
+                res[key] = per[len(per) // 2] * 1e6
+                res[key + "_best"] = per[0] * 1e6
+                del g
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.empty_cache()
+        return res
+
     def attention_operands(H=128, R=4, T=4096):
         """Decode attention operands on an INT4 key/value cache (fq_kv4_scores, fq_kv4_output): Llama3-8B, a batch of
         16 sequences x 8 key/value heads, 4 query heads each, 4096 cached tokens; HBM rate of the algorithmic bytes
@@ -425,6 +466,7 @@ def main() -> int:
             torch.cuda.empty_cache()
         out["other_configs"] = others
         out["table_mode"] = table_mode(name)
+        out["ffn_chain"] = ffn_chain()
         out["attention_operands"] = attention_operands()
         # the offline step that produces the weight operands, on the gate/up matrix of the same model
         out["offline_quantiser"] = offline_quantiser(11008, 4096)

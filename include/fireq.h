@@ -189,6 +189,27 @@ int fq_pack_weights(const int8_t *q, uint8_t *Wq_packed, int N, int K, void *str
 int fq_unpack_weights(const uint8_t *Wq_packed, int8_t *q, int N, int K, void *stream);
 
 /*
+ * The fused gate/up layer of fq_w4a8_gemm_swiglu_ws whose output also leaves as the FP8 input of the
+ * next layer (Sec. 3.1.1 step 3, Fig. 1: the feed-forward chain without a separate pass that searches
+ * every row for its largest magnitude): H_bf16 [M, N/2] as before, and H_fp8 [M, N/2] (E4M3 codes,
+ * 16-byte aligned) with h_scale [M] exactly as fq_quantize_act gives them for H_bf16, bit for bit.
+ * The per-token scale of eq. 2 is a maximum over a whole row, which the workgroups of all the row's
+ * tiles produce, so no code can be written before every tile is done: the GEMM's epilogue raises the
+ * row maxima (kept in h_scale meanwhile) with one atomic per row and tile, and a second, element-wise
+ * kernel turns H_bf16 into codes.  N/2 must be a multiple of 8.  With next_workspace != NULL
+ * (fq_w4a8_gemm_workspace_bytes(M, N', N/2) bytes or more, N' the next layer's width; needs M > 64 and
+ * N/2 a multiple of 128, at most 16384) that kernel also prepares the workspace of a GEMM that takes
+ * H_fp8 as its input (workspace_prepared = 1 there), as fq_quantize_act_ws does.  For M <= 64 the call
+ * runs the fused gate/up GEMM and the plain quantiser.  Other arguments, workspace and status codes as
+ * for fq_w4a8_gemm_swiglu_ws; allocates nothing, keeps no state, never synchronises.
+ */
+int fq_w4a8_gemm_swiglu_quant_ws(const uint8_t *A_fp8, const float *a_scale, const uint8_t *Wq_packed,
+                                 const uint8_t *w_gscale, float w_tscale, uint16_t *H_bf16,
+                                 uint8_t *H_fp8, float *h_scale, int M, int N, int K,
+                                 void *workspace, size_t workspace_bytes, int workspace_prepared,
+                                 void *next_workspace, size_t next_workspace_bytes, void *stream);
+
+/*
  * A whole linear layer from bfloat16 activations: the quantiser of Sec. 2.1 eq. 2 followed by the
  * GEMM of Sec. 2.2 eq. 3, with the result fq_quantize_act + fq_w4a8_gemm_ws give, bit for bit.
  * For M <= 6 and K <= 4096 (decode) it is ONE kernel: every workgroup quantises the few rows of

@@ -56,6 +56,9 @@ def lib() -> ctypes.CDLL:
     L.fq_w4a8_gemm_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
     L.fq_w4a8_gemm_add_ws.restype = ci
     L.fq_w4a8_gemm_add_ws.argtypes = [vp, vp, vp, vp, cf, vp, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
+    L.fq_w4a8_gemm_swiglu_quant_ws.restype = ci
+    L.fq_w4a8_gemm_swiglu_quant_ws.argtypes = [vp, vp, vp, vp, cf, vp, vp, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp,
+                                               ctypes.c_size_t, vp]
     L.fq_w4a8_gemm_swiglu_ws.restype = ci
     L.fq_w4a8_gemm_swiglu_ws.argtypes = [vp, vp, vp, vp, cf, vp, ci, ci, ci, vp, ctypes.c_size_t, ci, vp]
     L.fq_quantize_act_ws.restype = ci
@@ -282,6 +285,46 @@ def fq_w4a8_gemm_swiglu(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_swiglu_ws")
     return out
+
+
+def fq_w4a8_gemm_swiglu_quant(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor,
+                              w_gscale: torch.Tensor, w_tscale: float, N: int,
+                              out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                              workspace_prepared: bool = False, next_workspace: Optional[torch.Tensor] = None
+                              ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """(H bf16 [M,N/2], H as E4M3 codes [M,N/2], float32 [M] scales): fq_w4a8_gemm_swiglu whose output also leaves
+    quantised for the next layer, as fq_quantize_act would give it.  Calls fq_w4a8_gemm_swiglu_quant_ws;
+    `next_workspace` (fq_w4a8_gemm_workspace_bytes(M, N', N/2) bytes or more) is prepared for a GEMM on the codes."""
+    A = _dev(A, torch.uint8, "A")
+    a_scale = _dev(a_scale, torch.float32, "a_scale")
+    Wq_packed = _dev(Wq_packed, torch.uint8, "Wq_packed")
+    w_gscale = _dev(w_gscale, torch.uint8, "w_gscale")
+    M, K = A.shape
+    if N % 2 or a_scale.numel() != M or K % GROUP or w_gscale.numel() != N * (K // GROUP) \
+            or Wq_packed.numel() < fq_packed_weight_bytes(N, K):
+        raise FireqError(-2, "fq_w4a8_gemm_swiglu_quant")
+    if out is None:
+        out = torch.empty((M, N // 2), dtype=torch.bfloat16, device=A.device)
+    else:
+        out = _dev(out, torch.bfloat16, "out")
+        if tuple(out.shape) != (M, N // 2):
+            raise FireqError(-2, "fq_w4a8_gemm_swiglu_quant")
+    codes = torch.empty((M, N // 2), dtype=torch.uint8, device=A.device)
+    scales = torch.empty((M,), dtype=torch.float32, device=A.device)
+    need = lib().fq_w4a8_gemm_workspace_bytes(M, N, K)
+    if workspace is None and need > 0:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=A.device)
+    ws_ptr, ws_bytes = (workspace.data_ptr(), workspace.numel() * workspace.element_size()) if workspace is not None else (0, 0)
+    nws_ptr, nws_bytes = (next_workspace.data_ptr(), next_workspace.numel() * next_workspace.element_size()) \
+        if next_workspace is not None else (0, 0)
+    rc = lib().fq_w4a8_gemm_swiglu_quant_ws(A.data_ptr(), a_scale.data_ptr(), Wq_packed.data_ptr(),
+                                            w_gscale.data_ptr(), ctypes.c_float(float(w_tscale)), out.data_ptr(),
+                                            codes.data_ptr(), scales.data_ptr(), M, N, K, ws_ptr, ws_bytes,
+                                            1 if (workspace_prepared and workspace is not None) else 0,
+                                            nws_ptr, nws_bytes, _stream())
+    if rc != 0:
+        raise FireqError(rc, "fq_w4a8_gemm_swiglu_quant_ws")
+    return out, codes, scales
 
 
 def fq_w4a8_gemm_add(A: torch.Tensor, a_scale: torch.Tensor, Wq_packed: torch.Tensor,

@@ -292,6 +292,50 @@ int fq_w4a8_gemm_swiglu_ws(const uint8_t* A_fp8, const float* a_scale, const uin
                    workspace_prepared, true, nullptr, false, stream);
 }
 
+int fq_w4a8_gemm_swiglu_quant_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed,
+                                 const uint8_t* w_gscale, float w_tscale, uint16_t* H_bf16,
+                                 uint8_t* H_fp8, float* h_scale, int M, int N, int K,
+                                 void* workspace, size_t workspace_bytes, int workspace_prepared,
+                                 void* next_workspace, size_t next_workspace_bytes, void* stream) {
+    const int rc = check_gemm_args(A_fp8, a_scale, Wq_packed, w_gscale, H_bf16, M, N, K);
+    if (rc != FQ_OK) return rc;
+    if (N & 1) return FQ_ERR_SHAPE;
+    if (M == 0) return FQ_OK;
+    const int NH = N / 2;
+    if ((NH % 8) != 0) return FQ_ERR_SHAPE;               // the quantiser works on whole 16-byte chunks of a row
+    if (!H_fp8 || !h_scale) return FQ_ERR_NULL;
+    if (!aligned16(H_fp8)) return FQ_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // zero-point terms for a GEMM that takes H_fp8 as its input: only where that GEMM has a workspace and the
+    // quantiser can write them (rows of at most 16384 codes, whole groups)
+    const bool next_large = next_workspace != nullptr && choose_kernel(M) == GemmKernel::Large &&
+                            (NH % FQ_GROUP) == 0 && fq_quantize_can_write_zero_point(NH);
+    if (next_workspace) {
+        if (!next_large) return FQ_ERR_SHAPE;
+        if (next_workspace_bytes < fq_gemm_large_workspace_bytes(M, NH)) return FQ_ERR_MEMORY;
+        if (!aligned16(next_workspace)) return FQ_ERR_ALIGN;
+    }
+    const bool fused = choose_kernel(M) == GemmKernel::Large;
+    const size_t need = fq_w4a8_gemm_workspace_bytes(M, N, K);
+    if (need > 0) {
+        if (!workspace || workspace_bytes < need) return FQ_ERR_MEMORY;
+        if (!aligned16(workspace)) return FQ_ERR_ALIGN;
+    }
+    if (fused) {
+        fq_launch_fill_zero(reinterpret_cast<unsigned*>(h_scale), M, s);   // the row maxima start at zero
+        fq_launch_gemm_large(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, H_bf16, M, N, K, workspace,
+                             workspace_prepared != 0, true, nullptr, s, false, reinterpret_cast<unsigned*>(h_scale));
+        fq_launch_quantize_known(H_bf16, H_fp8, h_scale, M, NH, next_workspace, s);
+        return after_launch();
+    }
+    // M <= 64 (or a kernel forced from outside): the fused gate/up GEMM, then the plain quantiser
+    const int g = fq_w4a8_gemm_swiglu_ws(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, H_bf16, M, N, K, workspace,
+                                         workspace_bytes, workspace_prepared, stream);
+    if (g != FQ_OK) return g;
+    fq_launch_quantize(H_bf16, H_fp8, h_scale, M, NH, s);
+    return after_launch();
+}
+
 namespace {
 
 inline size_t round16(size_t v) { return (v + 15u) & ~(size_t)15u; }

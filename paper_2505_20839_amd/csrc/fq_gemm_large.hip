@@ -158,7 +158,7 @@ __device__ __forceinline__ void fql_item(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K,
     int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, const int swiglu,
-    const uint16_t* R) {
+    const uint16_t* R, unsigned* rowmax = nullptr) {
     constexpr int NT = NMT;                               // A transfers per wave and stage
     const int G = K / FQ_GROUP;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -454,6 +454,23 @@ __device__ __forceinline__ void fql_item(
             for (int j = 0; j < NMT; ++j) {
                 const fq_v4i v = *reinterpret_cast<const fq_v4i*>(rd + 8 * j * HS);
                 __builtin_amdgcn_raw_buffer_store_b128(v, rsH, hlane, 8 * j * NH * 2, 0);
+                if (rowmax) {
+                    // largest |H| of this row's 64 columns of the tile: bf16 magnitudes order like 16-bit integers;
+                    // the 8 lanes of a row fold theirs and one of them raises the row's maximum (the bits of the
+                    // number as FP32), which the quantiser of the next layer takes its scale from
+                    typedef unsigned short v2us __attribute__((ext_vector_type(2)));
+                    v2us mx = __builtin_bit_cast(v2us, (unsigned)v[0] & 0x7FFF7FFFu);
+#pragma unroll
+                    for (int e = 1; e < 4; ++e)
+                        mx = __builtin_elementwise_max(mx, __builtin_bit_cast(v2us, (unsigned)v[e] & 0x7FFF7FFFu));
+                    unsigned m16 = mx[0] > mx[1] ? mx[0] : mx[1];
+#pragma unroll
+                    for (int o = 1; o < 8; o <<= 1) {
+                        const unsigned other = (unsigned)__shfl_xor((int)m16, o, 64);
+                        m16 = other > m16 ? other : m16;
+                    }
+                    if ((lane & 7) == 0) atomicMax(&rowmax[m0 + wave * (8 * NMT) + (lane >> 3) + 8 * j], m16 << 16);
+                }
             }
             return;
         }
@@ -469,7 +486,9 @@ __device__ __forceinline__ void fql_item(
                 if (m0 + ml < M && (lane & 1) == 0) {
                     fq_v2f pr = {fq_silu_mul(f, up), 0.f};
                     fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
-                    Y[(size_t)(m0 + ml) * NH + (n >> 1)] = __builtin_bit_cast(unsigned short, pk[0]);
+                    const unsigned short hb = __builtin_bit_cast(unsigned short, pk[0]);
+                    Y[(size_t)(m0 + ml) * NH + (n >> 1)] = hb;
+                    if (rowmax) atomicMax(&rowmax[m0 + ml], ((unsigned)hb & 0x7FFFu) << 16);
                 }
             }
         }
@@ -575,13 +594,14 @@ void fq_gemm_large_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
     const uint8_t* __restrict__ gs, float tscale, uint16_t* Y, int M, int N, int K,
     int tiles_m, int tiles_n, int slots, int pm, const uint16_t* __restrict__ planes, unsigned full_wgs,
-    int swiglu, const uint16_t* R) {
+    int swiglu, const uint16_t* R, unsigned* rowmax) {
     extern __shared__ fq_v4i lds[];                       // 2 A stages (64 KiB) + 4 x 4 KiB of packed weights
     if (blockIdx.x < full_wgs)
-        fql_item<8>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, swiglu, R);
+        fql_item<8>(lds, blockIdx.x, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, swiglu, R,
+                    rowmax);
     else
         fql_item<4>(lds, blockIdx.x - full_wgs, A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes,
-                    swiglu, R);
+                    swiglu, R, rowmax);
 }
 
 // The table mode of the same items (no zero-point planes).
@@ -631,7 +651,7 @@ void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipSt
 
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
-                          bool swiglu, const uint16_t* R, hipStream_t stream, bool lut) {
+                          bool swiglu, const uint16_t* R, hipStream_t stream, bool lut, unsigned* rowmax) {
     static fq_device_once attr_once;
     fq_once_per_device(attr_once, [] {
         (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_large_kernel),
@@ -661,5 +681,5 @@ void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t*
     }
     hipLaunchKernelGGL(fq_gemm_large_kernel, dim3(full_wgs + half_wgs), dim3(FQL_THREADS), FQL_LDS_BYTES, stream,
                        A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, slots, pm, planes, full_wgs,
-                       swiglu ? 1 : 0, R);
+                       swiglu ? 1 : 0, R, swiglu ? rowmax : nullptr);
 }

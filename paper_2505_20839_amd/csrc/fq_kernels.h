@@ -31,6 +31,12 @@ void fq_launch_quantize(const uint16_t* X, uint8_t* A, float* a_scale, int M, in
 // The same, also filling the large-M GEMM's workspace (fq_gemm_large_workspace_bytes(M, K)) with the
 // zero-point terms of A; only for shapes fq_quantize_can_write_zero_point(K) accepts.
 bool fq_quantize_can_write_zero_point(int K);
+// fq_launch_quantize_known: the same quantiser for rows whose largest magnitude is already known: a_scale[m] holds
+// it on entry (the bits of the number as FP32, as the fused gate/up epilogue leaves it) and the scale on return;
+// workspace may be null (no zero-point terms written).
+void fq_launch_quantize_known(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, void* workspace,
+                              hipStream_t stream);
+void fq_launch_fill_zero(unsigned* p, int n, hipStream_t stream);
 void fq_launch_quantize_zp(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, void* workspace,
                            hipStream_t stream);
 
@@ -61,7 +67,8 @@ void fq_gemm_large_plan(int M, int N, int cus, int out[4]);
 void fq_launch_zero_point(const uint8_t* A, void* workspace, int M, int K, hipStream_t stream);
 void fq_launch_gemm_large(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
-                          bool swiglu, const uint16_t* R, hipStream_t stream, bool lut = false);
+                          bool swiglu, const uint16_t* R, hipStream_t stream, bool lut = false,
+                          unsigned* rowmax = nullptr);   // (fused gate/up only: row maxima of |H|, see the kernel)
 // M <= 64 only; returns false (nothing enqueued) for a shape it does not serve.
 bool fq_launch_gemm_small(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                           float tscale, uint16_t* Y, int M, int N, int K, bool swiglu, const uint16_t* R,

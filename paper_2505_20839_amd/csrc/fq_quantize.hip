@@ -41,7 +41,9 @@ __device__ __forceinline__ float fq_sum8(fq_v2i o) {
 // kernels take from their workspace: -2^-6 * (sum of the group's E4M3 values) as two fp16 terms,
 // laid out as that kernel reads it ([plane][group / 8][M rows][group % 8]; groups up to the next
 // multiple of 16 are zero).  Needs K % 128 == 0 and the row in registers.
-template <bool ZP>
+// KNOWN: the row's largest magnitude is not searched for but taken from a_scale[m], where the kernel that
+// produced X left it (the fused gate/up epilogue); the scale replaces it there.
+template <bool ZP, bool KNOWN = false>
 __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_t* __restrict__ X,
                                                                    uint8_t* __restrict__ A,
                                                                    float* __restrict__ a_scale, int K,
@@ -68,10 +70,12 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
             keep[i] = (fq_v4i){0, 0, 0, 0};
             if (c < nchunk) {
                 keep[i] = x[c];
+                if (!KNOWN) {
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    unsigned w = (unsigned)keep[i][j];
-                    amax = fmaxf(amax, fmaxf(fabsf(fq_bf16_lo(w)), fabsf(fq_bf16_hi(w))));
+                    for (int j = 0; j < 4; ++j) {
+                        unsigned w = (unsigned)keep[i][j];
+                        amax = fmaxf(amax, fmaxf(fabsf(fq_bf16_lo(w)), fabsf(fq_bf16_hi(w))));
+                    }
                 }
             }
         }
@@ -85,7 +89,13 @@ __global__ __launch_bounds__(FQ_Q_THREADS) void fq_quantize_kernel(const uint16_
             }
         }
     }
-    amax = fq_block_max(amax, red);
+    if (KNOWN) {                                          // (read by one thread before anyone overwrites it below)
+        if (threadIdx.x == 0) red[0] = a_scale[m];
+        __syncthreads();
+        amax = red[0];
+    } else {
+        amax = fq_block_max(amax, red);
+    }
     const float s = (amax == 0.f) ? 1.0f : amax / 448.0f;
     if (threadIdx.x == 0) a_scale[m] = s;
     const float rcp = 1.0f / s;
@@ -144,6 +154,25 @@ void fq_launch_quantize(const uint16_t* X, uint8_t* A, float* a_scale, int M, in
 
 bool fq_quantize_can_write_zero_point(int K) {
     return (K % FQ_GROUP) == 0 && (K >> 3) <= FQ_Q_THREADS * FQ_Q_MAXCHUNK;
+}
+
+void fq_launch_quantize_known(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, void* workspace,
+                              hipStream_t stream) {
+    if (workspace)
+        hipLaunchKernelGGL((fq_quantize_kernel<true, true>), dim3((unsigned)M), dim3(FQ_Q_THREADS), 0, stream, X, A, a_scale,
+                           K, static_cast<uint16_t*>(workspace), M);
+    else
+        hipLaunchKernelGGL((fq_quantize_kernel<false, true>), dim3((unsigned)M), dim3(FQ_Q_THREADS), 0, stream, X, A, a_scale,
+                           K, static_cast<uint16_t*>(nullptr), M);
+}
+
+__global__ void fq_fill_zero_kernel(unsigned* __restrict__ p, int n) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < n) p[i] = 0u;
+}
+
+void fq_launch_fill_zero(unsigned* p, int n, hipStream_t stream) {
+    hipLaunchKernelGGL(fq_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream, p, n);
 }
 
 void fq_launch_quantize_zp(const uint16_t* X, uint8_t* A, float* a_scale, int M, int K, void* workspace,
