@@ -11,7 +11,7 @@
 //     NMT = 4, NW = 2, KS = 4   128 x 64 tiles, K quartered: for 64 < M <= 512 (batched decode, chunked
 //                               prefill), where 128-channel tiles are too few and the small-M kernels
 //                               re-read the activations once per compute unit from L2
-// One workgroup per compute unit (160 KiB of LDS, two waves per SIMD).
+// One workgroup per compute unit (128 or 160 KiB of LDS, two waves per SIMD).
 //
 // K slices: when even these tiles are fewer than the compute units, S workgroups share a tile, each taking a
 // contiguous 1/S of the groups (and splitting that among its waves as above).  A workgroup's loop is bound by
@@ -31,7 +31,7 @@
 
 namespace {
 
-// LDS: KS * 2 stages of 32 * NMT rows x 128 bytes, then 8 x 4 KiB of packed weights; reused for the fold
+// LDS: KS * 2 stages of 32 * NMT rows x 128 bytes, then (256 x 128 shape) 8 x 4 KiB of packed weights; reused for the fold
 // (8 waves x NMT tiles of 4 KiB, half of them at a time), the zero-point units and the output tile.
 template <int NMT, int NW, int KS>
 struct fqk_cfg {

@@ -291,9 +291,10 @@ void fq_gemm_small16_kernel(
         if (j < NSUB) {
             float v = 0.f, vu = 0.f;
 #pragma unroll
-            for (int w = 0; w < FQS16_WAVES; ++w) {
-                v += red[w][j][r][l];
-                vu += red[w][j][r][l | 1];                // the up channel of an even (gate) channel
+            for (int w = 0; w < FQS16_WAVES; ++w) v += red[w][j][r][l];
+            if (swiglu) {                                 // the up channel of an even (gate) channel
+#pragma unroll
+                for (int w = 0; w < FQS16_WAVES; ++w) vu += red[w][j][r][l | 1];
             }
             const int m = 4 * (l >> 4) + r;
             const int c = 16 * j + (l & 15);
@@ -549,9 +550,10 @@ void fq_gemm_smallm_kernel(
         if (t < MT) {
             float v = 0.f, vu = 0.f;
 #pragma unroll
-            for (int w = 0; w < FQS16_WAVES; ++w) {
-                v += red[w * (MT * NSUB * 256) + idx];
-                vu += red[w * (MT * NSUB * 256) + (idx | 1)];   // the up channel of an even (gate) channel
+            for (int w = 0; w < FQS16_WAVES; ++w) v += red[w * (MT * NSUB * 256) + idx];
+            if (swiglu) {                                 // the up channel of an even (gate) channel
+#pragma unroll
+                for (int w = 0; w < FQS16_WAVES; ++w) vu += red[w * (MT * NSUB * 256) + (idx | 1)];
             }
             const int m = 16 * t + 4 * (l >> 4) + r;
             const int c = 16 * j + (l & 15);
