@@ -66,8 +66,9 @@ enum {
  * then); it may be reused or freed once the work enqueued by the call has finished.  With
  * workspace_prepared == 0 the call fills the workspace itself (one more small kernel); with
  * workspace_prepared != 0 it takes the contents as they are, which must then have been written
- * by fq_quantize_act_ws for this very A_fp8 (same M and K).  That variant allocates nothing,
- * keeps no state and never synchronises.  fq_w4a8_gemm is the same call on a workspace the library owns: one device
+ * by fq_quantize_act_ws for this very A_fp8 (same M and K); a prepared workspace serves any number of
+ * GEMMs on that A_fp8, one after the other (calls that overlap in time on one workspace race on it).
+ * That variant allocates nothing, keeps no state and never synchronises.  fq_w4a8_gemm is the same call on a workspace the library owns: one device
  * buffer for the whole process that grows (hipFree + hipMalloc, which synchronise the device)
  * when a call needs more than any call before it, so calls that overlap on different streams
  * race on it, and a first call must not be made under stream capture.
