@@ -81,8 +81,11 @@ __device__ __forceinline__ fq_v8i fqk_join(fq_v4i lo, fq_v4i hi) {
 // w * NSUB .. of 16 tokens each.  Lane l = 16 * kq + r holds, of the A operand, dimensions 32 kq .. of query
 // row r, and of the B operand the same dimensions of token r of the sub-tile: one 16-byte chunk of the
 // packed cache.  MT row tiles of 16 queries share every unpacked operand.
+// WIDE (T a multiple of 4, S 8-byte aligned): a lane ends up with 4 rows x 1 token; the four lanes of a quad hold the
+// same rows of four neighbouring tokens, and a 4 x 4 transpose of bf16 pairs inside the quad (two DPP exchanges)
+// leaves each lane with one row x four tokens = one 8-byte store instead of four 2-byte ones.
 #define FQK_S_NSUB 4
-template <int MT>
+template <int MT, bool WIDE>
 __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
     const uint8_t* __restrict__ Q, const float* __restrict__ q_scale, const uint8_t* __restrict__ kp,
     const uint8_t* __restrict__ ks, float out_scale, uint16_t* __restrict__ S, int R, int T) {
@@ -131,13 +134,33 @@ __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
 #pragma unroll
         for (int m = 0; m < MT; ++m) {
             const fq_v4f p = FQ_MFMA16(a[m], b, c0[m]);
+            if (WIDE) {
+                const fq_v2f pr0 = {(sig[j] * p[0]) * rs[m][0], (sig[j] * p[1]) * rs[m][1]};
+                const fq_v2f pr1 = {(sig[j] * p[2]) * rs[m][2], (sig[j] * p[3]) * rs[m][3]};
+                const unsigned pk0 = __builtin_bit_cast(unsigned, __builtin_convertvector(pr0, fq_v2bf));   // rows 0, 1
+                const unsigned pk1 = __builtin_bit_cast(unsigned, __builtin_convertvector(pr1, fq_v2bf));   // rows 2, 3
+                const bool oddl = lane & 1, upper = (lane & 2) != 0;
+                const unsigned sel = oddl ? 0x03020706u : 0x05040100u;   // even: (own.lo, partner.lo); odd: (partner.hi, own.hi)
+                const unsigned n0 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)pk0, 0xB1, 0xF, 0xF, false);
+                const unsigned n1 = (unsigned)__builtin_amdgcn_update_dpp(0, (int)pk1, 0xB1, 0xF, 0xF, false);
+                const unsigned a0 = __builtin_amdgcn_perm(n0, pk0, sel);  // row 0 (even lane) / 1 (odd), the pair's two tokens
+                const unsigned a1 = __builtin_amdgcn_perm(n1, pk1, sel);  // row 2 / 3
+                const unsigned give = upper ? a0 : a1;
+                const unsigned got = (unsigned)__builtin_amdgcn_update_dpp(0, (int)give, 0x4E, 0xF, 0xF, false);
+                const fq_v2i out = upper ? (fq_v2i){(int)got, (int)a1} : (fq_v2i){(int)a0, (int)got};
+                const int orow = 16 * m + 4 * kq + (lane & 3);            // the row this lane now holds, for tokens t4 .. t4 + 3
+                const int t4 = t_first + 16 * j + (r16 & 12);
+                if (orow < R && t4 < T)
+                    *reinterpret_cast<fq_v2i*>(S + ((size_t)h * R + orow) * T + t4) = out;
+            } else {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int orow = 16 * m + 4 * kq + i;
-                if (orow < R && t < T) {
-                    const fq_v2f pr = {(sig[j] * p[i]) * rs[m][i], 0.f};
-                    const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
-                    S[((size_t)h * R + orow) * T + t] = __builtin_bit_cast(unsigned short, pk[0]);
+                for (int i = 0; i < 4; ++i) {
+                    const int orow = 16 * m + 4 * kq + i;
+                    if (orow < R && t < T) {
+                        const fq_v2f pr = {(sig[j] * p[i]) * rs[m][i], 0.f};
+                        const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+                        S[((size_t)h * R + orow) * T + t] = __builtin_bit_cast(unsigned short, pk[0]);
+                    }
                 }
             }
         }
@@ -159,7 +182,10 @@ __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
 // FAST: P rows and the scale rows are 8-byte aligned (ldp and T multiples of 8), so a lane's 8 codes are one
 // 8-byte load each, converted by the hardware; otherwise byte loads.
 #define FQK_O_WAVES 8
-template <int MT, bool FAST, int DT>
+#ifndef FQK_O_FILL
+#define FQK_O_FILL 2                                     // workgroups per compute unit the grid aims for
+#endif
+template <int MT, bool FAST, int DT, bool PF>
 __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
     const uint8_t* __restrict__ P, const float* __restrict__ p_scale, const uint8_t* __restrict__ vp,
     const uint8_t* __restrict__ vs, uint16_t* __restrict__ O, int R, int T, int ldp) {
@@ -180,23 +206,45 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
 #pragma unroll
     for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(__bf16, (unsigned short)0x3F80);
     const int nblocks = (T + 31) / 32;
-    for (int blk = wave; blk < nblocks; blk += FQK_O_WAVES) {
-        const int t0 = 32 * blk + 8 * kq;                 // this lane's first token of the block
-        // the 8 dimension tiles' codes: 8 bytes of chunk (group blk / 4, half, kh, dimension)
-        fq_v2i vq[DT];
+    // what a lane needs of one block, as it comes from memory: the DT dimension tiles' codes (8 bytes of chunk
+    // (group blk / 4, half, kh, dimension)), and in FAST mode the 8 scale bytes and the 8 P codes of each row tile;
+    // with PF (grids that leave compute units with a single workgroup or none: nothing else hides the latency) the
+    // next block's are requested before the current one is worked on
+    struct fqk_raw { fq_v2i vq[DT]; fq_v2i ws; fq_v2i wp[MT]; };
+    auto fetch = [&](int blk, fqk_raw& raw) __attribute__((always_inline)) {
+        const int t0 = 32 * blk + 8 * kq;
+        const bool on = blk < nblocks;
 #pragma unroll
         for (int d = 0; d < DT; ++d) {
             const int dim = 16 * (d0 + d) + r16;
             const int g = blk >> 2, hh = (blk >> 1) & 1, kh = blk & 1;
             const unsigned off = ((unsigned)(dim >> 5) * (unsigned)G + (unsigned)g) * 2048u + (unsigned)hh * 1024u +
                                  (unsigned)(kh * 32 + (dim & 31)) * 16u + (unsigned)(kq & 1) * 8u;
-            vq[d] = __builtin_bit_cast(fq_v2i, __builtin_amdgcn_raw_buffer_load_b64(rsV, off, 0, 2));
+            raw.vq[d] = __builtin_bit_cast(fq_v2i, __builtin_amdgcn_raw_buffer_load_b64(rsV, on ? off : 0xFFFFFF00u, 0, 2));
         }
+        if (FAST) {
+            raw.ws = (fq_v2i){0, 0};
+            if (on && t0 < T) raw.ws = *reinterpret_cast<const fq_v2i*>(vs + (size_t)h * T + t0);   // T % 8 == 0: all 8 or none
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const int row = 16 * m + r16;
+                raw.wp[m] = (fq_v2i){0, 0};
+                if (on && t0 < T)
+                    raw.wp[m] = *reinterpret_cast<const fq_v2i*>(P + ((size_t)h * R + (row < R ? row : R - 1)) * ldp + t0);
+            }
+        }
+    };
+    fqk_raw cur, nxt;
+    if (PF) fetch(wave, cur);
+    for (int blk = wave; blk < nblocks; blk += FQK_O_WAVES) {
+        const int t0 = 32 * blk + 8 * kq;                 // this lane's first token of the block
+        if (PF) fetch(blk + FQK_O_WAVES, nxt);
+        else    fetch(blk, cur);
+        const fq_v2i* vq = cur.vq;
         // sigma of the lane's 8 tokens (zero past T), as FP32
         float sg[8];
         if (FAST) {
-            fq_v2i w = {0, 0};
-            if (t0 < T) w = *reinterpret_cast<const fq_v2i*>(vs + (size_t)h * T + t0);   // T % 8 == 0: all 8 or none
+            const fq_v2i w = cur.ws;
 #pragma unroll
             for (int x = 0; x < 2; ++x) {
                 const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], true);
@@ -213,8 +261,7 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
             const uint8_t* prow = P + ((size_t)h * R + (row < R ? row : R - 1)) * ldp + t0;
             float pv[8];
             if (FAST) {
-                fq_v2i w = {0, 0};
-                if (t0 < T) w = *reinterpret_cast<const fq_v2i*>(prow);
+                const fq_v2i w = cur.wp[m];
 #pragma unroll
                 for (int x = 0; x < 2; ++x) {
                     const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[x], true);
@@ -225,9 +272,14 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
                 for (int j = 0; j < 8; ++j) pv[j] = (t0 + j < T) ? fq_e4m3_to_float(prow[j]) : 0.f;
             }
             // P * sigma: at most 8 significant bits, exact in FP32 and in bf16 (tokens past T: both factors are 0)
+            // (so the conversion's rounding never acts: one v_cvt_pk_bf16_f32 per pair)
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                a[m][j] = __builtin_bit_cast(__bf16, (unsigned short)(__float_as_uint(pv[j] * sg[j]) >> 16));
+            for (int j = 0; j < 8; j += 2) {
+                const fq_v2f pr = {pv[j] * sg[j], pv[j + 1] * sg[j + 1]};
+                const fq_v2bf pb = __builtin_convertvector(pr, fq_v2bf);
+                a[m][j] = pb[0];
+                a[m][j + 1] = pb[1];
+            }
             acc[m][DT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], ones, acc[m][DT], 0, 0, 0);   // sum_t A'[r, t], every column
         }
 #pragma unroll
@@ -244,6 +296,7 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
 #pragma unroll
             for (int m = 0; m < MT; ++m) acc[m][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], b, acc[m][d], 0, 0, 0);
         }
+        if (PF) cur = nxt;
     }
 #pragma unroll
     for (int m = 0; m < MT; ++m)
@@ -291,27 +344,44 @@ void fq_launch_kv4_unpack(const uint8_t* packed, int8_t* codes, int H, int T, bo
 void fq_launch_kv4_scores(const uint8_t* Q, const float* q_scale, const uint8_t* kp, const uint8_t* ks, float out_scale,
                           uint16_t* S, int H, int R, int T, hipStream_t stream) {
     const dim3 grid((unsigned)((T + 4 * FQK_S_NSUB * 16 - 1) / (4 * FQK_S_NSUB * 16)), (unsigned)H);
+    const bool wide = (T % 4) == 0 && (reinterpret_cast<uintptr_t>(S) % 8) == 0;   // rows of S are then 8-byte aligned
+#define FQK_SCORES(MT_) \
+    do { \
+        if (wide) hipLaunchKernelGGL((fq_kv4_scores_kernel<MT_, true>), grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); \
+        else      hipLaunchKernelGGL((fq_kv4_scores_kernel<MT_, false>), grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); \
+    } while (0)
     switch ((R + 15) / 16) {
-        case 1: hipLaunchKernelGGL(fq_kv4_scores_kernel<1>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
-        case 2: hipLaunchKernelGGL(fq_kv4_scores_kernel<2>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
-        case 3: hipLaunchKernelGGL(fq_kv4_scores_kernel<3>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
-        default: hipLaunchKernelGGL(fq_kv4_scores_kernel<4>, grid, dim3(256), 0, stream, Q, q_scale, kp, ks, out_scale, S, R, T); break;
+        case 1: FQK_SCORES(1); break;
+        case 2: FQK_SCORES(2); break;
+        case 3: FQK_SCORES(3); break;
+        default: FQK_SCORES(4); break;
     }
+#undef FQK_SCORES
 }
 
 namespace {
 
-template <int MT, bool FAST, int DT>
-void fqk_launch_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
-                       int H, int R, int T, int ldp, hipStream_t stream) {
+template <int MT, bool FAST, int DT, bool PF>
+void fqk_launch_output_pf(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                          int H, int R, int T, int ldp, hipStream_t stream) {
     constexpr size_t lds = (size_t)FQK_O_WAVES * MT * (DT + 1) * 4 * 64 * sizeof(float);
     static fq_device_once attr_once;                      // (one per template instance)
     fq_once_per_device(attr_once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<MT, FAST, DT>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_kernel<MT, FAST, DT, PF>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     });
-    hipLaunchKernelGGL((fq_kv4_output_kernel<MT, FAST, DT>), dim3((unsigned)H, 8 / DT), dim3(64 * FQK_O_WAVES), lds, stream,
-                       P, p_scale, vp, vs, O, R, T, ldp);
+    hipLaunchKernelGGL((fq_kv4_output_kernel<MT, FAST, DT, PF>), dim3((unsigned)H, 8 / DT), dim3(64 * FQK_O_WAVES), lds,
+                       stream, P, p_scale, vp, vs, O, R, T, ldp);
+}
+
+template <int MT, bool FAST, int DT>
+void fqk_launch_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                       int H, int R, int T, int ldp, hipStream_t stream) {
+    // fewer workgroups than twice the compute units (only possible at one dimension tile per workgroup): prefetch
+    if (DT == 1 && (long)H * 8 < (long)FQK_O_FILL * fq_device_cus())
+        fqk_launch_output_pf<MT, FAST, DT, true>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else
+        fqk_launch_output_pf<MT, FAST, DT, false>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
 }
 
 template <int MT, bool FAST>
@@ -332,7 +402,7 @@ void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t*
     // dimension tiles per workgroup: the most that still give two workgroups per compute unit
     const int cus = fq_device_cus();
     int dt = 8;
-    while (dt > 1 && (long)H * (8 / dt) < 2L * cus) dt >>= 1;
+    while (dt > 1 && (long)H * (8 / dt) < (long)FQK_O_FILL * cus) dt >>= 1;
     if (R <= 16) {
         if (fast) fqk_launch_output_dt<1, true>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
         else      fqk_launch_output_dt<1, false>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);

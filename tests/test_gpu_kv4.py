@@ -44,7 +44,8 @@ def test_cache_pack_roundtrip(fq, H, T):
         assert np.array_equal(kp[h], fq.fq_pack_weights(_gpu(codes[h])).cpu().numpy())
 
 
-SCORE_SHAPES = [(1, 1, 1), (2, 4, 100), (3, 16, 256), (2, 17, 300), (1, 64, 513), (8, 4, 4096), (5, 33, 70)]
+SCORE_SHAPES = [(1, 1, 1), (2, 4, 100), (3, 16, 256), (2, 17, 300), (1, 64, 513), (8, 4, 4096), (5, 33, 70), (2, 64, 516),
+                (3, 5, 4)]
 
 
 @pytest.mark.parametrize("H,R,T", SCORE_SHAPES)
