@@ -106,7 +106,15 @@ __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
                                      (unsigned)((kq & 1) * 32 + (t & 31)) * 16u
                                    : FQK_OOB;
         bq[j] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsK, off, 0, 2));
-        sig[j] = t < T ? fq_e4m3_to_float(ks[(size_t)h * T + t]) : 0.f;
+    }
+    // token scales: lane (kq, r) fetches the one of token r of sub-tile kq, and the four lanes with the same r pass
+    // them round (one byte load per lane instead of four: a load costs the address path the same whatever its width)
+    {
+        const int t = t_first + 16 * kq + r16;
+        const float own = t < T ? fq_e4m3_to_float(ks[(size_t)h * T + t]) : 0.f;
+        static_assert(FQK_S_NSUB == 4, "one sub-tile per lane quarter");
+#pragma unroll
+        for (int j = 0; j < FQK_S_NSUB; ++j) sig[j] = __shfl(own, 16 * j + r16, 64);
     }
     fq_v8i a[MT];
     fq_v4f c0[MT];
