@@ -480,11 +480,16 @@ def test_mid_m_configs_full_size(fq, name):
     _full_config(fq, name, range(workloads.WORKLOADS[name].M))
 
 
-def test_ws_entry_points_replay_in_a_hip_graph(fq):
+@pytest.mark.parametrize("shape", [(300, 512, 1024), (128, 256, 4096)])
+def test_ws_entry_points_replay_in_a_hip_graph(fq, shape):
     """The explicit-workspace entry points allocate nothing and keep no state, so a captured graph of
-    quantiser + GEMM (plain, with residual, fused gate/up) can be replayed: three replays on fresh inputs,
-    eager work and synchronisations between them, each replay equal to the eager result bit for bit."""
-    M, N, K = 300, 512, 1024
+    quantiser + GEMM (plain, with residual, fused gate/up, fused gate/up with quantised output) can be replayed:
+    three replays on fresh inputs, eager work and synchronisations between them, each replay equal to the eager
+    result bit for bit.  The second shape takes the K-split kernel with four workgroups per tile, whose arrival
+    counters must be back at zero after every GEMM of every replay."""
+    M, N, K = shape
+    if shape[0] == 128:
+        assert fq.fq_w4a8_gemm_plan(M, N, K)["ksplit_slices"] == 4
     d = workloads.draw(M, N, K, seed=91, gs_lo=0.01, gs_hi=0.1, outlier_frac=0.01)
     packed = fq.fq_pack_weights(_gpu(d["q"]))
     gs = _gpu(d["gscale"])
@@ -496,6 +501,9 @@ def test_ws_entry_points_replay_in_a_hip_graph(fq):
     Y = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     Ya = torch.empty((M, N), dtype=torch.bfloat16, device="cuda")
     H = torch.empty((M, N // 2), dtype=torch.bfloat16, device="cuda")
+    Hq = torch.empty((M, N // 2), dtype=torch.bfloat16, device="cuda")
+    Cq = torch.empty((M, N // 2), dtype=torch.uint8, device="cuda")
+    hq = torch.empty((M,), dtype=torch.float32, device="cuda")
     L = fq.lib()
 
     def enqueue():
@@ -509,6 +517,8 @@ def test_ws_entry_points_replay_in_a_hip_graph(fq):
                                      Ya.data_ptr(), M, N, K, ws.data_ptr(), wsb, 1, st) == 0
         assert L.fq_w4a8_gemm_swiglu_ws(A.data_ptr(), s.data_ptr(), packed.data_ptr(), gs.data_ptr(), t, H.data_ptr(),
                                         M, N, K, ws.data_ptr(), wsb, 1, st) == 0
+        assert L.fq_w4a8_gemm_swiglu_quant_ws(A.data_ptr(), s.data_ptr(), packed.data_ptr(), gs.data_ptr(), t, Hq.data_ptr(),
+                                              Cq.data_ptr(), hq.data_ptr(), M, N, K, ws.data_ptr(), wsb, 1, None, 0, st) == 0
 
     enqueue()                                                  # warm-up outside the capture
     torch.cuda.synchronize()
@@ -522,12 +532,15 @@ def test_ws_entry_points_replay_in_a_hip_graph(fq):
     for rep in range(3):
         Xn = to_gpu_bf16(workloads.draw(M, N, K, seed=100 + rep, outlier_frac=0.01)["X_bf16"])
         X.copy_(Xn)
-        for out in (Y, Ya, H, A):
+        for out in (Y, Ya, H, A, Hq, Cq, hq):
             out.zero_()
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
         got = [bf16_bits_from_gpu(Y).copy(), bf16_bits_from_gpu(Ya).copy(), bf16_bits_from_gpu(H).copy()]
+        assert torch.equal(Hq.view(torch.int16), H.view(torch.int16))
+        C_e, h_e = fq.fq_quantize_act(H)
+        assert torch.equal(Cq, C_e) and torch.equal(hq, h_e), "replay %d: quantised gate/up output" % rep
         A2, s2 = fq.fq_quantize_act(Xn)                        # eager, library-owned paths
         want = [bf16_bits_from_gpu(fq.fq_w4a8_gemm(A2, s2, packed, gs, d["w_tscale"], N)),
                 bf16_bits_from_gpu(fq.fq_w4a8_gemm_add(A2, s2, packed, gs, d["w_tscale"], N, R)),
