@@ -286,6 +286,8 @@ int fq_quantize_weights(const uint16_t *W_bf16, const float *lambda, int n_pts, 
  *                    scores, or any factor), S_bf16 [H][R][T].  R <= 64.
  *   fq_kv4_output    P_fp8 [H][R][ldp] E4M3 codes, the first T of each row used (ldp >= T),
  *                    p_scale [H][R] FP32, v_scale [H][T], O_bf16 [H][R][128].  R <= 32, T >= 1.
+ *                    Fastest when T and ldp are multiples of 16 and P_fp8 and v_scale 16-byte
+ *                    aligned (16-byte loads); any other T, ldp and alignment is served too.
  * H <= 65535.  Status codes as above; a zero H, R (or T for the scores) is a successful no-op.
  */
 size_t fq_kv4_packed_bytes(int H, int T, int values);

@@ -188,11 +188,54 @@ __global__ __launch_bounds__(256) void fq_kv4_scores_kernel(
 // an all-ones operand delivers sum A', and 24 times that is taken off at the end (all products are exact; the
 // offset costs a few FP32 roundings of the larger intermediate sum, far below the tolerance).
 // FAST: P rows and the scale rows are 8-byte aligned (ldp and T multiples of 8), so a lane's 8 codes are one
-// 8-byte load each, converted by the hardware; otherwise byte loads.
+// 8-byte load each, converted by the hardware; otherwise byte loads.  (16-byte aligned rows take the kernel of
+// 16-byte steps further down.)
 #define FQK_O_WAVES 8
 #ifndef FQK_O_FILL
 #define FQK_O_FILL 2                                     // workgroups per compute unit the grid aims for
 #endif
+// the kernel of 16-byte steps: at most 4 dimension tiles per workgroup, and one workgroup per compute unit is enough
+// (measured, 128-wide heads x 4 rows x 4096 tokens: 128 heads 10.0 us with 4 tiles, 11.0 with 2, 13.8 with 1; 256 heads
+// 16.3 us with 4 tiles, 21.9 with 8)
+#ifndef FQK_O_WIDE_FILL
+#define FQK_O_WIDE_FILL 1
+#endif
+#ifndef FQK_O_WIDE_MAXDT
+#define FQK_O_WIDE_MAXDT 4
+#endif
+#ifndef FQK_O_WIDE_PF
+#define FQK_O_WIDE_PF(MT, DT) ((DT) <= 4)                // request a group ahead (registers allow it)
+#endif
+// The tail both output kernels share: the waves' partial sums (DT dimension tiles and the row sums of A') are added through
+// LDS in the order of the waves, the offset of 24 per code comes off, the row's scale goes on, one rounding to bf16.
+template <int MT, int DT>
+__device__ __forceinline__ void fqk_output_finish(const fq_v4f (&acc)[MT][DT + 1], float* red, const float* __restrict__ p_scale,
+                                                  uint16_t* __restrict__ O, int h, int d0, int R) {
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int d = 0; d < DT + 1; ++d)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) red[(((wave * MT + m) * (DT + 1) + d) * 4 + i) * 64 + lane] = acc[m][d][i];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < MT * DT * 4 * 64; idx += 64 * FQK_O_WAVES) {
+        const int l = idx & 63, i = (idx >> 6) & 3, d = (idx >> 8) % DT, m = (idx >> 8) / DT;
+        const int row = 16 * m + 4 * (l >> 4) + i, dim = 16 * (d0 + d) + (l & 15);
+        if (row < R) {
+            float v = 0.f, s1 = 0.f;                      // fixed order: deterministic
+#pragma unroll
+            for (int w = 0; w < FQK_O_WAVES; ++w) {
+                v += red[(((w * MT + m) * (DT + 1) + d) * 4 + i) * 64 + l];
+                s1 += red[(((w * MT + m) * (DT + 1) + DT) * 4 + i) * 64 + l];
+            }
+            const fq_v2f pr = {fmaf(-24.0f, s1, v) * p_scale[(size_t)h * R + row], 0.f};
+            const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
+            O[((size_t)h * R + row) * FQK_HEAD + dim] = __builtin_bit_cast(unsigned short, pk[0]);
+        }
+    }
+}
+
 template <int MT, bool FAST, int DT, bool PF>
 __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
     const uint8_t* __restrict__ P, const float* __restrict__ p_scale, const uint8_t* __restrict__ vp,
@@ -306,28 +349,128 @@ __global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_kernel(
         }
         if (PF) cur = nxt;
     }
+    fqk_output_finish<MT, DT>(acc, red, p_scale, O, h, d0, R);
+}
+
+
+// The same product for caches and probability rows in 16-byte steps (T and ldp multiples of 16, P and the scales 16-byte
+// aligned): a step of a wave is a whole 128-token group.  Lane l = 16 * kq + r fetches, per dimension tile, the
+// whole 16-byte chunk of tokens 32 kq .. 32 kq + 31 of dimension r, and the 32 probability codes and 32 scales of the
+// same tokens (two 16-byte loads each): 4 + DT wave-level loads per 128 tokens where the kernel above issues
+// 4 * (2 + DT) -- a load costs the address path the same whatever its width.  Four matrix instructions use them up:
+// number j4 takes, in every lane, tokens 32 kq + 8 j4 .. + 7 (the order of the summation index is free as long
+// as both operands agree), i.e. bytes 8 j4 .. of the codes and scales and, of the chunk, the low (j4 < 2) or high
+// nibbles of bytes 8 (j4 % 2) ...  A nibble becomes the bf16 number 16 + c in a byte shuffle: low byte 0x80 | c << 3,
+// high byte 0x41.  The next group's loads are requested before the current one is worked on.
+template <int MT, int DT, bool PF>
+__global__ __launch_bounds__(64 * FQK_O_WAVES) void fq_kv4_output_wide_kernel(
+    const uint8_t* __restrict__ P, const float* __restrict__ p_scale, const uint8_t* __restrict__ vp,
+    const uint8_t* __restrict__ vs, uint16_t* __restrict__ O, int R, int T, int ldp) {
+    extern __shared__ float red[];                        // [waves][MT][DT + 1][4][64]
+    const int d0 = blockIdx.y * DT;
+    const int h = blockIdx.x;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, r16 = lane & 15, kq = lane >> 4;
+    const int G = (T + 127) / 128;
+    const size_t vbytes = fqk_value_bytes(T);
+    const __amdgpu_buffer_rsrc_t rsV = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(vp) + (size_t)h * vbytes, 0, (int)vbytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(vs) + (size_t)h * T, 0, T, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<uint8_t*>(P) + (size_t)h * R * ldp, 0, R * ldp, 0x00020000);
+    fq_v4f acc[MT][DT + 1];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
 #pragma unroll
-        for (int d = 0; d < DT + 1; ++d)
+        for (int d = 0; d < DT + 1; ++d) acc[m][d] = (fq_v4f){0.f, 0.f, 0.f, 0.f};
+    fqk_v8bf ones;
 #pragma unroll
-            for (int i = 0; i < 4; ++i) red[(((wave * MT + m) * (DT + 1) + d) * 4 + i) * 64 + lane] = acc[m][d][i];
-    __syncthreads();
-    for (int idx = threadIdx.x; idx < MT * DT * 4 * 64; idx += 64 * FQK_O_WAVES) {
-        const int l = idx & 63, i = (idx >> 6) & 3, d = (idx >> 8) % DT, m = (idx >> 8) / DT;
-        const int row = 16 * m + 4 * (l >> 4) + i, dim = 16 * (d0 + d) + (l & 15);
-        if (row < R) {
-            float v = 0.f, s1 = 0.f;                      // fixed order: deterministic
+    for (int j = 0; j < 8; ++j) ones[j] = __builtin_bit_cast(__bf16, (unsigned short)0x3F80);
+    unsigned prow[MT];                                    // byte offset of this lane's probability row(s) in the head
 #pragma unroll
-            for (int w = 0; w < FQK_O_WAVES; ++w) {
-                v += red[(((w * MT + m) * (DT + 1) + d) * 4 + i) * 64 + l];
-                s1 += red[(((w * MT + m) * (DT + 1) + DT) * 4 + i) * 64 + l];
-            }
-            const fq_v2f pr = {fmaf(-24.0f, s1, v) * p_scale[(size_t)h * R + row], 0.f};
-            const fq_v2bf pk = __builtin_convertvector(pr, fq_v2bf);
-            O[((size_t)h * R + row) * FQK_HEAD + dim] = __builtin_bit_cast(unsigned short, pk[0]);
-        }
+    for (int m = 0; m < MT; ++m) {
+        const int row = 16 * m + r16;
+        prow[m] = (unsigned)(row < R ? row : R - 1) * (unsigned)ldp;
     }
+    unsigned vlane[DT];                                   // this lane's chunk inside a 2048-byte block, per dimension tile
+#pragma unroll
+    for (int d = 0; d < DT; ++d) {
+        const int dim = 16 * (d0 + d) + r16;
+        vlane[d] = (unsigned)(dim >> 5) * (unsigned)G * 2048u + (unsigned)(kq >> 1) * 1024u +
+                   (unsigned)((kq & 1) * 32 + (dim & 31)) * 16u;
+    }
+    struct fqk_raw { fq_v4i vq[DT]; fq_v4i ws[2]; fq_v4i wp[MT][2]; };
+    auto fetch = [&](int g, fqk_raw& raw) __attribute__((always_inline)) {
+        const bool on = g < G;
+        const int t0 = 128 * g + 32 * kq;
+#pragma unroll
+        for (int d = 0; d < DT; ++d)                      // (streamed once: non-temporal)
+            raw.vq[d] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(
+                rsV, on ? vlane[d] + (unsigned)g * 2048u : FQK_OOB, 0, 2));
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {                     // T % 16 == 0: a 16-byte step lies before T or past it
+            const int tt = t0 + 16 * x;
+            const bool in = on && tt < T;
+            raw.ws[x] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(rsS, in ? (unsigned)tt : FQK_OOB, 0, 0));
+#pragma unroll
+            for (int m = 0; m < MT; ++m)
+                raw.wp[m][x] = __builtin_bit_cast(fq_v4i, __builtin_amdgcn_raw_buffer_load_b128(
+                    rsP, in ? prow[m] + (unsigned)tt : FQK_OOB, 0, 0));
+        }
+    };
+    fqk_raw cur, nxt;
+    if (PF) fetch(wave, cur);
+    for (int g = wave; g < G; g += FQK_O_WAVES) {
+        if (PF) fetch(g + FQK_O_WAVES, nxt);
+        else    fetch(g, cur);
+#pragma unroll
+        for (int j4 = 0; j4 < 4; ++j4) {
+            const int x = j4 >> 1, w0 = 2 * (j4 & 1);     // which 16-byte step of codes and scales, which 8 bytes of it
+            float sg[8];                                  // sigma of the lane's 8 tokens (zero past T)
+#pragma unroll
+            for (int y = 0; y < 2; ++y) {
+                const int w = cur.ws[x][w0 + y];
+                const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(w, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
+                sg[4 * y] = lo[0]; sg[4 * y + 1] = lo[1]; sg[4 * y + 2] = hi[0]; sg[4 * y + 3] = hi[1];
+            }
+            fqk_v8bf a[MT];
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                float pv[8];
+#pragma unroll
+                for (int y = 0; y < 2; ++y) {
+                    const int w = cur.wp[m][x][w0 + y];
+                    const fq_v2f lo = __builtin_amdgcn_cvt_pk_f32_fp8(w, false), hi = __builtin_amdgcn_cvt_pk_f32_fp8(w, true);
+                    pv[4 * y] = lo[0]; pv[4 * y + 1] = lo[1]; pv[4 * y + 2] = hi[0]; pv[4 * y + 3] = hi[1];
+                }
+                // P * sigma: at most 8 significant bits, exact in FP32 and in bf16 (the conversion's rounding never acts)
+#pragma unroll
+                for (int j = 0; j < 8; j += 2) {
+                    const fq_v2f pr = {pv[j] * sg[j], pv[j + 1] * sg[j + 1]};
+                    const fq_v2bf pb = __builtin_convertvector(pr, fq_v2bf);
+                    a[m][j] = pb[0];
+                    a[m][j + 1] = pb[1];
+                }
+                acc[m][DT] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], ones, acc[m][DT], 0, 0, 0);   // sum_t A'[r, t], every column
+            }
+#pragma unroll
+            for (int d = 0; d < DT; ++d) {
+                fq_v4i bw;
+#pragma unroll
+                for (int y = 0; y < 2; ++y) {
+                    const unsigned w = (unsigned)cur.vq[d][w0 + y];
+                    const unsigned c3 = (((j4 >> 1) ? (w >> 1) : (w << 3)) & 0x78787878u) | 0x80808080u;   // 0x80 | c << 3, 4 tokens
+                    bw[2 * y] = (int)__builtin_amdgcn_perm(0x41414141u, c3, 0x04010400u);
+                    bw[2 * y + 1] = (int)__builtin_amdgcn_perm(0x41414141u, c3, 0x04030402u);
+                }
+                const fqk_v8bf b = __builtin_bit_cast(fqk_v8bf, bw);
+#pragma unroll
+                for (int m = 0; m < MT; ++m) acc[m][d] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[m], b, acc[m][d], 0, 0, 0);
+            }
+        }
+        if (PF) cur = nxt;
+    }
+    fqk_output_finish<MT, DT>(acc, red, p_scale, O, h, d0, R);
 }
 
 }  // namespace
@@ -382,40 +525,60 @@ void fqk_launch_output_pf(const uint8_t* P, const float* p_scale, const uint8_t*
                        stream, P, p_scale, vp, vs, O, R, T, ldp);
 }
 
-template <int MT, bool FAST, int DT>
-void fqk_launch_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
-                       int H, int R, int T, int ldp, hipStream_t stream) {
-    // fewer workgroups than twice the compute units (only possible at one dimension tile per workgroup): prefetch
-    if (DT == 1 && (long)H * 8 < (long)FQK_O_FILL * fq_device_cus())
-        fqk_launch_output_pf<MT, FAST, DT, true>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-    else
-        fqk_launch_output_pf<MT, FAST, DT, false>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+template <int MT, int DT>
+void fqk_launch_output_wide(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                            int H, int R, int T, int ldp, hipStream_t stream) {
+    constexpr size_t lds = (size_t)FQK_O_WAVES * MT * (DT + 1) * 4 * 64 * sizeof(float);
+    constexpr bool PF = FQK_O_WIDE_PF(MT, DT);
+    static fq_device_once attr_once;                      // (one per template instance)
+    fq_once_per_device(attr_once, [] {
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_kv4_output_wide_kernel<MT, DT, PF>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    });
+    hipLaunchKernelGGL((fq_kv4_output_wide_kernel<MT, DT, PF>), dim3((unsigned)H, 8 / DT), dim3(64 * FQK_O_WAVES), lds,
+                       stream, P, p_scale, vp, vs, O, R, T, ldp);
 }
 
-template <int MT, bool FAST>
+// MODE 0: byte loads; 1: 8-byte steps; 2: 16-byte steps (the wide kernel)
+template <int MT, int MODE, int DT>
+void fqk_launch_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
+                       int H, int R, int T, int ldp, hipStream_t stream) {
+    if (MODE == 2)
+        fqk_launch_output_wide<MT, DT>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    // fewer workgroups than twice the compute units (only possible at one dimension tile per workgroup): prefetch
+    else if (DT == 1 && (long)H * 8 < (long)FQK_O_FILL * fq_device_cus())
+        fqk_launch_output_pf<MT, MODE == 1, DT, true>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else
+        fqk_launch_output_pf<MT, MODE == 1, DT, false>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+}
+
+template <int MT, int MODE>
 void fqk_launch_output_dt(int dt, const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
                           int H, int R, int T, int ldp, hipStream_t stream) {
-    if (dt == 8)      fqk_launch_output<MT, FAST, 8>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-    else if (dt == 4) fqk_launch_output<MT, FAST, 4>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-    else if (dt == 2) fqk_launch_output<MT, FAST, 2>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-    else              fqk_launch_output<MT, FAST, 1>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    if (dt == 8)      fqk_launch_output<MT, MODE, 8>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else if (dt == 4) fqk_launch_output<MT, MODE, 4>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else if (dt == 2) fqk_launch_output<MT, MODE, 2>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
+    else              fqk_launch_output<MT, MODE, 1>(P, p_scale, vp, vs, O, H, R, T, ldp, stream);
 }
 
 }  // namespace
 
 void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
                           int H, int R, int T, int ldp, hipStream_t stream) {
-    const bool fast = (T % 8) == 0 && (ldp % 8) == 0 && (reinterpret_cast<uintptr_t>(P) % 8) == 0 &&
-                      (reinterpret_cast<uintptr_t>(vs) % 8) == 0;
-    // dimension tiles per workgroup: the most that still give two workgroups per compute unit
+    const uintptr_t both = reinterpret_cast<uintptr_t>(P) | reinterpret_cast<uintptr_t>(vs) | (uintptr_t)T | (uintptr_t)ldp;
+    const int mode = (both % 16) == 0 ? 2 : (both % 8) == 0 ? 1 : 0;
+    // dimension tiles per workgroup: the most that still give `fill` workgroups per compute unit
     const int cus = fq_device_cus();
-    int dt = 8;
-    while (dt > 1 && (long)H * (8 / dt) < (long)FQK_O_FILL * cus) dt >>= 1;
-    if (R <= 16) {
-        if (fast) fqk_launch_output_dt<1, true>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-        else      fqk_launch_output_dt<1, false>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-    } else {
-        if (fast) fqk_launch_output_dt<2, true>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-        else      fqk_launch_output_dt<2, false>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream);
-    }
+    int dt = mode == 2 ? FQK_O_WIDE_MAXDT : 8;
+    const int fill = mode == 2 ? FQK_O_WIDE_FILL : FQK_O_FILL;
+    while (dt > 1 && (long)H * (8 / dt) < (long)fill * cus) dt >>= 1;
+#define FQK_OUTPUT(MT_) \
+    do { \
+        if (mode == 2)      fqk_launch_output_dt<MT_, 2>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream); \
+        else if (mode == 1) fqk_launch_output_dt<MT_, 1>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream); \
+        else                fqk_launch_output_dt<MT_, 0>(dt, P, p_scale, vp, vs, O, H, R, T, ldp, stream); \
+    } while (0)
+    if (R <= 16) FQK_OUTPUT(1);
+    else         FQK_OUTPUT(2);
+#undef FQK_OUTPUT
 }

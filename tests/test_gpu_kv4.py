@@ -64,7 +64,9 @@ def test_scores_match_the_oracle(fq, H, R, T):
     assert not oracle.bf16_bits_to_f64(got)[:, :, T // 2].any()
 
 
-OUTPUT_SHAPES = [(1, 1, 1), (2, 4, 100), (3, 16, 256), (2, 17, 300), (1, 32, 513), (8, 4, 4096), (5, 9, 70)]
+# (T a multiple of 16 with the padded stride below: the kernel of 16-byte steps; 144 and 1040 end inside a 128-token group)
+OUTPUT_SHAPES = [(1, 1, 1), (2, 4, 100), (3, 16, 256), (2, 17, 300), (1, 32, 513), (8, 4, 4096), (5, 9, 70), (2, 20, 144),
+                 (3, 4, 1040), (1, 1, 16), (40, 16, 272)]
 
 
 @pytest.mark.parametrize("H,R,T", OUTPUT_SHAPES)
