@@ -306,10 +306,10 @@ int fq_kv4_output(const uint8_t *P_fp8, const float *p_scale, const uint8_t *V_p
  * fq_w4a8_gemm_plan: how fq_w4a8_gemm_ws would run an M x N x K problem on a device with `cus`
  *   compute units (0 = the current device).  `plan` is HOST memory of 8 ints:
  *     plan[0]  kernel: 0 one-thread-per-output cross-check kernel, 1 the M <= 16 kernel, 2 the
- *              M <= 64 kernel, 3 the large-M kernel, 4 / 5 the K-split kernel with 256 x 128 /
- *              128 x 64 tiles (plain GEMM and residual form; the fused gate/up form always
- *              takes the large-M kernel), its number of tiles in plan[5] and the number of
- *              workgroups that share a tile along K in plan[6]
+ *              M <= 64 kernel, 3 the large-M kernel, 4 / 5 / 6 the K-split kernel with 256 x 128 /
+ *              128 x 64 / 64 x 64 tiles (plain GEMM and residual form; the fused gate/up form
+ *              always takes the large-M or the M <= 64 kernel), its number of tiles in plan[5] and
+ *              the number of workgroups that share a tile along K in plan[6]
  *     plan[1]  large-M kernel: whole tiles (256 rows x 128 channels) written with whole-row stores
  *     plan[2]  whole tiles written element by element (a ragged edge, or N not a multiple of 8)
  *     plan[3], plan[4]  the same two counts for the 128-row half tiles of the last round

@@ -402,7 +402,7 @@ def fq_w4a8_gemm_plan(M: int, N: int, K: int, cus: int = 0) -> dict:
     rc = lib().fq_w4a8_gemm_plan(int(M), int(N), int(K), int(cus), buf)
     if rc != 0:
         raise FireqError(rc, "fq_w4a8_gemm_plan")
-    return {"kernel": ("simple", "small16", "smallm", "large", "ksplit256x128", "ksplit128x64")[buf[0]], "whole": buf[1],
+    return {"kernel": ("simple", "small16", "smallm", "large", "ksplit256x128", "ksplit128x64", "ksplit64x64")[buf[0]], "whole": buf[1],
             "whole_ragged": buf[2], "half": buf[3], "half_ragged": buf[4], "ksplit_tiles": buf[5], "ksplit_slices": buf[6]}
 
 

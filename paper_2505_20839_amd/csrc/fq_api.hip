@@ -74,6 +74,12 @@ int ksplit_choice(int M, int N, int K, bool swiglu) {
     return fq_gemm_ksplit_choice(M, N, K, fq_device_cus());
 }
 
+// The top of 16 < M <= 64: the K-split kernel on 64 x 64 tiles instead of the M <= 64 kernel (never when a kernel is forced,
+// never with the fused gate/up epilogue)
+bool ksplit64_choice(int M, int N, int K, bool swiglu) {
+    return !swiglu && forced_kernel() == GemmKernel::Auto && fq_gemm_ksplit64_serves(M, N, K, fq_device_cus());
+}
+
 }  // namespace
 
 extern "C" {
@@ -173,6 +179,12 @@ int fq_w4a8_gemm_plan(int M, int N, int K, int cus, int* plan) {
     for (int i = 0; i < 8; ++i) plan[i] = 0;
     const GemmKernel k = choose_kernel(M);
     plan[0] = k == GemmKernel::Simple ? 0 : k == GemmKernel::Small ? (M <= 16 ? 1 : 2) : 3;
+    if (k == GemmKernel::Small && forced_kernel() == GemmKernel::Auto &&
+        fq_gemm_ksplit64_serves(M, N, K, cus > 0 ? cus : fq_device_cus())) {
+        plan[0] = 6;
+        plan[5] = (N + 63) / 64;
+        plan[6] = 1;
+    }
     if (k == GemmKernel::Large) {
         const int c = cus > 0 ? cus : fq_device_cus();
         const GemmKernel f = forced_kernel();
@@ -249,7 +261,9 @@ int gemm_ws(const uint8_t* A_fp8, const float* a_scale, const uint8_t* Wq_packed
             fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s);
             break;
         case GemmKernel::Small:
-            if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s))
+            if (ksplit64_choice(M, N, K, swiglu))
+                fq_launch_gemm_ksplit64(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, R, s);
+            else if (!fq_launch_gemm_small(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s))
                 fq_launch_gemm_simple(A_fp8, a_scale, Wq_packed, w_gscale, w_tscale, out, M, N, K, swiglu, R, s);
             break;
         default: {

@@ -11,7 +11,9 @@
 //     NMT = 4, NW = 2, KS = 4   128 x 64 tiles, K quartered: for 64 < M <= 512 (batched decode, chunked
 //                               prefill), where 128-channel tiles are too few and the small-M kernels
 //                               re-read the activations once per compute unit from L2
-// One workgroup per compute unit (128 or 160 KiB of LDS, two waves per SIMD).
+//     NMT = 2, NW = 2, KS = 4   64 x 64 tiles, the zero point through the matrix cores (no workspace): M just
+//                               below 64 with many channels, where the M <= 64 kernel is slowest
+// One workgroup per compute unit (64 to 160 KiB of LDS, two waves per SIMD).
 //
 // K slices: when even these tiles are fewer than the compute units, S workgroups share a tile, each taking a
 // contiguous 1/S of the groups (and splitting that among its waves as above).  A workgroup's loop is bound by
@@ -32,7 +34,7 @@
 namespace {
 
 // LDS: KS * 2 stages of 32 * NMT rows x 128 bytes, then (256 x 128 shape) 8 x 4 KiB of packed weights; reused for the fold
-// (8 waves x NMT tiles of 4 KiB, half of them at a time), the zero-point units and the output tile.
+// (8 waves x NMT tiles of 4 KiB, all at once where they fit, else half of them at a time), the zero-point units and the output tile.
 template <int NMT, int NW, int KS>
 struct fqk_cfg {
     static constexpr int BM = 32 * NMT, BN = 32 * NW;
@@ -40,15 +42,20 @@ struct fqk_cfg {
     static constexpr int OUT_STRIDE = BN * 2 + 16;        // bytes per row of the output tile staged in LDS
     static constexpr bool WREG = NMT <= 4;                // packed weights through registers instead of LDS
     static constexpr int LOOP_LDS = KS * 2 * STG * 16 + (WREG ? 0 : FQK_WAVES * 4096);
-    static constexpr int FOLD_LDS = FQK_WAVES * (NMT / 2 > 0 ? NMT / 2 : 1) * 4096;
+    // row tiles that go through LDS at a time when the K splits' partial tiles are added: all of them where the
+    // stages have room for 8 waves x NMT tiles of 4 KiB, else half
+    static constexpr int HALF = FQK_WAVES * NMT * 4096 <= LOOP_LDS ? NMT : (NMT / 2 > 0 ? NMT / 2 : 1);
+    static constexpr int FOLD_LDS = FQK_WAVES * HALF * 4096;
     static constexpr int EPI_LDS = BM * OUT_STRIDE + 1024;
     static constexpr int LDS = LOOP_LDS > FOLD_LDS ? (LOOP_LDS > EPI_LDS ? LOOP_LDS : EPI_LDS)
                                                    : (FOLD_LDS > EPI_LDS ? FOLD_LDS : EPI_LDS);
-    static_assert(NW * KS == FQK_WAVES && NMT % KS == 0 && (4 * NMT) % NW == 0 && 8 % NMT == 0, "shape");
+    static_assert(NW * KS == FQK_WAVES && (NMT % KS == 0 || KS % NMT == 0) && (4 * NMT) % NW == 0 && 8 % NMT == 0, "shape");
     static_assert(LDS <= 160 * 1024, "LDS");
 };
 
-template <int NMT, int NW, int KS>
+// ZPM: the zero point comes out through one more matrix instruction per operand half against a constant operand
+// (every byte -2^-6), as in the small-M kernels, instead of the Z planes of a workspace: for problems that have none.
+template <int NMT, int NW, int KS, bool ZPM = false>
 __global__ __launch_bounds__(FQK_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void fq_gemm_ksplit_kernel(
     const uint8_t* __restrict__ A, const float* __restrict__ a_scale, const uint8_t* __restrict__ wp,
@@ -57,7 +64,8 @@ void fq_gemm_ksplit_kernel(
     int S, unsigned* counters, float* partials) {
     typedef fqk_cfg<NMT, NW, KS> cfg;
     constexpr int NT = 4 * NMT / NW;                      // A transfers (8 rows each) per wave and stage
-    constexpr int OWN = NMT / KS;                         // row tiles a wave finishes
+    constexpr int OWN = NMT >= KS ? NMT / KS : 1;         // row tiles a wave finishes (fewer row tiles than splits:
+                                                          // the first NMT splits finish one each, the others none)
     extern __shared__ fq_v4i lds[];
     const int G = K / FQ_GROUP;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -130,6 +138,9 @@ void fq_gemm_ksplit_kernel(
     fq_v16f zero;
 #pragma unroll
     for (int r = 0; r < 16; ++r) zero[r] = 0.f;
+    fq_v8i zpb;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) zpb[r] = (int)FQ_ZP_BYTES;
 
     // ---- prologue ----
     fq_v4i* stages = lds + kw * (2 * cfg::STG);           // this split's two A stages
@@ -195,7 +206,8 @@ void fq_gemm_ksplit_kernel(
                     } else if (mt + 1 < NMT) {
                         an = fql_join(cur[(mt + 1) * 256 + o00], cur[(mt + 1) * 256 + o01]);
                     }
-                    if (h == 0) pt = FQ_MFMA(ac, b0[u], zero);
+                    if (ZPM) pt = FQ_MFMA(ac, zpb, h == 0 ? zero : pt);   // -2^-6 * sum_k a_k in every column
+                    if (h == 0) pt = FQ_MFMA(ac, b0[u], ZPM ? pt : zero);
                     else        pt = FQ_MFMA(ac, b1[u], pt);
 #pragma unroll
                     for (int r = 8 * h; r < 8 * h + 8; ++r) acc[tp][r] = fmaf(sp, pprev[r], acc[tp][r]);
@@ -209,7 +221,7 @@ void fq_gemm_ksplit_kernel(
                     }
                     if (mt == NMT / 2 - 1 && h == 1) q = cfg::WREG ? wraw[u ^ 1][1] : nxt[64];
                     __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x008, ZPM ? 2 : 1, 0);
                     __builtin_amdgcn_sched_group_barrier(0x002, 24, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -233,16 +245,19 @@ void fq_gemm_ksplit_kernel(
 
     // ---- fold: add the K splits' partial tiles through LDS ----
     // Row tiles are handed out in blocks: split kw finishes row tiles kw * OWN .. kw * OWN + OWN - 1 (for its
-    // NW waves' channels).  Half of the row tiles go through LDS at a time: every wave writes its partial
-    // tiles of that half ([wave][tile of the half][4 x 4 registers][64 lanes], 16 bytes per lane and access), and
+    // NW waves' channels).  All row tiles go through LDS at once where they fit, else half of them at a time: every
+    // wave writes its partial tiles of the pass ([wave][tile of the pass][4 x 4 registers][64 lanes], 16 bytes per lane and access), and
     // the waves that own one of them add up the KS partials in the order of the splits (a fixed order: the result
     // is deterministic).
     __builtin_amdgcn_s_waitcnt(FQL_WAIT_VM(0));           // ghost transfers have landed: the stages can be reused
     __syncthreads();
     fq_v16f fin[OWN];
+    const bool owner = kw * OWN < NMT;                    // this wave finishes row tiles kw * OWN ..
+#pragma unroll
+    for (int i = 0; i < OWN; ++i) fin[i] = zero;
     {
         fq_v4f* fold = reinterpret_cast<fq_v4f*>(lds);
-        constexpr int HALF = NMT / 2 > 0 ? NMT / 2 : 1;   // row tiles per pass
+        constexpr int HALF = cfg::HALF;                   // row tiles per pass
         constexpr int PASSES = NMT / HALF;
 #pragma unroll
         for (int pass = 0; pass < PASSES; ++pass) {
@@ -275,13 +290,13 @@ void fq_gemm_ksplit_kernel(
     const int mown = m0 + kw * (32 * OWN);                // first row of this wave's own row tiles
 
     // the first round of zero-point units is requested now: it travels while the slices hand over
-    const int rounds = (ZU + 7) >> 3;
-    fql_issue_z<NMT, FQK_WAVES>(rsZ, lds, wave, lane, m0, M, 0, ZU < 8 ? ZU : 8);
+    const int rounds = ZPM ? 0 : (ZU + 7) >> 3;
+    if (!ZPM) fql_issue_z<NMT, FQK_WAVES>(rsZ, lds, wave, lane, m0, M, 0, ZU < 8 ? ZU : 8);
     const __amdgpu_buffer_rsrc_t rsS = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(gs), 0, (int)(((unsigned)N * (unsigned)G + 3u) & ~3u), 0x00020000);
     const unsigned srow = n_ok ? (unsigned)n * (unsigned)G : FQL_OOB;    // channels past N read zeros
     fql_raw_scales zraw;                                  // the round's scale words, requested a round ahead
-    fql_scales_issue(rsS, srow, n_ok, G, C2, 0, ZU < 8 ? ZU : 8, lane >> 5, zraw);
+    if (!ZPM) fql_scales_issue(rsS, srow, n_ok, G, C2, 0, ZU < 8 ? ZU : 8, lane >> 5, zraw);
 
     // ---- K slices: hand the partial tile over; the workgroup that arrives last adds them up and goes on ----
     // The partial tiles and the counter are written and read with device-scope accesses (the sc1 bit: they go to
@@ -289,7 +304,7 @@ void fq_gemm_ksplit_kernel(
     // acknowledged there (vmcnt = 0) before its workgroup counts itself in: a device-scope fence would do the same
     // by writing back the whole L2, once per workgroup, which cost more than the GEMM.  A tile's partial sums are
     // laid out [slice][wave][own row tile][4 x 4 registers][64 lanes], 16 bytes per lane and access.
-    if (S > 1) {
+    if (!ZPM && S > 1) {
         constexpr int SC1 = 16;                           // cache policy of the buffer builtins: device scope
         constexpr unsigned WAVE_BYTES = (unsigned)OWN * 4096u;
         const __amdgpu_buffer_rsrc_t rsP = __builtin_amdgcn_make_buffer_rsrc(
@@ -338,7 +353,7 @@ void fq_gemm_ksplit_kernel(
     }
 
     // ---- zero point: fin += Z * gscale^T over all groups (fp16 matrix cores), 8 units of Z per round ----
-    {
+    if (!ZPM) {
         constexpr int RT = 32 * NMT;
         const int hl = lane >> 5;
         for (int r = 0; r < rounds; ++r) {
@@ -378,7 +393,7 @@ void fq_gemm_ksplit_kernel(
         char* wcol = tile + (kw * (32 * OWN) + 4 * (lane >> 5)) * cfg::OUT_STRIDE + (nw * 32 + (lane & 31)) * 2;
         const float* oscl = osc + kw * (32 * OWN) + 4 * (lane >> 5);
 #pragma unroll
-        for (int it = 0; it < 4 * OWN; ++it) {            // step it: rows 8 * it + 4 * (lane / 32) + 0..3 of the wave's own rows
+        for (int it = 0; it < (owner ? 4 * OWN : 0); ++it) {   // step it: rows 8 * it + 4 * (lane / 32) + 0..3 of the wave's own rows
             const int i = it >> 2, jj = it & 3;
             const fq_v4f sc4 = *reinterpret_cast<const fq_v4f*>(&oscl[8 * it]);
 #pragma unroll
@@ -410,7 +425,7 @@ void fq_gemm_ksplit_kernel(
     }
     // ragged tile: element-wise, with bounds checks.  (In-place residual: an element is read and written by the
     // same lane, and nobody else touches it.)
-    if (!wave_on || !n_ok) return;
+    if (!wave_on || !n_ok || !owner) return;
 #pragma unroll
     for (int i = 0; i < OWN; ++i) {
 #pragma unroll
@@ -427,21 +442,21 @@ void fq_gemm_ksplit_kernel(
     }
 }
 
-template <int NMT, int NW, int KS>
+template <int NMT, int NW, int KS, bool ZPM = false>
 void fqk_launch(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs, float tscale, uint16_t* Y,
                 int M, int N, int K, const uint16_t* planes, const uint16_t* R, int S, unsigned* counters, float* partials,
                 hipStream_t stream) {
     typedef fqk_cfg<NMT, NW, KS> cfg;
     static fq_device_once attr_once;                      // (one per template instance)
     fq_once_per_device(attr_once, [] {
-        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_ksplit_kernel<NMT, NW, KS>),
+        (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fq_gemm_ksplit_kernel<NMT, NW, KS, ZPM>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, cfg::LDS);
     });
     const int tiles_m = (M + cfg::BM - 1) / cfg::BM, tiles_n = (N + cfg::BN - 1) / cfg::BN;
     const int ntiles = tiles_m * tiles_n;
     const int pm = tiles_m < 4 ? tiles_m : 4;
     const unsigned grid = (unsigned)((ntiles + FQL_XCDS - 1) / FQL_XCDS * FQL_XCDS * S);
-    hipLaunchKernelGGL((fq_gemm_ksplit_kernel<NMT, NW, KS>), dim3(grid), dim3(FQK_THREADS), cfg::LDS, stream,
+    hipLaunchKernelGGL((fq_gemm_ksplit_kernel<NMT, NW, KS, ZPM>), dim3(grid), dim3(FQK_THREADS), cfg::LDS, stream,
                        A, a_scale, wp, gs, tscale, Y, M, N, K, tiles_m, tiles_n, pm, planes, R, S, counters, partials);
 }
 
@@ -500,4 +515,19 @@ void fq_launch_gemm_ksplit(int choice, const uint8_t* A, const float* a_scale, c
     const int S = fq_gemm_ksplit_slices(choice, M, N, K, fq_device_cus());
     if (choice == 1) fqk_launch<8, 4, 2>(A, a_scale, wp, gs, tscale, Y, M, N, K, planes, R, 1, counters, partials, stream);
     else             fqk_launch<4, 2, 4>(A, a_scale, wp, gs, tscale, Y, M, N, K, planes, R, S, counters, partials, stream);
+}
+
+// 16 < M <= 64 without a workspace: 64 x 64 tiles, K quartered, the zero point through the matrix cores.  Measured
+// against the M <= 64 kernel (N = 14336, K = 4096): M = 64 16.2 -> 13.7 us, M = 48 13.3 -> 14.0, M = 33 12.1 -> 13.9 (its
+// time hardly depends on M: 2 us until the first operands arrive, 7.4 us of loop at the rate the weights stream, 1.7 us
+// of fold and epilogue); N = 11008: M = 64 14.9 -> 12.8; N = 4096 (64 tiles for 256 compute units): 11.7 -> 10.9;
+// N = 4096, K = 11008: 25.7 -> 26.5.  So: the top of the range, at least half a round of tiles, K up to 8192.
+bool fq_gemm_ksplit64_serves(int M, int N, int K, int cus) {
+    const int tiles = (N + 63) / 64;
+    return M > FQ_KSPLIT64_MIN_M && M <= 64 && K / FQ_GROUP >= 8 && K <= 8192 && tiles <= cus && 2 * tiles >= cus;
+}
+
+void fq_launch_gemm_ksplit64(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs, float tscale,
+                             uint16_t* Y, int M, int N, int K, const uint16_t* R, hipStream_t stream) {
+    fqk_launch<2, 2, 4, true>(A, a_scale, wp, gs, tscale, Y, M, N, K, nullptr, R, 1, nullptr, nullptr, stream);
 }

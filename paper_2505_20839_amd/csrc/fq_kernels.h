@@ -112,6 +112,13 @@ int fq_gemm_ksplit_choice(int M, int N, int K, int cus);
 // bytes of partial tiles, which follow the arrival counters in the workspace; 1 and 0 when there are none.
 int fq_gemm_ksplit_slices(int choice, int M, int N, int K, int cus);
 size_t fq_gemm_ksplit_partial_bytes(int choice, int M, int N, int K, int cus);
+// The same kernel on 64 x 64 tiles for the top of 16 < M <= 64, which has no workspace (zero point through the matrix cores).
+#ifndef FQ_KSPLIT64_MIN_M
+#define FQ_KSPLIT64_MIN_M 56
+#endif
+bool fq_gemm_ksplit64_serves(int M, int N, int K, int cus);
+void fq_launch_gemm_ksplit64(const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs, float tscale,
+                             uint16_t* Y, int M, int N, int K, const uint16_t* R, hipStream_t stream);
 void fq_launch_gemm_ksplit(int choice, const uint8_t* A, const float* a_scale, const uint8_t* wp, const uint8_t* gs,
                            float tscale, uint16_t* Y, int M, int N, int K, void* workspace, bool prepared,
                            const uint16_t* R, hipStream_t stream);

@@ -214,6 +214,58 @@ def test_k_split_kernel_every_element(fq, shape):
     assert np.array_equal(bf16_bits_from_gpu(Yi), bf16_bits_from_gpu(Ya)), "in place differs"
 
 
+# 56 < M <= 64 with at least half a round of 64 x 64 tiles: the K-split kernel without a workspace (zero point through
+# the matrix cores); ragged last channel tile (8200), K splits of unequal length (K / 128 = 11), every K split a ghost
+# step short of the others (K / 128 = 9)
+KSPLIT64_SHAPES = [(64, 8192, 1024), (57, 16384, 1024), (60, 8200, 1408), (64, 8256, 1152)]
+
+
+@pytest.mark.parametrize("shape", KSPLIT64_SHAPES)
+def test_k_split_kernel_without_workspace_every_element(fq, shape):
+    """Plain GEMM and residual (out of place, in place) on 64 x 64 tiles against the oracle, and against the M <= 64
+    kernel, whose arithmetic it shares (same zero-point instruction, same order inside a group): equal within the FP32
+    summation-order margin."""
+    M, N, K = shape
+    assert _plan(fq, shape)["kernel"] == "ksplit64x64" and fq.fq_w4a8_gemm_workspace_bytes(M, N, K) == 0
+    d = _problem(shape, seed=5 * M + N + K)
+    A, s = fq.fq_quantize_act(to_gpu_bf16(d["X_bf16"]))
+    packed, gs = fq.fq_pack_weights(_gpu(d["q"])), _gpu(d["gscale"])
+    An, sn = A.cpu().numpy(), s.cpu().numpy()
+    Rb = workloads.draw_residual(M, N, scale=4.0, seed=M + N)
+    R = to_gpu_bf16(Rb)
+    try:
+        Yk = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+        Ya = fq.fq_w4a8_gemm_add(A, s, packed, gs, d["w_tscale"], N, R)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_bits_from_gpu(R), Rb)
+        Yi = fq.fq_w4a8_gemm_add(A, s, packed, gs, d["w_tscale"], N, R, out=R)
+        Yk2 = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+        fq.fq_test_force_kernel("small")
+        assert _plan(fq, shape)["kernel"] == "smallm"
+        Ys = fq.fq_w4a8_gemm(A, s, packed, gs, d["w_tscale"], N)
+        torch.cuda.synchronize()
+    finally:
+        fq.fq_test_force_kernel(None)
+    Y, B = oracle.w4a8_gemm(An, sn, d["q"], d["gscale"], d["w_tscale"], want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Yk), Y, B, "k-split 64 x 64 %s" % (shape,))
+    assert np.array_equal(bf16_bits_from_gpu(Yk), bf16_bits_from_gpu(Yk2)), "not deterministic"
+    diff = np.abs(oracle.bf16_bits_to_f64(bf16_bits_from_gpu(Yk)) - oracle.bf16_bits_to_f64(bf16_bits_from_gpu(Ys)))
+    assert np.all(diff <= oracle.bf16_ulp_array(Y) + 1e-4 * B)
+    Yr, Br = oracle.w4a8_gemm_add(An, sn, d["q"], d["gscale"], d["w_tscale"], Rb, want_bound=True)
+    check_gemm(bf16_bits_from_gpu(Ya), Yr, Br, "k-split 64 x 64 + residual %s" % (shape,))
+    assert np.array_equal(bf16_bits_from_gpu(Yi), bf16_bits_from_gpu(Ya)), "in place differs"
+
+
+def test_k_split_kernel_without_workspace_keeps_to_its_shapes(fq):
+    assert _plan(fq, (64, 14336, 4096))["kernel"] == "ksplit64x64"          # the decode sweep's largest batch
+    assert _plan(fq, (56, 14336, 4096))["kernel"] == "smallm"               # below the top of the range
+    assert _plan(fq, (64, 4096, 4096))["kernel"] == "smallm"                # a quarter of a round of tiles
+    assert _plan(fq, (64, 14336, 11008))["kernel"] == "smallm"              # long K
+    assert _plan(fq, (64, 16448, 4096))["kernel"] == "smallm"               # more than one round
+    assert _plan(fq, (64, 8192, 512))["kernel"] == "smallm"                 # fewer than two groups per K split
+    assert _plan(fq, (65, 14336, 4096))["kernel"] == "ksplit128x64"
+
+
 def test_k_split_kernel_zero_activations_return_the_residual(fq):
     for shape in [(300, 264, 1024), (1024, 640, 2048), (700, 1032, 2048)]:
         M, N, K = shape

@@ -6,8 +6,8 @@ import itertools
 from paper_2505_20839_amd import binding
 
 CUS = 256
-MS = [1, 16, 17, 64, 65, 100, 128, 129, 192, 256, 300, 384, 512, 513, 1024, 2048, 8192]
-NS = [32, 64, 96, 200, 512, 1000, 4096, 6144, 11008, 14336, 22016, 28672]
+MS = [1, 16, 17, 56, 57, 64, 65, 100, 128, 129, 192, 256, 300, 384, 512, 513, 1024, 2048, 8192]
+NS = [32, 64, 96, 200, 512, 1000, 4096, 6144, 8192, 11008, 14336, 16384, 16448, 22016, 28672]
 KS = [128, 256, 1024, 1408, 4096, 5120, 8192, 11008, 16384]
 
 
@@ -22,7 +22,11 @@ def test_kernel_choice_follows_m_and_the_tile_count():
         if M <= 16:
             assert p["kernel"] == "small16", (M, N, K)
         elif M <= 64:
-            assert p["kernel"] == "smallm", (M, N, K)
+            tiles64 = -(-N // 64)
+            top = M > 56 and 8 <= K // 128 <= 64 and tiles64 <= CUS <= 2 * tiles64
+            assert p["kernel"] == ("ksplit64x64" if top else "smallm"), (M, N, K)
+            if top:
+                assert p["ksplit_tiles"] == tiles64 and p["ksplit_slices"] == 1
         else:
             tiles = -(-M // 128) * -(-N // 64)
             rounds = 2 if (M <= 128 and K // 128 >= 40) else 1
