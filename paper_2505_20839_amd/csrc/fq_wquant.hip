@@ -40,12 +40,16 @@ __device__ __forceinline__ int fqw_log2_over_7(unsigned bits) {
 // waves 64; FQW_CAS_UNROLL such loads are in flight per lane.  FP64 sums, combined in a fixed order: the result
 // does not depend on timing.
 #define FQW_CAS_UNROLL 16
-#define FQW_CAS_ROWS 64
-__global__ __launch_bounds__(16 * FQW_CAS_ROWS) void fq_cas_scales_kernel(const uint16_t* __restrict__ W, float target,
+#define FQW_CAS_THREADS 1024
+// LPR lanes per row (2 channels each): 16 -> 32 channels per workgroup.  (8 -> 16 channels and twice the workgroups
+// is slower, 57 against 35 us on 11008 x 4096: four workgroups then fetch every 128-byte line.)
+template <int LPR>
+__global__ __launch_bounds__(FQW_CAS_THREADS) void fq_cas_scales_kernel(const uint16_t* __restrict__ W, float target,
                                                             float* __restrict__ lambda, int N, int K) {
-    __shared__ double part[FQW_CAS_ROWS][32];
-    const int sub = threadIdx.x >> 4;                     // which of the 64 rows of a pass
-    const int k = blockIdx.x * 32 + 2 * (threadIdx.x & 15);
+    constexpr int FQW_CAS_ROWS = FQW_CAS_THREADS / LPR, CH = 2 * LPR;
+    __shared__ double part[FQW_CAS_ROWS][CH];
+    const int sub = threadIdx.x / LPR;                    // which of the rows of a pass
+    const int k = blockIdx.x * CH + 2 * (threadIdx.x % LPR);
     const bool two = k + 1 < K, one = k < K;              // K may be odd: the last channel then loads 2 bytes
     double s0 = 0.0, s1 = 0.0;
     for (int n0 = sub; n0 < N; n0 += FQW_CAS_ROWS * FQW_CAS_UNROLL) {
@@ -67,14 +71,67 @@ __global__ __launch_bounds__(16 * FQW_CAS_ROWS) void fq_cas_scales_kernel(const 
             s1 += (double)fabsf(fqw_bf16((unsigned short)(w[u] >> 16)));
         }
     }
-    part[sub][2 * (threadIdx.x & 15)] = s0;
-    part[sub][2 * (threadIdx.x & 15) + 1] = s1;
+    part[sub][2 * (threadIdx.x % LPR)] = s0;
+    part[sub][2 * (threadIdx.x % LPR) + 1] = s1;
     __syncthreads();
-    if (threadIdx.x < 32 && blockIdx.x * 32 + (int)threadIdx.x < K) {
+    if (threadIdx.x < CH && blockIdx.x * CH + (int)threadIdx.x < K) {
+        double t = 0.0;
+#pragma unroll 16
+        for (int r = 0; r < FQW_CAS_ROWS; ++r) t += part[r][threadIdx.x];
+        lambda[blockIdx.x * CH + threadIdx.x] =
+            t == 0.0 ? 1.0f : (float)((double)target / (t / (double)N));            // an all-zero channel keeps 1
+    }
+}
+
+// The same for rows in 16-byte steps (K a multiple of 8, W 16-byte aligned), 64 channels per workgroup: a workgroup
+// then reads whole 128-byte lines (with 32 channels two workgroups fetch each line, and the memory side moved the
+// matrix twice: 35 us; with 16 channels four times: 57 us), 8 lanes x 16 bytes per row, 8 rows per wave-level load,
+// and keeps FQW_CASW_UNROLL of them in flight per lane -- with K / 64 workgroups (64 for K = 4096) it is the bytes in
+// flight per workgroup that set the rate.  The 8 rows of a wave are added by shuffles, the 16 waves through LDS, both
+// in a fixed order.
+#define FQW_CASW_UNROLL 8
+#define FQW_CASW_ROWS 128
+__global__ __launch_bounds__(8 * FQW_CASW_ROWS) void fq_cas_scales_wide_kernel(const uint16_t* __restrict__ W, float target,
+                                                                              float* __restrict__ lambda, int N, int K) {
+    __shared__ double part[16][64];
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int sub = threadIdx.x >> 3;                     // which of the 128 rows of a pass
+    const int k = blockIdx.x * 64 + 8 * (lane & 7);
+    const bool on = k < K;                                // (K % 8 == 0: the 8 channels are inside or outside together)
+    double s[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s[i] = 0.0;
+    for (int n0 = sub; n0 < N; n0 += FQW_CASW_ROWS * FQW_CASW_UNROLL) {
+        fq_v4i w[FQW_CASW_UNROLL];
+#pragma unroll
+        for (int u = 0; u < FQW_CASW_UNROLL; ++u) {
+            const int n = n0 + FQW_CASW_ROWS * u;
+            w[u] = (fq_v4i){0, 0, 0, 0};
+            if (n < N && on) w[u] = __builtin_nontemporal_load(reinterpret_cast<const fq_v4i*>(W + (size_t)n * K + k));
+        }
+#pragma unroll
+        for (int u = 0; u < FQW_CASW_UNROLL; ++u)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const unsigned word = (unsigned)w[u][i];
+                s[2 * i] += (double)__uint_as_float((word << 16) & 0x7FFF0000u);     // |bf16| as FP32, exact in FP64
+                s[2 * i + 1] += (double)__uint_as_float(word & 0x7FFF0000u);
+            }
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+        for (int m = 8; m < 64; m <<= 1) s[i] += __shfl_xor(s[i], m, 64);
+    if (lane < 8) {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part[wave][8 * lane + i] = s[i];
+    }
+    __syncthreads();
+    if (threadIdx.x < 64 && blockIdx.x * 64 + (int)threadIdx.x < K) {
         double t = 0.0;
 #pragma unroll
-        for (int r = 0; r < FQW_CAS_ROWS; ++r) t += part[r][threadIdx.x];
-        lambda[blockIdx.x * 32 + threadIdx.x] =
+        for (int r = 0; r < 16; ++r) t += part[r][threadIdx.x];
+        lambda[blockIdx.x * 64 + threadIdx.x] =
             t == 0.0 ? 1.0f : (float)((double)target / (t / (double)N));            // an all-zero channel keeps 1
     }
 }
@@ -109,7 +166,9 @@ __device__ __forceinline__ int fqw_pts_resolve(unsigned vmin, unsigned vmax) {
 // Thread t works on the 16-byte chunk (8 weights) t % (K / 8) of the rows t / (K / 8), + rows_par, ...: its 8
 // input channels never change, so their lambda sit in registers, and neighbouring threads read neighbouring
 // chunks.  FQW_PTS_UNROLL rows are in flight per thread.
+#ifndef FQW_PTS_UNROLL
 #define FQW_PTS_UNROLL 4
+#endif
 __global__ __launch_bounds__(256) void fq_pts_stats_kernel(const uint16_t* __restrict__ W,
                                                            const float* __restrict__ lambda,
                                                            unsigned* __restrict__ stats,
@@ -228,7 +287,17 @@ __global__ __launch_bounds__(256) void fq_quantize_weights_kernel(const uint16_t
 }
 
 void fq_launch_cas_scales(const uint16_t* W, float target, float* lambda, int N, int K, hipStream_t stream) {
-    hipLaunchKernelGGL(fq_cas_scales_kernel, dim3((unsigned)((K + 31) / 32)), dim3(16 * FQW_CAS_ROWS), 0, stream, W, target, lambda, N, K);
+#ifndef FQW_CAS_LPR
+#define FQW_CAS_LPR 16
+#endif
+    // whole lines per workgroup where K / 64 workgroups are enough to cover half the chip (measured, N x K: 4096 x 11008
+    // 34.3 -> 19.1 us; 11008 x 4096, 64 workgroups: 35.1 -> 42.3, where the conversions to FP64 bound a compute unit)
+    if ((K % 8) == 0 && (reinterpret_cast<uintptr_t>(W) % 16) == 0 && 2 * ((K + 63) / 64) >= fq_device_cus()) {
+        hipLaunchKernelGGL(fq_cas_scales_wide_kernel, dim3((unsigned)((K + 63) / 64)), dim3(8 * FQW_CASW_ROWS), 0, stream, W, target, lambda, N, K);
+        return;
+    }
+    constexpr int CH = 2 * FQW_CAS_LPR;
+    hipLaunchKernelGGL(fq_cas_scales_kernel<FQW_CAS_LPR>, dim3((unsigned)((K + CH - 1) / CH)), dim3(FQW_CAS_THREADS), 0, stream, W, target, lambda, N, K);
 }
 
 void fq_launch_pts_exponent(const uint16_t* W, const float* lambda, int* n_out, int N, int K, hipStream_t stream) {

@@ -27,7 +27,8 @@ def _bits(x):
     return workloads.f32_to_bf16_bits(np.asarray(x, np.float32))
 
 
-@pytest.mark.parametrize("N,K,seed", [(40, 128, 0), (300, 1000, 1), (7, 64, 2), (1024, 512, 3)])
+# (K >= 8192 with whole 16-byte steps: the kernel of 64-channel blocks; 8200 leaves its last block 8 channels)
+@pytest.mark.parametrize("N,K,seed", [(40, 128, 0), (300, 1000, 1), (7, 64, 2), (1024, 512, 3), (70, 8192, 4), (300, 8200, 5)])
 def test_cas_scales_match_oracle(fq, N, K, seed):
     Wb = workloads.draw_weights(N, K, seed=seed, channel_spread=1.0)
     Wb[:, K // 3] = 0                                          # an all-zero channel keeps lambda = 1
