@@ -456,15 +456,28 @@ void fq_gemm_smallm_kernel(
     const __amdgpu_buffer_rsrc_t rsG = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<uint8_t*>(gs), 0, (int)((unsigned)N * (unsigned)G), 0x00020000);
     // the scale bytes of this workgroup: (channel c, group g) at gs[(n_first + c) * G + g]; up to 8 per thread now,
-    // the rest (K > 8192) after the ring has been requested
+    // the rest (K > 8192) after the ring has been requested.  Where rows of scales are whole words (K a multiple of
+    // 512) a thread fetches words, two instead of eight loads ahead of the weights in the queue: a load costs the
+    // address path the same whatever its width.
     const int nsc = FQSM_MAXCOLS * G;
+    const bool scw = (G & 3) == 0;
     unsigned scb[8];
+    if (scw) {
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
-        const int idx = threadIdx.x + x * FQS16_THREADS;  // idx = c * G + g
-        const int c = idx / G;
-        const bool on = idx < nsc && c < cols && n_first + c < N;
-        scb[x] = __builtin_amdgcn_raw_buffer_load_b8(rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+        for (int x = 0; x < 2; ++x) {
+            const int idx = 4 * (threadIdx.x + x * FQS16_THREADS);    // idx = c * G + g
+            const int c = idx / G;
+            const bool on = idx < nsc && c < cols && n_first + c < N;
+            scb[x] = __builtin_amdgcn_raw_buffer_load_b32(rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int idx = threadIdx.x + x * FQS16_THREADS;
+            const int c = idx / G;
+            const bool on = idx < nsc && c < cols && n_first + c < N;
+            scb[x] = __builtin_amdgcn_raw_buffer_load_b8(rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+        }
     }
     // per sub-tile: byte offset of this lane's chunk in group 0 of its packed block
     unsigned woff[NSUB];
@@ -504,17 +517,36 @@ void fq_gemm_smallm_kernel(
     for (int i = 0; i < BATCH; ++i) ring.issue(i, rsA, rsW, aoff, woff, g_begin + i, g_end);
     __builtin_amdgcn_sched_barrier(0);                    // all requests go out before anything else
     // scale table: transposed to [group][channel] so that a lane's sub-tiles are 16 bytes apart
+    if (scw) {
 #pragma unroll
-    for (int x = 0; x < 8; ++x) {
-        const int idx = threadIdx.x + x * FQS16_THREADS;
-        const int c = idx / G, g = idx - c * G;
-        if (idx < nsc) smem[g * FQSM_MAXCOLS + c] = (uint8_t)scb[x];
-    }
-    for (int idx = threadIdx.x + 8 * FQS16_THREADS; idx < nsc; idx += FQS16_THREADS) {
-        const int c = idx / G, g = idx - c * G;
-        const bool on = c < cols && n_first + c < N;
-        smem[g * FQSM_MAXCOLS + c] = (uint8_t)__builtin_amdgcn_raw_buffer_load_b8(
-            rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+        for (int x = 0; x < 2; ++x) {
+            const int idx = 4 * (threadIdx.x + x * FQS16_THREADS);
+            const int c = idx / G, g = idx - c * G;       // (G % 4 == 0: the word's four groups belong to one channel)
+            if (idx < nsc) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) smem[(g + e) * FQSM_MAXCOLS + c] = (uint8_t)(scb[x] >> (8 * e));
+            }
+        }
+        for (int idx = 4 * (threadIdx.x + 2 * FQS16_THREADS); idx < nsc; idx += 4 * FQS16_THREADS) {
+            const int c = idx / G, g = idx - c * G;
+            const bool on = c < cols && n_first + c < N;
+            const unsigned w = __builtin_amdgcn_raw_buffer_load_b32(rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) smem[(g + e) * FQSM_MAXCOLS + c] = (uint8_t)(w >> (8 * e));
+        }
+    } else {
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const int idx = threadIdx.x + x * FQS16_THREADS;
+            const int c = idx / G, g = idx - c * G;
+            if (idx < nsc) smem[g * FQSM_MAXCOLS + c] = (uint8_t)scb[x];
+        }
+        for (int idx = threadIdx.x + 8 * FQS16_THREADS; idx < nsc; idx += FQS16_THREADS) {
+            const int c = idx / G, g = idx - c * G;
+            const bool on = c < cols && n_first + c < N;
+            smem[g * FQSM_MAXCOLS + c] = (uint8_t)__builtin_amdgcn_raw_buffer_load_b8(
+                rsG, on ? (unsigned)(n_first * G + idx) : FQS16_OOB, 0, 0);
+        }
     }
     __syncthreads();
     const uint8_t* sc = smem + r16;
