@@ -419,7 +419,8 @@ def main() -> int:
         wb = wd.N * wd.K / 2 + wd.N * (wd.K // 128)
         g, g_best, rs = med(rd["gemm_s"]), min(rd["gemm_s"]), med(rd["read_s"])
         torch.cuda.empty_cache()
-        return {"workload": wl, "M": wd.M, "kernel_us": g * 1e6, "kernel_us_best": g_best * 1e6,
+        return {"workload": wl, "M": wd.M, "kernel": fq.fq_w4a8_gemm_plan(wd.M, wd.N, wd.K)["kernel"],
+                "kernel_us": g * 1e6, "kernel_us_best": g_best * 1e6,
                 "step_us": med(rd["step_s"]) * 1e6, "weight_GBps": wb / g / 1e9, "frac_hbm": wb / g / 1e9 / PEAK_HBM_GBPS,
                 "frac_hbm_best": wb / g_best / 1e9 / PEAK_HBM_GBPS, "stream_read_us": rs * 1e6,
                 "stream_read_GBps": wb / rs / 1e9, "frac_of_measured_read": rs / g,
