@@ -66,7 +66,9 @@ def test_scores_match_the_oracle(fq, H, R, T):
 
 # (T a multiple of 16 with the padded stride below: the kernel of 16-byte steps; 144 and 1040 end inside a 128-token group)
 OUTPUT_SHAPES = [(1, 1, 1), (2, 4, 100), (3, 16, 256), (2, 17, 300), (1, 32, 513), (8, 4, 4096), (5, 9, 70), (2, 20, 144),
-                 (3, 4, 1040), (1, 1, 16), (40, 16, 272)]
+                 (3, 4, 1040), (1, 1, 16), (40, 16, 272),
+                 # heads enough for 2 and for 4 dimension tiles per workgroup on a 256-unit device (1 below 64 heads)
+                 (70, 4, 144), (130, 3, 272), (260, 20, 48)]
 
 
 @pytest.mark.parametrize("H,R,T", OUTPUT_SHAPES)
