@@ -132,7 +132,10 @@ def test_quantize_all_finite_bf16_values_and_zero_row(fq):
 SMALL_SHAPES = [(16, 256, 512), (1, 32, 128), (33, 100, 384), (64, 96, 1408), (7, 31, 256),
                 (8, 100, 1408), (16, 64, 14336), (16, 4120, 512), (3, 9000, 256), (12, 14336, 384),
                 # ring depths 12 and 8 with and without a second round, scale rows that are not word-aligned
-                (5, 200, 11008), (8, 8192, 5120), (4, 8192, 11008), (16, 300, 1664)]
+                (5, 200, 11008), (8, 8192, 5120), (4, 8192, 11008), (16, 300, 1664),
+                # 16 < M <= 64 with rows of scales that are whole words (table fetched as words), also beyond the two words a
+                # thread fetches up front (K = 16384), ragged channel counts
+                (40, 300, 1024), (64, 136, 16384), (17, 8200, 512), (48, 72, 4096)]
 # large: ragged M and N, one group only, a second half tile without rows, several zero-point rounds
 LARGE_SHAPES = [(16, 256, 512), (300, 200, 640), (257, 513, 384), (512, 256, 1408), (65, 33, 128),
                 (129, 136, 256), (130, 64, 16384), (700, 1100, 256)]
