@@ -566,7 +566,9 @@ void fqk_launch_output_dt(int dt, const uint8_t* P, const float* p_scale, const 
 void fq_launch_kv4_output(const uint8_t* P, const float* p_scale, const uint8_t* vp, const uint8_t* vs, uint16_t* O,
                           int H, int R, int T, int ldp, hipStream_t stream) {
     const uintptr_t both = reinterpret_cast<uintptr_t>(P) | reinterpret_cast<uintptr_t>(vs) | (uintptr_t)T | (uintptr_t)ldp;
-    const int mode = (both % 16) == 0 ? 2 : (both % 8) == 0 ? 1 : 0;
+    // (the kernel of 16-byte steps addresses a head's probability rows through 32-bit buffer offsets)
+    const bool rows32 = (unsigned long long)R * (unsigned long long)ldp < 0xFFFFFF00ull;
+    const int mode = ((both % 16) == 0 && rows32) ? 2 : (both % 8) == 0 ? 1 : 0;
     // dimension tiles per workgroup: the most that still give `fill` workgroups per compute unit
     const int cus = fq_device_cus();
     int dt = mode == 2 ? FQK_O_WIDE_MAXDT : 8;
