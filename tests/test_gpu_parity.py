@@ -483,16 +483,19 @@ def test_mid_m_configs_full_size(fq, name):
     _full_config(fq, name, range(workloads.WORKLOADS[name].M))
 
 
-@pytest.mark.parametrize("shape", [(300, 512, 1024), (128, 256, 4096)])
+@pytest.mark.parametrize("shape", [(300, 512, 1024), (128, 256, 4096), (64, 8192, 1024)])
 def test_ws_entry_points_replay_in_a_hip_graph(fq, shape):
     """The explicit-workspace entry points allocate nothing and keep no state, so a captured graph of
     quantiser + GEMM (plain, with residual, fused gate/up, fused gate/up with quantised output) can be replayed:
     three replays on fresh inputs, eager work and synchronisations between them, each replay equal to the eager
     result bit for bit.  The second shape takes the K-split kernel with four workgroups per tile, whose arrival
-    counters must be back at zero after every GEMM of every replay."""
+    counters must be back at zero after every GEMM of every replay; the third has no workspace at all (the K-split kernel's
+    64 x 64 tiles for the plain and the residual form, the M <= 64 kernel for the fused gate/up layer)."""
     M, N, K = shape
     if shape[0] == 128:
         assert fq.fq_w4a8_gemm_plan(M, N, K)["ksplit_slices"] == 4
+    if shape[0] == 64:
+        assert fq.fq_w4a8_gemm_plan(M, N, K)["kernel"] == "ksplit64x64" and fq.fq_w4a8_gemm_workspace_bytes(M, N, K) == 0
     d = workloads.draw(M, N, K, seed=91, gs_lo=0.01, gs_hi=0.1, outlier_frac=0.01)
     packed = fq.fq_pack_weights(_gpu(d["q"]))
     gs = _gpu(d["gscale"])
